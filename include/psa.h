@@ -1,0 +1,158 @@
+/*
+ * psa.h -- C ABI of the MI355X (gfx950) Progressive Sparse Attention decode library.
+ *
+ * The calls follow the paper's statement of the problem (arxiv 2503.00392): a decode-step query
+ * attends a paged KV cache, blocks are scored from small per-block key metadata, ranked, and pulled
+ * in that order into an exact attention accumulation until the accumulated attention weight passes
+ * a threshold (Algorithm 1, Sec. 3.2).
+ *
+ * Conventions common to every call
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".
+ *   - The caller owns every buffer, the workspace included.  The library allocates no device
+ *     memory and keeps no state between calls; calls on distinct streams with distinct workspaces
+ *     may overlap, calls sharing a workspace must be ordered by the stream.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Calls validate their arguments on the host, enqueue kernels and return.  No call
+ *     synchronises the stream or copies to the host, except psa_read_device_error.  Outputs are
+ *     valid once the caller has synchronised the stream.
+ *   - Errors are return codes.  On any code other than PSA_OK nothing has been enqueued.
+ *     What the host can see is checked there (null required pointer, shapes, threshold outside
+ *     [0,1] or NaN, check_granularity < 1, workspace too small).  What only the device can see
+ *     (a block-table entry outside [0,num_pages), a context longer than max_blocks_per_seq pages,
+ *     a negative context length, a bounded in-kernel wait that ran out) is clamped by the
+ *     kernels, which set a sticky bit in the workspace that psa_read_device_error returns.
+ *   - Element type of Q, K, V and metadata: IEEE binary16 or bfloat16, 2 bytes.
+ *   - Supported shapes: head_dim == 128, page_size == 16, num_q_heads / num_kv_heads in
+ *     {1, 2, 4, 8}, max_blocks_per_seq <= 8192 for psa_decode_attention (128K tokens).
+ *     Anything else returns PSA_ERR_UNSUPPORTED.
+ */
+#ifndef PSA_H
+#define PSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PSA_OK = 0,
+    PSA_ERR_INVALID_ARG = 1,
+    PSA_ERR_UNSUPPORTED = 2,
+    PSA_ERR_WORKSPACE_TOO_SMALL = 3,
+    PSA_ERR_LAUNCH = 4
+} psa_status;
+
+typedef enum { PSA_F16 = 0, PSA_BF16 = 1 } psa_dtype;
+
+/* Bits of the sticky device error word (psa_read_device_error). */
+enum {
+    PSA_DEVERR_PAGE_RANGE = 1,   /* block-table entry outside [0, num_pages): page 0 was used   */
+    PSA_DEVERR_CTX_RANGE = 2,    /* ctx_len < 0 or > 16*max_blocks_per_seq: clamped             */
+    PSA_DEVERR_WAIT_EXPIRED = 4  /* a bounded in-kernel wait ran out: results are not reliable  */
+};
+
+/* Shapes and layout of ONE layer's paged KV cache (PagedAttention layout, Sec. 2.1 "KV Cache"). */
+typedef struct {
+    int32_t batch;              /* decode requests, one query token each                          */
+    int32_t num_q_heads;        /* Hq                                                             */
+    int32_t num_kv_heads;       /* Hkv; Hq % Hkv == 0; G = Hq / Hkv query heads share a KV head   */
+    int32_t head_dim;           /* d, must be 128                                                 */
+    int32_t page_size;          /* tokens per KV block, must be 16                                */
+    int32_t num_pages;          /* physical pages in each pool                                    */
+    int32_t max_blocks_per_seq; /* row stride of block_table                                      */
+    int32_t dtype;              /* psa_dtype of Q, K, V and metadata                              */
+    const void *k_pool;         /* [num_pages][num_kv_heads][page_size][head_dim]                 */
+    const void *v_pool;         /* same layout                                                    */
+    const int32_t *block_table; /* [batch][max_blocks_per_seq]: logical block -> physical page    */
+    const int32_t *ctx_lens;    /* [batch]: tokens of each request; need not be a multiple of 16  */
+} psa_kv_desc;
+
+/* Tuning knobs of psa_decode_attention; all zero = library defaults.  They change how much is read
+ * speculatively and how work is cut, never the result. */
+typedef struct {
+    int32_t chunk_blocks;   /* ranked blocks per work item, 8..64 (default 32)                    */
+    int32_t window_chunks;  /* work items of one (request, KV head) allowed past the last resolved
+                               one (default: from the number of streams)                          */
+    int32_t spin_limit;     /* polls before a bounded in-kernel wait gives up (default 1<<22)     */
+    int32_t reserved;
+} psa_tuning;
+
+/* Bytes of workspace psa_decode_attention needs for this descriptor and tuning (NULL = defaults);
+ * 0 on an invalid or unsupported descriptor. */
+size_t psa_decode_workspace_bytes(const psa_kv_desc *desc, const psa_tuning *tuning);
+
+/* Bytes of workspace psa_dense_attention needs for this descriptor (0 on an invalid one). */
+size_t psa_dense_workspace_bytes(const psa_kv_desc *desc);
+
+/*
+ * Block metadata (Sec. 2.2 "KV Cache Selection": per-block vectors derived from the block's keys;
+ * here the bounding cuboid, i.e. per-channel minimum and maximum; Sec. 3.1: created when a block
+ * reaches capacity and kept in GPU memory).
+ *   meta       out [num_pages][num_kv_heads][2][head_dim], desc->dtype; [..][0] = min, [..][1] = max.
+ *              Exact: each entry is one of the block's own key bit patterns (-0 orders below +0).
+ *   page_fill  [num_pages] valid tokens of each page (0..16), or NULL = every page is full.
+ *              A page with 0 valid tokens gets min = max = +0.
+ *   page_list  [num_listed] physical pages to (re)build, or NULL = all num_pages pages.  This is
+ *              the per-step form: the pages that filled since the last decode step.
+ * Only desc->k_pool, num_pages, num_kv_heads, head_dim, page_size and dtype are read.
+ */
+psa_status psa_build_block_metadata(const psa_kv_desc *desc, void *meta, const int32_t *page_fill,
+                                    const int32_t *page_list, int32_t num_listed, void *stream);
+
+/*
+ * One decode step of Progressive Sparse Attention for one layer (Algorithm 1; Sec. 3.2 for the
+ * microbatch size and for the batched form in which every query stops on its own).
+ * Per (request, KV head): score every block from its metadata (line 5: the largest scaled logit
+ * q.k/sqrt(d) any key inside [min,max] could give, maximised over the G query heads of the group),
+ * rank the blocks (line 6; ties to the smaller logical block), then for each query head walk the
+ * ranking, merging exact softmax attention block by block (lines 10-12) and stopping at the first
+ * n that is a multiple of check_granularity (or the last block) where
+ *   P_acc = AS_acc / (AS_acc + AS_min * N_left) > threshold            (lines 13-18).
+ *   q            [batch][num_q_heads][head_dim], desc->dtype
+ *   meta         as written by psa_build_block_metadata (pages' valid-token counts included)
+ *   threshold    epsilon in [0,1]; 1 never stops early, so the result is dense attention
+ *   check_granularity  m >= 1 (Sec. 3.2 "microbatch")
+ *   out          [batch][num_q_heads][head_dim] float32
+ *   n_selected   [batch][num_q_heads] blocks attended by that query head (a prefix of the ranking)
+ *   mass_est     [batch][num_q_heads] float32, P_acc at the stop (1 if every block was used)
+ *   blocks_read  [batch][num_kv_heads] max of n_selected over the group; may be NULL
+ *   order_out    [batch][num_kv_heads][max_blocks_per_seq] the ranking (logical blocks, -1 beyond
+ *                the request's block count); may be NULL
+ *   scores_out   [batch][num_kv_heads][max_blocks_per_seq] float32 criticality scores by logical
+ *                block (untouched beyond the block count); may be NULL
+ *   traffic_out  [batch][num_kv_heads][2] K blocks and V blocks actually loaded (K is read a
+ *                bounded window ahead of the stop); may be NULL
+ *   tuning       NULL = defaults
+ * A request with ctx_len 0 gets out = 0, n_selected = 0, mass_est = 0.
+ */
+psa_status psa_decode_attention(const psa_kv_desc *desc, const void *q, const void *meta,
+                                float threshold, int32_t check_granularity, float *out,
+                                int32_t *n_selected, float *mass_est, int32_t *blocks_read,
+                                int32_t *order_out, float *scores_out, int32_t *traffic_out,
+                                const psa_tuning *tuning, void *workspace, size_t workspace_bytes,
+                                void *stream);
+
+/*
+ * Dense control: exact softmax attention over every block of the same paged layout
+ * (Sec. 2.1: S = QK^T/sqrt(d), P = softmax(S), O = PV).
+ *   out  [batch][num_q_heads][head_dim] float32
+ *   lse  [batch][num_q_heads] float32 natural-log sum of exponentiated scaled logits; may be NULL
+ */
+psa_status psa_dense_attention(const psa_kv_desc *desc, const void *q, float *out, float *lse,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Copies the sticky device error word of a workspace to the host and clears nothing.
+ * Synchronises `stream`.  host_flags: host pointer, receives an OR of PSA_DEVERR_* bits.
+ */
+psa_status psa_read_device_error(const void *workspace, int32_t *host_flags, void *stream);
+
+/* Static, human-readable name of a status code. */
+const char *psa_status_string(psa_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSA_H */

@@ -1,0 +1,225 @@
+"""ctypes binding of libpsa.so: the same entry points as include/psa.h, nothing computed here.
+
+torch is used for device memory and streams only.  If the library has not been built the import of
+this module still works (so that CPU-only tooling can inspect it) but every call raises: there is
+no fallback path of any kind.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpsa.so")
+
+PSA_F16, PSA_BF16 = 0, 1
+PSA_OK = 0
+DEVERR_PAGE_RANGE, DEVERR_CTX_RANGE, DEVERR_WAIT_EXPIRED = 1, 2, 4
+
+
+class PsaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+class _KvDesc(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("page_size", C.c_int32), ("num_pages", C.c_int32),
+                ("max_blocks_per_seq", C.c_int32), ("dtype", C.c_int32),
+                ("k_pool", C.c_void_p), ("v_pool", C.c_void_p),
+                ("block_table", C.c_void_p), ("ctx_lens", C.c_void_p)]
+
+
+class _Tuning(C.Structure):
+    _fields_ = [("chunk_blocks", C.c_int32), ("window_chunks", C.c_int32),
+                ("spin_limit", C.c_int32), ("reserved", C.c_int32)]
+
+
+@dataclass
+class Tuning:
+    chunk_blocks: int = 0
+    window_chunks: int = 0
+    spin_limit: int = 0
+
+    def c(self) -> _Tuning:
+        return _Tuning(self.chunk_blocks, self.window_chunks, self.spin_limit, 0)
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> C.CDLL:
+    """Loads libpsa.so; raises if it has not been built (python -m paper_2503_00392_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2503_00392_amd.build`; "
+                "there is no fallback implementation")
+        lib = C.CDLL(_LIB_PATH)
+        vp, i32, sz, f32 = C.c_void_p, C.c_int32, C.c_size_t, C.c_float
+        lib.psa_status_string.restype = C.c_char_p
+        lib.psa_status_string.argtypes = [C.c_int]
+        lib.psa_decode_workspace_bytes.restype = sz
+        lib.psa_decode_workspace_bytes.argtypes = [C.POINTER(_KvDesc), C.POINTER(_Tuning)]
+        lib.psa_dense_workspace_bytes.restype = sz
+        lib.psa_dense_workspace_bytes.argtypes = [C.POINTER(_KvDesc)]
+        lib.psa_build_block_metadata.restype = C.c_int
+        lib.psa_build_block_metadata.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, i32, vp]
+        lib.psa_decode_attention.restype = C.c_int
+        lib.psa_decode_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, f32, i32, vp, vp, vp, vp, vp, vp,
+                                             vp, C.POINTER(_Tuning), vp, sz, vp]
+        lib.psa_dense_attention.restype = C.c_int
+        lib.psa_dense_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, vp, sz, vp]
+        lib.psa_read_device_error.restype = C.c_int
+        lib.psa_read_device_error.argtypes = [vp, C.POINTER(C.c_int32), vp]
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load_library().psa_status_string(int(status)).decode()
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream
+
+
+def _dtype_code(dt: torch.dtype) -> int:
+    if dt == torch.float16:
+        return PSA_F16
+    if dt == torch.bfloat16:
+        return PSA_BF16
+    raise TypeError(f"unsupported element type {dt}")
+
+
+@dataclass
+class KvCache:
+    """One layer's paged KV cache and its tables (device tensors, see psa_kv_desc)."""
+    k_pool: torch.Tensor       # [P][Hkv][16][128] fp16 / bf16
+    v_pool: torch.Tensor
+    block_table: torch.Tensor  # int32 [B][max_blocks]
+    ctx_lens: torch.Tensor     # int32 [B]
+    num_q_heads: int
+
+    def desc(self) -> _KvDesc:
+        P, H, T, D = self.k_pool.shape
+        assert self.k_pool.is_contiguous() and self.v_pool.is_contiguous()
+        assert self.block_table.is_contiguous() and self.block_table.dtype == torch.int32
+        assert self.ctx_lens.dtype == torch.int32
+        return _KvDesc(self.block_table.shape[0], self.num_q_heads, H, D, T, P,
+                       self.block_table.shape[1], _dtype_code(self.k_pool.dtype),
+                       _ptr(self.k_pool), _ptr(self.v_pool), _ptr(self.block_table),
+                       _ptr(self.ctx_lens))
+
+
+def _check(status: int, where: str) -> None:
+    if status != PSA_OK:
+        raise PsaError(status, where)
+
+
+def decode_workspace_bytes(kv: KvCache, tuning: Tuning | None = None) -> int:
+    d = kv.desc()
+    t = tuning.c() if tuning else None
+    return int(load_library().psa_decode_workspace_bytes(C.byref(d), C.byref(t) if t else None))
+
+
+def dense_workspace_bytes(kv: KvCache) -> int:
+    d = kv.desc()
+    return int(load_library().psa_dense_workspace_bytes(C.byref(d)))
+
+
+def build_block_metadata(kv: KvCache, meta: torch.Tensor | None = None, page_fill=None,
+                         page_list=None, stream=None) -> torch.Tensor:
+    """psa_build_block_metadata; allocates `meta` ([P][Hkv][2][128], the pool's type) if not given."""
+    P, H, T, D = kv.k_pool.shape
+    if meta is None:
+        meta = torch.empty((P, H, 2, D), dtype=kv.k_pool.dtype, device=kv.k_pool.device)
+    d = kv.desc()
+    n_listed = 0 if page_list is None else int(page_list.numel())
+    st = load_library().psa_build_block_metadata(C.byref(d), _ptr(meta), _ptr(page_fill), _ptr(page_list),
+                                                 n_listed, _stream(stream))
+    _check(st, "psa_build_block_metadata")
+    return meta
+
+
+@dataclass
+class DecodeOutput:
+    out: torch.Tensor          # float32 [B][Hq][128]
+    n_selected: torch.Tensor   # int32 [B][Hq]
+    mass_est: torch.Tensor     # float32 [B][Hq]
+    blocks_read: torch.Tensor  # int32 [B][Hkv]
+    order: torch.Tensor | None     # int32 [B][Hkv][max_blocks]
+    scores: torch.Tensor | None    # float32 [B][Hkv][max_blocks]
+    traffic: torch.Tensor | None   # int32 [B][Hkv][2]: K blocks, V blocks loaded
+
+
+def decode_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, threshold: float,
+                     check_granularity: int = 1, *, workspace: torch.Tensor | None = None,
+                     outputs: DecodeOutput | None = None, want_order: bool = False,
+                     want_scores: bool = False, want_traffic: bool = False,
+                     tuning: Tuning | None = None, stream=None) -> DecodeOutput:
+    """psa_decode_attention.  Pass `workspace` and `outputs` to make the call allocation-free."""
+    d = kv.desc()
+    dev = q.device
+    B, Hq, H, MB = d.batch, d.num_q_heads, d.num_kv_heads, d.max_blocks_per_seq
+    t = tuning.c() if tuning else None
+    if workspace is None:
+        workspace = torch.empty(max(decode_workspace_bytes(kv, tuning), 256), dtype=torch.uint8, device=dev)
+    if outputs is None:
+        outputs = DecodeOutput(
+            torch.empty((B, Hq, 128), dtype=torch.float32, device=dev),
+            torch.empty((B, Hq), dtype=torch.int32, device=dev),
+            torch.empty((B, Hq), dtype=torch.float32, device=dev),
+            torch.empty((B, H), dtype=torch.int32, device=dev),
+            torch.empty((B, H, MB), dtype=torch.int32, device=dev) if want_order else None,
+            torch.empty((B, H, MB), dtype=torch.float32, device=dev) if want_scores else None,
+            torch.empty((B, H, 2), dtype=torch.int32, device=dev) if want_traffic else None)
+    o = outputs
+    assert q.is_contiguous() and meta.is_contiguous()
+    st = load_library().psa_decode_attention(
+        C.byref(d), _ptr(q), _ptr(meta), float(threshold), int(check_granularity), _ptr(o.out),
+        _ptr(o.n_selected), _ptr(o.mass_est), _ptr(o.blocks_read), _ptr(o.order), _ptr(o.scores),
+        _ptr(o.traffic), C.byref(t) if t else None, _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, "psa_decode_attention")
+    o._workspace = workspace   # keeps the buffer alive until the caller has synchronised
+    return o
+
+
+def dense_attention(kv: KvCache, q: torch.Tensor, *, workspace: torch.Tensor | None = None,
+                    out: torch.Tensor | None = None, lse: torch.Tensor | None = None, stream=None):
+    """psa_dense_attention; returns (out float32 [B][Hq][128], lse float32 [B][Hq])."""
+    d = kv.desc()
+    dev = q.device
+    if workspace is None:
+        workspace = torch.empty(max(dense_workspace_bytes(kv), 256), dtype=torch.uint8, device=dev)
+    if out is None:
+        out = torch.empty((d.batch, d.num_q_heads, 128), dtype=torch.float32, device=dev)
+    if lse is None:
+        lse = torch.empty((d.batch, d.num_q_heads), dtype=torch.float32, device=dev)
+    st = load_library().psa_dense_attention(C.byref(d), _ptr(q), _ptr(out), _ptr(lse), _ptr(workspace),
+                                            workspace.numel(), _stream(stream))
+    _check(st, "psa_dense_attention")
+    out._workspace = workspace
+    return out, lse
+
+
+def read_device_error(workspace: torch.Tensor, stream=None) -> int:
+    flags = C.c_int32(0)
+    st = load_library().psa_read_device_error(_ptr(workspace), C.byref(flags), _stream(stream))
+    _check(st, "psa_read_device_error")
+    return int(flags.value)

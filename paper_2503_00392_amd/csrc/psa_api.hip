@@ -1,0 +1,117 @@
+// The C ABI of libpsa: argument validation on the host, then kernel launches.  See include/psa.h
+// for the contract of every entry point.
+#include <math.h>
+
+#include "psa_host.h"
+
+namespace {
+
+bool supported_group(int g) { return g == 1 || g == 2 || g == 4 || g == 8; }
+
+// Shape checks common to all entry points.  `need_tables`: the call reads block_table / ctx_lens.
+psa_status check_desc(const psa_kv_desc *d, bool need_tables, bool need_v) {
+    if (!d) return PSA_ERR_INVALID_ARG;
+    if (d->batch < 0 || d->num_q_heads <= 0 || d->num_kv_heads <= 0 || d->num_pages < 0 ||
+        d->max_blocks_per_seq < 0)
+        return PSA_ERR_INVALID_ARG;
+    if (d->num_q_heads % d->num_kv_heads != 0) return PSA_ERR_INVALID_ARG;
+    if (d->dtype != PSA_F16 && d->dtype != PSA_BF16) return PSA_ERR_UNSUPPORTED;
+    if (d->head_dim != psa::kHeadDim || d->page_size != psa::kPage) return PSA_ERR_UNSUPPORTED;
+    if (!supported_group(d->num_q_heads / d->num_kv_heads)) return PSA_ERR_UNSUPPORTED;
+    if ((long long)d->batch * d->num_kv_heads > (1 << 24)) return PSA_ERR_UNSUPPORTED;
+    if (d->num_pages > 0 && !d->k_pool) return PSA_ERR_INVALID_ARG;
+    if (need_v && d->num_pages > 0 && !d->v_pool) return PSA_ERR_INVALID_ARG;
+    if (need_tables && d->batch > 0) {
+        if (!d->ctx_lens) return PSA_ERR_INVALID_ARG;
+        if (d->max_blocks_per_seq > 0 && !d->block_table) return PSA_ERR_INVALID_ARG;
+    }
+    return PSA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *psa_status_string(psa_status s) {
+    switch (s) {
+        case PSA_OK: return "PSA_OK";
+        case PSA_ERR_INVALID_ARG: return "PSA_ERR_INVALID_ARG";
+        case PSA_ERR_UNSUPPORTED: return "PSA_ERR_UNSUPPORTED";
+        case PSA_ERR_WORKSPACE_TOO_SMALL: return "PSA_ERR_WORKSPACE_TOO_SMALL";
+        case PSA_ERR_LAUNCH: return "PSA_ERR_LAUNCH";
+    }
+    return "PSA_ERR_UNKNOWN";
+}
+
+size_t psa_decode_workspace_bytes(const psa_kv_desc *d, const psa_tuning *tuning) {
+    if (check_desc(d, false, false) != PSA_OK) return 0;
+    if (d->max_blocks_per_seq > psa::kMaxBlocks) return 0;
+    return psa::decode_workspace_bytes_plan(d, psa::make_plan(d, tuning));
+}
+
+size_t psa_dense_workspace_bytes(const psa_kv_desc *d) {
+    if (check_desc(d, false, false) != PSA_OK) return 0;
+    return psa::dense_workspace_bytes(d);
+}
+
+psa_status psa_build_block_metadata(const psa_kv_desc *d, void *meta, const int32_t *page_fill,
+                                    const int32_t *page_list, int32_t num_listed, void *stream) {
+    psa_status st = check_desc(d, false, false);
+    if (st != PSA_OK) return st;
+    if (!meta && d->num_pages > 0) return PSA_ERR_INVALID_ARG;
+    if (num_listed < 0 || (num_listed > 0 && !page_list)) return PSA_ERR_INVALID_ARG;
+    if ((long long)d->num_pages * d->num_kv_heads > INT32_MAX) return PSA_ERR_UNSUPPORTED;
+    if (page_list && num_listed == 0) return PSA_OK;
+    hipError_t e = psa::launch_metadata(d, meta, page_fill, page_list, num_listed, (hipStream_t)stream);
+    return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
+}
+
+psa_status psa_decode_attention(const psa_kv_desc *d, const void *q, const void *meta, float threshold,
+                                int32_t check_granularity, float *out, int32_t *n_selected,
+                                float *mass_est, int32_t *blocks_read, int32_t *order_out,
+                                float *scores_out, int32_t *traffic_out, const psa_tuning *tuning,
+                                void *workspace, size_t workspace_bytes, void *stream) {
+    psa_status st = check_desc(d, true, true);
+    if (st != PSA_OK) return st;
+    if (!(threshold >= 0.0f && threshold <= 1.0f)) return PSA_ERR_INVALID_ARG;   // also rejects NaN
+    if (check_granularity < 1) return PSA_ERR_INVALID_ARG;
+    if (d->max_blocks_per_seq > psa::kMaxBlocks) return PSA_ERR_UNSUPPORTED;
+    if (tuning && (tuning->chunk_blocks < 0 || tuning->window_chunks < 0 || tuning->spin_limit < 0))
+        return PSA_ERR_INVALID_ARG;
+    if (tuning && tuning->chunk_blocks != 0 &&
+        (tuning->chunk_blocks < 8 || tuning->chunk_blocks > psa::kMaxChunkBlocks))
+        return PSA_ERR_INVALID_ARG;
+    if (d->batch == 0) return PSA_OK;
+    if (!q || !out || !n_selected || !mass_est || !workspace) return PSA_ERR_INVALID_ARG;
+    if (d->num_pages > 0 && !meta) return PSA_ERR_INVALID_ARG;
+    const psa::DecodePlan plan = psa::make_plan(d, tuning);
+    if (workspace_bytes < psa::decode_workspace_bytes_plan(d, plan)) return PSA_ERR_WORKSPACE_TOO_SMALL;
+    psa::DecodeArgs a;
+    a.q = q; a.meta = meta; a.threshold = threshold; a.check_granularity = check_granularity;
+    a.out = out; a.n_selected = n_selected; a.mass_est = mass_est; a.blocks_read = blocks_read;
+    a.order_out = order_out; a.scores_out = scores_out; a.traffic_out = traffic_out;
+    hipError_t e = psa::launch_decode(d, a, plan, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
+}
+
+psa_status psa_dense_attention(const psa_kv_desc *d, const void *q, float *out, float *lse,
+                               void *workspace, size_t workspace_bytes, void *stream) {
+    psa_status st = check_desc(d, true, true);
+    if (st != PSA_OK) return st;
+    if (d->batch == 0) return PSA_OK;
+    if (!q || !out || !workspace) return PSA_ERR_INVALID_ARG;
+    if (workspace_bytes < psa::dense_workspace_bytes(d)) return PSA_ERR_WORKSPACE_TOO_SMALL;
+    hipError_t e = psa::launch_dense(d, q, out, lse, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
+}
+
+psa_status psa_read_device_error(const void *workspace, int32_t *host_flags, void *stream) {
+    if (!workspace || !host_flags) return PSA_ERR_INVALID_ARG;
+    // word 1 of the workspace header holds the sticky bits
+    hipError_t e = hipMemcpyAsync(host_flags, static_cast<const int32_t *>(workspace) + 1, sizeof(int32_t),
+                                  hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
+}
+
+}  // extern "C"

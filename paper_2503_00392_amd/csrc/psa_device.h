@@ -1,0 +1,135 @@
+// Shared device-side definitions of the PSA decode kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/psa.h"
+
+namespace psa {
+
+constexpr int kHeadDim = 128;     // channels per head
+constexpr int kPage = 16;         // tokens per KV block
+constexpr int kRowBytes = 256;    // one token's key (or value) for one head
+constexpr int kSliceBytes = 4096; // one (page, KV head) K or V slice
+constexpr int kMetaBytes = 512;   // one (page, KV head) metadata record: min[128] | max[128]
+constexpr int kMaxBlocks = 8192;  // ranking limit per request (128K tokens)
+constexpr int kMaxChunkBlocks = 64;
+
+// 1/sqrt(128) * log2(e): logits are carried in log2 units so that exp is one v_exp_f32.
+constexpr float kScaleLog2 = 0.08838834764831845f * 1.4426950408889634f;
+constexpr float kScale = 0.08838834764831845f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Kernel-side view of psa_kv_desc.
+struct KvView {
+    const uint8_t *k_pool;
+    const uint8_t *v_pool;
+    const int32_t *block_table;
+    const int32_t *ctx_lens;
+    int32_t batch, num_q_heads, num_kv_heads, num_pages, max_blocks;
+};
+
+// ---- workspace of psa_decode_attention -----------------------------------------------------
+// Per-stream control block ("stream" = one (request, KV head) pair).
+struct StreamCtl {
+    int32_t done_chunk;   // smallest chunk index in which every head of the group had stopped
+    int32_t resolved;     // chunks of this stream that have evaluated the stop rule
+    int32_t k_blocks;     // K blocks loaded (traffic accounting)
+    int32_t v_blocks;     // V blocks loaded
+    unsigned long long stop[8];  // per head: (n << 32) | float bits of P_acc, minimum over chunks
+};
+
+struct DecodeWs {
+    int32_t *header;        // [0] work ticket, [1] sticky error bits
+    StreamCtl *ctl;         // [S]
+    float *scores;          // [S][max_blocks]
+    int32_t *order;         // [S][max_blocks]  ranked logical blocks
+    int32_t *ranked_page;   // [S][max_blocks]  physical page of each ranked block
+    unsigned long long *agg;  // [S][max_chunks][G]  (L_chunk, Lmin_chunk) as two floats, or the NaN sentinel
+    float *partial;         // [S][max_chunks][G][kPartialStride]
+    int32_t max_chunks;
+};
+constexpr int kPartialStride = 132;  // M, l, pad, pad, acc[128]
+constexpr unsigned long long kAggSentinel = 0xFFFFFFFFFFFFFFFFull;  // both halves NaN: never a value
+
+__device__ __forceinline__ void set_error(int32_t *header, int bit) { atomicOr(&header[1], bit); }
+
+// ---- 16-bit float helpers ------------------------------------------------------------------
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2_t __attribute__((ext_vector_type(2)));
+
+// acc + a.lo*b.lo + a.hi*b.hi, fp32 accumulate, on packed fp16 (DT 0) or bf16 (DT 1) pairs.
+template <int DT>
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
+    if constexpr (DT == 0) {
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, a), __builtin_bit_cast(half2_t, b),
+                                      acc, false);
+    } else {
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2_t, a),
+                                               __builtin_bit_cast(bf2_t, b), acc, false);
+    }
+}
+
+template <int DT>
+__device__ __forceinline__ float cvt_lo(uint32_t w) {
+    if constexpr (DT == 0) {
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xffffu));
+    } else {
+        return __builtin_bit_cast(float, w << 16);
+    }
+}
+template <int DT>
+__device__ __forceinline__ float cvt_hi(uint32_t w) {
+    if constexpr (DT == 0) {
+        return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16));
+    } else {
+        return __builtin_bit_cast(float, w & 0xffff0000u);
+    }
+}
+
+// ---- cross-lane helpers ----------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+// Sum over the 16 lanes of a DPP row; every lane of the row gets the total.
+__device__ __forceinline__ float row_sum16(float v) {
+    v += dpp_f<0xB1>(v);   // quad_perm [1,0,3,2]
+    v += dpp_f<0x4E>(v);   // quad_perm [2,3,0,1]
+    v += dpp_f<0x141>(v);  // row_half_mirror
+    v += dpp_f<0x140>(v);  // row_mirror
+    return v;
+}
+
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_logf(x); }
+
+// log2(2^a + 2^b), safe for -inf operands.
+__device__ __forceinline__ float lse2(float a, float b) {
+    float hi = fmaxf(a, b), lo = fminf(a, b);
+    if (hi == -INFINITY) return -INFINITY;
+    return hi + log2_fast(1.0f + exp2_fast(lo - hi));
+}
+
+// 16-byte global load of 8 packed 16-bit values.
+__device__ __forceinline__ uint4 ld16(const uint8_t *p) { return *reinterpret_cast<const uint4 *>(p); }
+
+__device__ __forceinline__ int clamp_page(int page, int num_pages, int32_t *header) {
+    if ((unsigned)page >= (unsigned)num_pages) {
+        set_error(header, PSA_DEVERR_PAGE_RANGE);
+        return 0;
+    }
+    return page;
+}
+
+// Blocks of request r, clamped into [0, max_blocks]; reports a context outside the table.
+__device__ __forceinline__ int ctx_clamped(const KvView &kv, int r, int32_t *header) {
+    int ctx = kv.ctx_lens[r];
+    if (ctx < 0) { set_error(header, PSA_DEVERR_CTX_RANGE); ctx = 0; }
+    if (ctx > kv.max_blocks * kPage) { set_error(header, PSA_DEVERR_CTX_RANGE); ctx = kv.max_blocks * kPage; }
+    return ctx;
+}
+
+}  // namespace psa

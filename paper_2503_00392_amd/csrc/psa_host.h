@@ -1,0 +1,62 @@
+// Host-side glue shared by the translation units of libpsa: launcher prototypes and small helpers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "psa_device.h"
+
+namespace psa {
+
+inline KvView make_view(const psa_kv_desc *d) {
+    KvView kv;
+    kv.k_pool = static_cast<const uint8_t *>(d->k_pool);
+    kv.v_pool = static_cast<const uint8_t *>(d->v_pool);
+    kv.block_table = d->block_table;
+    kv.ctx_lens = d->ctx_lens;
+    kv.batch = d->batch;
+    kv.num_q_heads = d->num_q_heads;
+    kv.num_kv_heads = d->num_kv_heads;
+    kv.num_pages = d->num_pages;
+    kv.max_blocks = d->max_blocks_per_seq;
+    return kv;
+}
+
+// Zero-fill by kernel (kept out of hipMemsetAsync so that callers may capture the calls in a graph).
+static __global__ void clear_words_kernel(int32_t *p, int n) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0;
+}
+
+// psa_dense.hip
+int dense_num_splits(const psa_kv_desc *d);
+size_t dense_workspace_bytes(const psa_kv_desc *d);
+hipError_t launch_dense(const psa_kv_desc *d, const void *q, float *out, float *lse, void *ws,
+                        hipStream_t st);
+
+// psa_meta.hip
+hipError_t launch_metadata(const psa_kv_desc *d, void *meta, const int32_t *page_fill,
+                           const int32_t *page_list, int num_listed, hipStream_t st);
+
+// psa_decode.hip
+struct DecodePlan {
+    int chunk_blocks;
+    int window_chunks;
+    int spin_limit;
+    int max_chunks;
+};
+DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t);
+size_t decode_workspace_bytes_plan(const psa_kv_desc *d, const DecodePlan &p);
+struct DecodeArgs {
+    const void *q, *meta;
+    float threshold;
+    int check_granularity;
+    float *out;
+    int32_t *n_selected;
+    float *mass_est;
+    int32_t *blocks_read, *order_out;
+    float *scores_out;
+    int32_t *traffic_out;
+};
+hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const DecodePlan &plan, void *ws,
+                         hipStream_t st);
+
+}  // namespace psa

@@ -1,0 +1,152 @@
+"""Helpers of the GPU parity tests: run the HIP path through the C ABI and the fp64 oracle on the same
+bytes and compare them under the stated rules.  Nothing here is imported by the product."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+from oracle import psa_oracle as po
+from workloads import LayerInputs, as_bits
+
+OUT_RTOL = 2e-3        # relative L2 error of an output row, fp16/bf16 inputs, fp32 accumulation
+SCORE_ATOL = 1e-3      # score distance to the stopping boundary inside which a block may differ
+PACC_ATOL = 1e-5       # |P_acc - eps| inside which the stop index itself may flip
+
+
+def to_problem(li: LayerInputs) -> po.Problem:
+    return po.Problem(as_bits(li.q), as_bits(li.k_pool), as_bits(li.v_pool),
+                      li.block_table.cpu().numpy(), li.ctx_lens.cpu().numpy(), li.dtype_code)
+
+
+def to_kv(li: LayerInputs):
+    import paper_2503_00392_amd as psa
+    return psa.KvCache(li.k_pool, li.v_pool, li.block_table, li.ctx_lens, li.cfg.num_q_heads)
+
+
+def rel_l2(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """Row-wise ||a-b|| / ||b|| over the last axis (0 where both are 0)."""
+    num = np.linalg.norm(a - b, axis=-1)
+    den = np.linalg.norm(b, axis=-1)
+    return np.where(den > 0, num / np.where(den > 0, den, 1), num)
+
+
+@dataclass
+class ParityReport:
+    heads: int = 0
+    set_equal: int = 0
+    set_tolerated: int = 0        # sets differ only by blocks within SCORE_ATOL of the boundary
+    stop_flips: int = 0           # stop index differs with the oracle's P_acc within PACC_ATOL of eps
+    worst_out: float = 0.0
+    worst_out_vs_own_set: float = 0.0
+    worst_score: float = 0.0
+    worst_mass: float = 0.0
+
+    def __str__(self):
+        return (f"heads={self.heads} set_equal={self.set_equal} tolerated={self.set_tolerated} "
+                f"stop_flips={self.stop_flips} worst_out={self.worst_out:.2e} "
+                f"worst_out_vs_own_set={self.worst_out_vs_own_set:.2e} "
+                f"worst_score_err={self.worst_score:.2e} worst_mass_err={self.worst_mass:.2e}")
+
+
+def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, requests=None) -> ParityReport:
+    """gpu: DecodeOutput with order and scores.  `requests`: subset of request indices the oracle
+    computes (all by default)."""
+    B, Hq, H, D, T, P, MB = pb.dims
+    G = Hq // H
+    if requests is not None:
+        requests = list(requests)
+        sub = po.Problem(pb.q[requests], pb.k_pool, pb.v_pool, pb.block_table[requests],
+                         pb.ctx_lens[requests], pb.dtype)
+    else:
+        requests = list(range(B))
+        sub = pb
+    g_out = gpu.out.cpu().numpy().astype(np.float64)[requests]
+    g_n = gpu.n_selected.cpu().numpy()[requests]
+    g_mass = gpu.mass_est.cpu().numpy().astype(np.float64)[requests]
+    g_read = gpu.blocks_read.cpu().numpy()[requests]
+    g_order = gpu.order.cpu().numpy()[requests]
+    g_scores = gpu.scores.cpu().numpy().astype(np.float64)[requests]
+
+    ora = po.psa_decode(sub, eps, m)
+    nb = sub.num_blocks()
+    rep = ParityReport()
+
+    # -- scores and ranking ------------------------------------------------------------------------
+    for i in range(len(requests)):
+        N = int(nb[i])
+        for h in range(H):
+            cs, gs = ora.cs[i, h, :N], g_scores[i, h, :N]
+            if N:
+                rep.worst_score = max(rep.worst_score, float(np.abs(cs - gs).max()))
+            o = g_order[i, h]
+            assert np.array_equal(np.sort(o[:N]), np.arange(N)), "ranking is not a permutation"
+            assert np.all(o[N:] == -1)
+            ranked = gs[o[:N]]
+            assert np.all(np.diff(ranked) <= 0), "ranking is not descending in the GPU's own scores"
+            ties = np.diff(ranked) == 0
+            assert np.all(np.diff(o[:N])[ties] > 0), "ties must go to the smaller logical block"
+            # against the oracle's ranking: the score at every rank agrees within the tolerance
+            if N:
+                assert np.abs(cs[o[:N]] - cs[ora.order[i, h, :N]]).max() <= SCORE_ATOL
+    assert rep.worst_score <= SCORE_ATOL / 4, f"score error {rep.worst_score}"
+
+    # -- output against attention over the GPU's OWN selected prefix (always) ----------------------
+    own = po.attend_prefix(sub, g_order, g_n)
+    err_own = rel_l2(g_out, own)
+    rep.worst_out_vs_own_set = float(err_own.max()) if err_own.size else 0.0
+    assert rep.worst_out_vs_own_set <= OUT_RTOL, f"output vs own set: {rep.worst_out_vs_own_set}"
+
+    # -- stop index, selected set, estimate ---------------------------------------------------------
+    curves = None
+    for i in range(len(requests)):
+        N = int(nb[i])
+        for hq in range(Hq):
+            h = hq // G
+            rep.heads += 1
+            n_g, n_o = int(g_n[i, hq]), int(ora.n_selected[i, hq])
+            assert 0 <= n_g <= N and (n_g % m == 0 or n_g == N)
+            if N == 0:
+                assert n_g == 0 and g_mass[i, hq] == 0 and not g_out[i, hq].any()
+                continue
+            assert g_mass[i, hq] > eps or n_g == N, "estimate must exceed eps unless all blocks were used"
+            if n_g != n_o:
+                if curves is None:
+                    curves = po.psa_decode(sub, eps, m, curves=True)
+                p_at = curves.p_acc[i, hq, min(n_g, n_o) - 1]
+                assert abs(p_at - eps) <= PACC_ATOL, \
+                    f"stop index {n_g} vs oracle {n_o} with P_acc {p_at} not at the boundary {eps}"
+                rep.stop_flips += 1
+                continue
+            sg, so = set(g_order[i, h, :n_g].tolist()), set(ora.order[i, h, :n_o].tolist())
+            if sg == so:
+                rep.set_equal += 1
+                e = float(rel_l2(g_out[i, hq], ora.out[i, hq]))
+                rep.worst_out = max(rep.worst_out, e)
+                assert e <= OUT_RTOL, f"output vs oracle: {e}"
+                me = abs(g_mass[i, hq] - ora.mass_est[i, hq])
+                rep.worst_mass = max(rep.worst_mass, me)
+                assert me <= 1e-4, f"mass estimate {g_mass[i, hq]} vs {ora.mass_est[i, hq]}"
+            else:
+                boundary = ora.cs[i, h, ora.order[i, h, n_o - 1]]
+                for b in sg ^ so:
+                    assert abs(ora.cs[i, h, b] - boundary) <= SCORE_ATOL, \
+                        f"block {b} differs away from the stopping boundary"
+                rep.set_tolerated += 1
+        for h in range(H):
+            assert g_read[i, h] == g_n[i, h * G:(h + 1) * G].max()
+    return rep
+
+
+def run_gpu_decode(li: LayerInputs, eps: float, m: int = 1, tuning=None, meta=None):
+    import paper_2503_00392_amd as psa
+    kv = to_kv(li)
+    if meta is None:
+        meta = psa.build_block_metadata(kv, page_fill=li.page_fill)
+    out = psa.decode_attention(kv, li.q, meta, eps, m, want_order=True, want_scores=True,
+                               want_traffic=True, tuning=tuning)
+    torch.cuda.synchronize()
+    flags = psa.read_device_error(out._workspace)
+    assert flags == 0, f"device error flags {flags}"
+    return out
