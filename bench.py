@@ -1,0 +1,284 @@
+#!/usr/bin/env python3
+"""Benchmark of the PSA decode hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3]
+
+A "step" is one decode step of the whole model of the chosen workload: for every layer, the
+per-step metadata build (the pages that filled at this step), then scoring, ranking, progressive
+attention with the on-GPU stop rule, and the final merge -- all through the C ABI of libpsa.so.
+Inputs are seeded synthetic KV caches (workloads/generator.py), resident in HBM before timing.
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class HipEvents:
+    """hipEvent_t handles through the HIP runtime directly (the library records them itself)."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+        self.all = []
+
+    def array(self, n):
+        arr = (C.c_void_p * n)()
+        for i in range(n):
+            ev = C.c_void_p()
+            assert self.hip.hipEventCreate(C.byref(ev)) == 0
+            arr[i] = ev
+            self.all.append(ev)
+        return arr
+
+    def elapsed_ms(self, a, b) -> float:
+        ms = C.c_float()
+        rc = self.hip.hipEventElapsedTime(C.byref(ms), a, b)
+        assert rc == 0, rc
+        return float(ms.value)
+
+    def destroy(self):
+        for ev in self.all:
+            self.hip.hipEventDestroy(ev)
+        self.all = []
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = the 128K-context one)")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
+    ap.add_argument("--check-granularity", type=int, default=1)
+    ap.add_argument("--chunk-blocks", type=int, default=0)
+    ap.add_argument("--window-chunks", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--cpu-layers", type=str, default="", help="layers the oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+            "(the path shards by request or by KV head with no exchange, see DESIGN.md)")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2503_00392_amd as psa
+    from workloads import generate_layer, get_config
+
+    psa.load_library()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    cfg = get_config(args.config)
+    if args.layers:
+        cfg = cfg.scaled(layers=args.layers)
+    L, B, Hq, H, G = cfg.layers, cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.group
+    eps, m = cfg.threshold, args.check_granularity
+    tuning_kw = dict(chunk_blocks=args.chunk_blocks, window_chunks=args.window_chunks)
+
+    # ---- inputs, resident in HBM ---------------------------------------------------------------
+    t0 = time.time()
+    layers = []
+    for l in range(L):
+        li = generate_layer(cfg, layer=l, device=dev)
+        layers.append(li)
+        if l % 8 == 0:
+            log(f"[bench] generated layer {l + 1}/{L}  ({time.time() - t0:.1f}s, "
+                f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB)")
+    kvs = [psa.KvCache(li.k_pool, li.v_pool, li.block_table, li.ctx_lens, Hq) for li in layers]
+    nblk = [((li.ctx_lens.cpu().numpy().astype(np.int64) + 15) // 16) for li in layers]
+    # the page of each request that fills at this step (its last one): the per-step metadata work
+    last_pages = [torch.stack([li.block_table[r, max(int(nblk[i][r]) - 1, 0)] for r in range(B)]).contiguous()
+                  for i, li in enumerate(layers)]
+    torch.cuda.synchronize()
+
+    # ---- bulk metadata build (once per filled page in a serving system; timed on its own) -------
+    metas = [torch.empty((kv.k_pool.shape[0], H, 2, 128), dtype=kv.k_pool.dtype, device=dev) for kv in kvs]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for rep in range(2):
+        e0.record()
+        for kv, meta, li in zip(kvs, metas, layers):
+            psa.build_block_metadata(kv, meta, page_fill=li.page_fill)
+        e1.record()
+        torch.cuda.synchronize()
+    meta_ms = e0.elapsed_time(e1)
+    meta_bytes = sum(kv.k_pool.numel() * 2 + mt.numel() * 2 for kv, mt in zip(kvs, metas))
+
+    # ---- buffers of the timed loop: nothing is allocated inside it --------------------------------
+    tun = psa.Tuning(**tuning_kw)
+    ws_bytes = max(psa.decode_workspace_bytes(kv, tun) for kv in kvs)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    MB = max(kv.block_table.shape[1] for kv in kvs)
+    outs = [psa.DecodeOutput(torch.empty((B, Hq, 128), dtype=torch.float32, device=dev),
+                             torch.empty((B, Hq), dtype=torch.int32, device=dev),
+                             torch.empty((B, Hq), dtype=torch.float32, device=dev),
+                             torch.empty((B, H), dtype=torch.int32, device=dev), None, None,
+                             torch.empty((B, H, 2), dtype=torch.int32, device=dev)) for _ in range(L)]
+
+    def step(tunings=None):
+        for i in range(L):
+            psa.build_block_metadata(kvs[i], metas[i], page_fill=layers[i].page_fill, page_list=last_pages[i])
+            psa.decode_attention(kvs[i], layers[i].q, metas[i], eps, m, workspace=ws, outputs=outs[i],
+                                 tuning=tunings[i] if tunings else tun)
+
+    log(f"[bench] inputs ready in {time.time() - t0:.1f}s; warmup")
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    assert psa.read_device_error(ws) == 0
+
+    # ---- timed region: exactly K steps -------------------------------------------------------------
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_start) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    ms_per_step = max(wall_ms, gpu_ms) / args.steps
+    q_heads_per_step = L * B * Hq
+    value = q_heads_per_step / (ms_per_step * 1e-3)
+
+    # ---- selection statistics and bytes (from the outputs of the last step) -------------------------
+    blocks_read = np.stack([o.blocks_read.cpu().numpy().astype(np.int64) for o in outs])      # [L][B][H]
+    traffic = np.stack([o.traffic.cpu().numpy().astype(np.int64) for o in outs])              # [L][B][H][2]
+    n_sel = np.stack([o.n_selected.cpu().numpy().astype(np.int64) for o in outs])
+    N_total = np.stack([np.repeat(nb[:, None], H, 1) for nb in nblk])                          # [L][B][H]
+    page_bytes = blocks_read * 8192
+    meta_read = N_total * 512
+    table_read = N_total * 4
+    q_bytes = L * B * Hq * 256
+    alg_bytes = int(page_bytes.sum() + meta_read.sum() + table_read.sum() + q_bytes)
+    dense_bytes = int((N_total * 8192).sum() + table_read.sum() + q_bytes)
+    kv_reduction = float((N_total * 8192).sum() / (meta_read.sum() + page_bytes.sum()))
+    spec_k_bytes = int(((traffic[..., 0] - blocks_read) * 4096).sum())
+    eff_gbs = alg_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---- per-kernel durations, live, with HIP events recorded by the library around its kernels ----
+    hev = HipEvents()
+    ev_sets = [[hev.array(6) for _ in range(L)] for _ in range(args.steps)]
+    for k in range(args.steps):
+        step([psa.Tuning(phase_events=ev_sets[k][i], **tuning_kw) for i in range(L)])
+    torch.cuda.synchronize()
+    names = ["score", "order", "select", "attend", "finalize"]
+    phase_ms = {n: [] for n in names}
+    for k in range(args.steps):
+        for i in range(L):
+            ev = ev_sets[k][i]
+            for j, n in enumerate(names):
+                phase_ms[n].append(hev.elapsed_ms(ev[j], ev[j + 1]))
+    hev.destroy()
+    phase_avg = {n: float(np.mean(v)) for n, v in phase_ms.items()}
+    # algorithmic bytes per launch of the two heavy kernels ("Measurement")
+    logit_bytes = blocks_read.sum() * 16 * G * 4
+    kern_bytes = {
+        "select_kernel": float((blocks_read.sum() * (4096 + 8) + logit_bytes) / L),   # K slices, tables, logits out
+        "attend_kernel": float((blocks_read.sum() * (4096 + 8) + logit_bytes) / L),   # V slices, tables, logits in
+    }
+    kern_ms = {"select_kernel": phase_avg["select"], "attend_kernel": phase_avg["attend"]}
+    dom = max(kern_ms, key=kern_ms.get)
+    dom_gbs = kern_bytes[dom] / (kern_ms[dom] * 1e-3) / 1e9
+    kern_gbs = {k: kern_bytes[k] / (kern_ms[k] * 1e-3) / 1e9 for k in kern_ms}
+    score_bytes_per_launch = float((meta_read.sum() + table_read.sum()) / L)
+    score_gbs = score_bytes_per_launch / (phase_avg["score"] * 1e-3) / 1e9
+    per_layer = {n: np.array(phase_ms[n]).reshape(args.steps, L).mean(0) for n in names}
+
+    # ---- dense control on the same inputs -------------------------------------------------------------
+    dense = None
+    if not args.no_dense:
+        dws = torch.empty(max(psa.dense_workspace_bytes(kv) for kv in kvs), dtype=torch.uint8, device=dev)
+        dout = torch.empty((B, Hq, 128), dtype=torch.float32, device=dev)
+        dlse = torch.empty((B, Hq), dtype=torch.float32, device=dev)
+        for rep in range(1 + args.steps):
+            if rep == 1:
+                e0.record()
+            for i in range(L):
+                psa.dense_attention(kvs[i], layers[i].q, workspace=dws, out=dout, lse=dlse)
+        e1.record()
+        torch.cuda.synchronize()
+        dense_ms = e0.elapsed_time(e1) / args.steps
+        dense = {"ms_per_step": dense_ms, "query_heads_per_s": q_heads_per_step / (dense_ms * 1e-3),
+                 "bytes": dense_bytes, "GBps": dense_bytes / (dense_ms * 1e-3) / 1e9,
+                 "hbm_frac": dense_bytes / (dense_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                 "psa_speedup": dense_ms / ms_per_step, "kv_reduction_implied": kv_reduction}
+
+    # ---- the oracle on the host cores, bounded sample ----------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        import gpu_common as gc
+        from oracle import psa_oracle as po
+        if args.cpu_layers:
+            sample = [int(x) for x in args.cpu_layers.split(",")]
+        else:
+            sample = sorted(set([0, L // 2] if L > 1 else [0]))
+        reqs = list(range(min(B, 2)))
+        t_cpu, heads = 0.0, 0
+        for l in sample:
+            pb = gc.to_problem(layers[l])
+            sub = po.Problem(pb.q[reqs], pb.k_pool, pb.v_pool, pb.block_table[reqs], pb.ctx_lens[reqs], pb.dtype)
+            meta_bits = metas[l].view(torch.int16).cpu().numpy().view(np.uint16)
+            t1 = time.perf_counter()
+            res = po.psa_decode(sub, eps, m, meta=meta_bits)
+            t_cpu += time.perf_counter() - t1
+            heads += len(reqs) * Hq
+            g_n = outs[l].n_selected.cpu().numpy()[reqs]
+            log(f"[bench] oracle layer {l}: {len(reqs) * Hq} heads, n_selected equal on "
+                f"{(g_n == res.n_selected).mean() * 100:.1f}% of heads, cumulative {t_cpu:.1f}s")
+            del pb, sub
+        cpu = {"value": heads / t_cpu, "unit": "query-heads/s", "cores": po.num_threads(), "kind": "oracle",
+               "sample": f"config {cfg.index}, layers {sample}, requests {reqs}, all {Hq} query heads, "
+                         f"scoring+ranking+progressive loop in fp64 ({t_cpu:.1f}s of CPU time)"}
+
+    result = {
+        "metric": "psa_decode_query_heads_per_s", "value": value, "unit": "query-heads/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "layers": L, "batch": B, "num_q_heads": Hq, "num_kv_heads": H,
+                   "ctx": cfg.ctx, "kv_dtype": cfg.dtype, "threshold": eps, "check_granularity": m,
+                   "chunk_blocks": args.chunk_blocks or 32, "parallelism": "1 GPU"},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_ms": kern_ms[dom], "algorithmic_bytes_per_launch": kern_bytes[dom]},
+        "cpu_baseline": cpu,
+        "whole_path": {"algorithmic_bytes_per_step": alg_bytes, "GBps": eff_gbs, "hbm_frac": eff_gbs / HBM_PEAK_GBS,
+                       "speculative_k_bytes_per_step": spec_k_bytes,
+                       "kv_reduction_vs_dense": kv_reduction,
+                       "mean_selected_fraction": float((blocks_read / np.maximum(N_total, 1)).mean()),
+                       "phase_avg_ms_per_layer": phase_avg,
+                       "kernel_GBps": dict(kern_gbs, score_kernel=score_gbs)},
+        "dense_control": dense,
+        "metadata_bulk_build": {"ms": meta_ms, "GBps": meta_bytes / (meta_ms * 1e-3) / 1e9},
+    }
+    for n in ("select", "attend"):
+        log(f"[bench] per-layer {n} ms: " + " ".join(f"{x:.3f}" for x in per_layer[n]))
+    log("[bench] per-layer selected fraction: " +
+        " ".join(f"{x:.3f}" for x in (blocks_read / np.maximum(N_total, 1)).mean((1, 2))))
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -73,10 +73,15 @@ typedef struct {
  * speculatively and how work is cut, never the result. */
 typedef struct {
     int32_t chunk_blocks;   /* ranked blocks per work item, 8..64 (default 32)                    */
-    int32_t window_chunks;  /* work items of one (request, KV head) allowed past the last resolved
-                               one (default: from the number of streams)                          */
+    int32_t window_chunks;  /* least number of work items of one (request, KV head) handed out past
+                               its resolved ones; the window grows to half the resolved count, at
+                               most 64 (default: from the number of streams)                      */
     int32_t spin_limit;     /* polls before a bounded in-kernel wait gives up (default 1<<22)     */
-    int32_t reserved;
+    int32_t force_bitonic;  /* 1: always rank with the bitonic network (testing); 0: automatic    */
+    void *phase_events;     /* host pointer: NULL, or hipEvent_t[6] the call records on `stream`
+                               before scoring and after each of its kernels: scoring, ranking,
+                               selection (key pass), attention (value pass), final merge
+                               (profiling aid)                                                    */
 } psa_tuning;
 
 /* Bytes of workspace psa_decode_attention needs for this descriptor and tuning (NULL = defaults);
@@ -122,8 +127,8 @@ psa_status psa_build_block_metadata(const psa_kv_desc *desc, void *meta, const i
  *                the request's block count); may be NULL
  *   scores_out   [batch][num_kv_heads][max_blocks_per_seq] float32 criticality scores by logical
  *                block (untouched beyond the block count); may be NULL
- *   traffic_out  [batch][num_kv_heads][2] K blocks and V blocks actually loaded (K is read a
- *                bounded window ahead of the stop); may be NULL
+ *   traffic_out  [batch][num_kv_heads][2] key slices and value slices actually loaded (keys are read
+ *                a bounded window ahead of the stop, values only for selected blocks); may be NULL
  *   tuning       NULL = defaults
  * A request with ctx_len 0 gets out = 0, n_selected = 0, mass_est = 0.
  */

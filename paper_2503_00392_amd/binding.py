@@ -36,7 +36,7 @@ class _KvDesc(C.Structure):
 
 class _Tuning(C.Structure):
     _fields_ = [("chunk_blocks", C.c_int32), ("window_chunks", C.c_int32),
-                ("spin_limit", C.c_int32), ("reserved", C.c_int32)]
+                ("spin_limit", C.c_int32), ("force_bitonic", C.c_int32), ("phase_events", C.c_void_p)]
 
 
 @dataclass
@@ -44,9 +44,12 @@ class Tuning:
     chunk_blocks: int = 0
     window_chunks: int = 0
     spin_limit: int = 0
+    force_bitonic: int = 0
+    phase_events: object = None   # ctypes array of 6 hipEvent_t (c_void_p), or None
 
     def c(self) -> _Tuning:
-        return _Tuning(self.chunk_blocks, self.window_chunks, self.spin_limit, 0)
+        ev = C.cast(self.phase_events, C.c_void_p) if self.phase_events is not None else None
+        return _Tuning(self.chunk_blocks, self.window_chunks, self.spin_limit, self.force_bitonic, ev)
 
 
 _lib = None

@@ -15,7 +15,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpsa.so")
-SOURCES = ["psa_api.hip", "psa_meta.hip", "psa_dense.hip", "psa_decode.hip"]
+SOURCES = ["psa_api.hip", "psa_meta.hip", "psa_dense.hip", "psa_decode.hip", "psa_score.hip",
+           "psa_order.hip", "psa_select.hip", "psa_values.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 VALU forms are kept out of the generated code

@@ -78,6 +78,7 @@ psa_status psa_decode_attention(const psa_kv_desc *d, const void *q, const void 
     if (d->max_blocks_per_seq > psa::kMaxBlocks) return PSA_ERR_UNSUPPORTED;
     if (tuning && (tuning->chunk_blocks < 0 || tuning->window_chunks < 0 || tuning->spin_limit < 0))
         return PSA_ERR_INVALID_ARG;
+    if (tuning && (tuning->force_bitonic < 0 || tuning->force_bitonic > 1)) return PSA_ERR_INVALID_ARG;
     if (tuning && tuning->chunk_blocks != 0 &&
         (tuning->chunk_blocks < 8 || tuning->chunk_blocks > psa::kMaxChunkBlocks))
         return PSA_ERR_INVALID_ARG;

@@ -32,24 +32,35 @@ struct KvView {
 
 // ---- workspace of psa_decode_attention -----------------------------------------------------
 // Per-stream control block ("stream" = one (request, KV head) pair).
-struct StreamCtl {
+struct alignas(128) StreamCtl {
+    int32_t next_chunk;   // ticket: next chunk of this stream to hand out
     int32_t done_chunk;   // smallest chunk index in which every head of the group had stopped
     int32_t resolved;     // chunks of this stream that have evaluated the stop rule
     int32_t k_blocks;     // K blocks loaded (traffic accounting)
-    int32_t v_blocks;     // V blocks loaded
+    int32_t pad[4];
     unsigned long long stop[8];  // per head: (n << 32) | float bits of P_acc, minimum over chunks
 };
 
 struct DecodeWs {
-    int32_t *header;        // [0] work ticket, [1] sticky error bits
+    int32_t *header;        // [1] sticky error bits
     StreamCtl *ctl;         // [S]
     float *scores;          // [S][max_blocks]
     int32_t *order;         // [S][max_blocks]  ranked logical blocks
     int32_t *ranked_page;   // [S][max_blocks]  physical page of each ranked block
     unsigned long long *agg;  // [S][max_chunks][G]  (L_chunk, Lmin_chunk) as two floats, or the NaN sentinel
+    float *logits;          // [S][max_blocks][G][16]  scaled logits (log2 units) by ranked block
     float *partial;         // [S][max_chunks][G][kPartialStride]
     int32_t max_chunks;
+#ifdef PSA_ENABLE_TRACE
+    unsigned long long *trace;   // [0] record count, then 8 words per processed chunk (tuning aid)
+#endif
 };
+#ifdef PSA_ENABLE_TRACE
+constexpr int kTraceRecords = 1 << 16;
+#define PSA_TRACE_STAMP(var) const unsigned long long var = wall_clock64()
+#else
+#define PSA_TRACE_STAMP(var)
+#endif
 constexpr int kPartialStride = 132;  // M, l, pad, pad, acc[128]
 constexpr unsigned long long kAggSentinel = 0xFFFFFFFFFFFFFFFFull;  // both halves NaN: never a value
 
@@ -68,6 +79,23 @@ __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
     } else {
         return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2_t, a),
                                                __builtin_bit_cast(bf2_t, b), acc, false);
+    }
+}
+
+// D(16x16, fp32) += A(16x32) * B(32x16) on the matrix cores, 16-bit inputs.  Lane l supplies row
+// l%16 of A and column l%16 of B, 8 consecutive k values each (k block l/16); it receives column
+// l%16 of D, rows 4*(l/16) .. 4*(l/16)+3.
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+template <int DT>
+__device__ __forceinline__ f32x4_t mfma_16x16x32(const uint4 &a, const uint4 &b, f32x4_t c) {
+    if constexpr (DT == 0) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a),
+                                                      __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     }
 }
 
@@ -103,6 +131,15 @@ __device__ __forceinline__ float row_sum16(float v) {
     return v;
 }
 
+// Maximum over the 16 lanes of a DPP row; every lane of the row gets it.
+__device__ __forceinline__ float row_max16(float v) {
+    v = fmaxf(v, dpp_f<0xB1>(v));
+    v = fmaxf(v, dpp_f<0x4E>(v));
+    v = fmaxf(v, dpp_f<0x141>(v));
+    v = fmaxf(v, dpp_f<0x140>(v));
+    return v;
+}
+
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float log2_fast(float x) { return __builtin_amdgcn_logf(x); }
 
@@ -111,6 +148,15 @@ __device__ __forceinline__ float lse2(float a, float b) {
     float hi = fmaxf(a, b), lo = fminf(a, b);
     if (hi == -INFINITY) return -INFINITY;
     return hi + log2_fast(1.0f + exp2_fast(lo - hi));
+}
+
+// Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not wait for the
+// wave's outstanding global loads, stores and atomics, so those stay in flight across it.  Use it
+// where the waves of a workgroup communicate through LDS alone.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
 // 16-byte global load of 8 packed 16-bit values.

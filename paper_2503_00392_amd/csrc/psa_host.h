@@ -42,6 +42,9 @@ struct DecodePlan {
     int window_chunks;
     int spin_limit;
     int max_chunks;
+    int persistent_wgs;   // workgroups of the progressive kernel's persistent grid
+    int force_bitonic;
+    hipEvent_t *events;   // NULL or 6 events recorded between the kernels
 };
 DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t);
 size_t decode_workspace_bytes_plan(const psa_kv_desc *d, const DecodePlan &p);
@@ -58,5 +61,18 @@ struct DecodeArgs {
 };
 hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const DecodePlan &plan, void *ws,
                          hipStream_t st);
+
+// psa_score.hip, psa_order.hip, psa_select.hip, psa_values.hip: the kernels of one decode call
+hipError_t launch_score(const KvView &kv, int dtype, int G, const void *q, const void *meta,
+                        const DecodeWs &ws, float *scores_out, hipStream_t st);
+hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int force_bitonic,
+                        int32_t *order_out, hipStream_t st);
+hipError_t launch_select(const KvView &kv, int dtype, int G, const void *q, const DecodeWs &ws, float eps,
+                         int m, const DecodePlan &plan, hipStream_t st);
+hipError_t launch_attend(const KvView &kv, int dtype, int G, const DecodeWs &ws, const DecodePlan &plan,
+                         hipStream_t st);
+hipError_t launch_finalize(const KvView &kv, const DecodeWs &ws, int G, int CB, float *out,
+                           int32_t *n_selected, float *mass_est, int32_t *blocks_read,
+                           int32_t *traffic_out, hipStream_t st);
 
 }  // namespace psa

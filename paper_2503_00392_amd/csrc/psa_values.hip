@@ -1,0 +1,281 @@
+// Value pass and final merge of one PSA decode step (Algorithm 1, lines 10-12 and 19).
+//
+// By the time these kernels run, the selection kernel has fixed every query head's stop n_g and
+// left the exact scaled logits of the ranked blocks in the workspace.  What remains is plain
+// attention over each head's own prefix: softmax numerators from the stored logits, times the value
+// slices of the selected blocks -- every workgroup independent, no waiting, and only blocks
+// actually selected are read.
+//   attend_kernel    one workgroup per (chunk, stream): p = exp(logit - chunk max), partial
+//                    numerator sum_t p_t v_t per head, exp-sum and reference maximum
+//   finalize_kernel  merges a head's chunks (the online-softmax merge of line 11, all at once)
+#include "psa_attend.h"
+#include "psa_host.h"
+
+namespace psa {
+
+constexpr int kBatch = 4;   // slices a wave keeps in flight
+
+template <int G>
+struct AttendShared {
+    float p[kMaxChunkBlocks][kPage][G];    // logits, then softmax numerators
+    float st_acc[4][G][kHeadDim];          // per-wave partial numerators
+    float red[256];
+    int page[kMaxChunkBlocks];
+    int valid[kMaxChunkBlocks];
+    int cnt[G];
+    float Mref[G];
+    float lsum[G];
+};
+
+// Stop of head g of a stream: (n, P_acc) as the selection kernel left it, n = N when it never stopped.
+__device__ __forceinline__ int head_stop(const StreamCtl *ctl, int g, int N) {
+    const unsigned long long st = ctl->stop[g];
+    return (st != ~0ull && (int)(st >> 32) <= N) ? (int)(st >> 32) : N;
+}
+
+// grid (max_chunks, S), 256 threads.
+template <int DT, int G>
+__global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int CB) {
+    __shared__ AttendShared<G> sh;
+    const int c = blockIdx.x, s = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, rg = lane >> 4, cl = lane & 15;
+    const int h = s % kv.num_kv_heads;
+    int ctx = kv.ctx_lens[s / kv.num_kv_heads];
+    ctx = ctx < 0 ? 0 : (ctx > kv.max_blocks * kPage ? kv.max_blocks * kPage : ctx);
+    const int N = (ctx + kPage - 1) / kPage;
+    const int start = c * CB;
+    if (start >= N) return;
+    const int nblk = min(CB, N - start);
+    const StreamCtl *ctl = &ws.ctl[s];
+    int cnt[G], maxcnt = 0;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        cnt[g] = min(nblk, max(0, head_stop(ctl, g, N) - start));
+        maxcnt = max(maxcnt, cnt[g]);
+    }
+    if (maxcnt == 0) return;    // no head of the group reaches this chunk
+
+    if (tid < maxcnt) {
+        const size_t at = (size_t)s * kv.max_blocks + start + tid;
+        sh.page[tid] = ws.ranked_page[at];
+        sh.valid[tid] = min(kPage, ctx - ws.order[at] * kPage);
+    }
+    lds_barrier();
+    // first batch of value slices, issued before the softmax bookkeeping so that they overlap it
+    Slice v[kBatch];
+#pragma unroll
+    for (int u = 0; u < kBatch; ++u) {
+        const int i = wave * kBatch + u;
+        if (i < maxcnt) {
+            const size_t off = ((size_t)sh.page[i] * kv.num_kv_heads + h) * kSliceBytes;
+            v[u] = load_slice(kv.v_pool + off, lane);
+        }
+    }
+    // logits of the chunk (contiguous in the workspace as [block][head][token]) -> LDS as
+    // [block][token][head], with each head's maximum over the blocks it uses
+    const float *lg = ws.logits + ((size_t)s * kv.max_blocks + start) * (kPage * G);
+    const int total = maxcnt * kPage * G;
+    float mx = -INFINITY;                       // thread-local, for head g = (tid / 16) % G
+    for (int idx = tid; idx < total; idx += 256) {
+        const int t = idx % kPage, g = (idx / kPage) % G, i = idx / (kPage * G);
+        const float x = lg[idx];
+        sh.p[i][t][g] = x;
+        if (i < cnt[g]) mx = fmaxf(mx, x);
+    }
+    // thread tid holds head (tid / 16) % G: reduce each 16-lane row, then the 16/G rows of a head
+    mx = row_max16(mx);
+    if (cl == 0) sh.red[tid >> 4] = mx;
+    lds_barrier();
+    if (tid < G) {
+        float M = -INFINITY;
+        for (int j = tid; j < 16; j += G) M = fmaxf(M, sh.red[j]);
+        sh.Mref[tid] = M;
+    }
+    lds_barrier();
+    float sum = 0.0f;
+    for (int idx = tid; idx < total; idx += 256) {
+        const int t = idx % kPage, g = (idx / kPage) % G, i = idx / (kPage * G);
+        float *p = &sh.p[i][t][g];
+        const float e = (i < cnt[g]) ? exp2_fast(*p - sh.Mref[g]) : 0.0f;   // masked tokens hold -inf
+        *p = e;
+        sum += e;
+    }
+    sum = row_sum16(sum);
+    if (cl == 0) sh.red[16 + (tid >> 4)] = sum;
+    lds_barrier();
+    if (tid < G) {
+        float l = 0.0f;
+        for (int j = tid; j < 16; j += G) l += sh.red[16 + j];
+        sh.lsum[tid] = l;
+    }
+
+    float acc[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int x = 0; x < 8; ++x) acc[g][x] = 0.0f;
+    for (int i0 = wave * kBatch; i0 < maxcnt; i0 += 4 * kBatch) {
+        if (i0 != wave * kBatch) {
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                if (i0 + u < maxcnt) {
+                    const size_t off = ((size_t)sh.page[i0 + u] * kv.num_kv_heads + h) * kSliceBytes;
+                    v[u] = load_slice(kv.v_pool + off, lane);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int i = i0 + u;
+            if (i < maxcnt) {
+                if (sh.valid[i] < kPage) zero_invalid_rows(v[u], rg, sh.valid[i]);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    float vf[8];
+                    vf[0] = cvt_lo<DT>(v[u].r[x].x); vf[1] = cvt_hi<DT>(v[u].r[x].x);
+                    vf[2] = cvt_lo<DT>(v[u].r[x].y); vf[3] = cvt_hi<DT>(v[u].r[x].y);
+                    vf[4] = cvt_lo<DT>(v[u].r[x].z); vf[5] = cvt_hi<DT>(v[u].r[x].z);
+                    vf[6] = cvt_lo<DT>(v[u].r[x].w); vf[7] = cvt_hi<DT>(v[u].r[x].w);
+                    const float *pp = sh.p[i][4 * x + rg];
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const float p = pp[g];
+#pragma unroll
+                        for (int y = 0; y < 8; ++y) acc[g][y] = fmaf(p, vf[y], acc[g][y]);
+                    }
+                }
+            }
+        }
+    }
+    // sum the 4 row groups of the wave, then the 4 waves
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            float a = acc[g][x];
+            a += __shfl_xor(a, 16);
+            a += __shfl_xor(a, 32);
+            acc[g][x] = a;
+        }
+    if (rg == 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int x = 0; x < 8; ++x) sh.st_acc[wave][g][cl * 8 + x] = acc[g][x];
+    }
+    lds_barrier();
+    float *dst = ws.partial + ((size_t)s * ws.max_chunks + c) * G * kPartialStride;
+    for (int idx = tid; idx < G * kHeadDim; idx += 256) {
+        const int g = idx / kHeadDim, ch = idx % kHeadDim;
+        dst[g * kPartialStride + 4 + ch] =
+            (sh.st_acc[0][g][ch] + sh.st_acc[1][g][ch]) + (sh.st_acc[2][g][ch] + sh.st_acc[3][g][ch]);
+        if (ch == 0) { dst[g * kPartialStride] = sh.Mref[g]; dst[g * kPartialStride + 1] = sh.lsum[g]; }
+    }
+}
+
+// =================================================================================================
+// Finalize: out_g = sum over the chunks of the head's own prefix of the partial numerators, over
+// the sum of the partial exp-sums, both rescaled to one reference.
+// grid (S*G), 512 threads = 4 chunk lanes x 128 channels; chunk lane j takes chunks j, j+4, ...
+// =================================================================================================
+__global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, int G, int CB,
+                                                       float *__restrict__ out,
+                                                       int32_t *__restrict__ n_selected,
+                                                       float *__restrict__ mass_est,
+                                                       int32_t *__restrict__ blocks_read,
+                                                       int32_t *__restrict__ traffic_out) {
+    __shared__ float red[512];
+    __shared__ float wgt[1024];          // per-chunk rescale factor (max_chunks <= 1024)
+    __shared__ float den_part[512];
+    const int s = blockIdx.x / G, g = blockIdx.x % G, tid = threadIdx.x;
+    const int ch = tid & 127, cj = tid >> 7;
+    const int r = s / kv.num_kv_heads, h = s % kv.num_kv_heads;
+    int ctx = kv.ctx_lens[r];
+    ctx = ctx < 0 ? 0 : (ctx > kv.max_blocks * kPage ? kv.max_blocks * kPage : ctx);
+    const int N = (ctx + kPage - 1) / kPage;
+    const StreamCtl *ctl = &ws.ctl[s];
+    const unsigned long long st = ctl->stop[g];
+    int n = N;
+    float P = N > 0 ? 1.0f : 0.0f;
+    if (st != ~0ull && (int)(st >> 32) <= N) { n = (int)(st >> 32); P = __uint_as_float((uint32_t)st); }
+    const int nch = (n + CB - 1) / CB;
+    const float *src = ws.partial + ((size_t)s * ws.max_chunks * G + g) * kPartialStride;
+    const size_t stride = (size_t)G * kPartialStride;
+
+    // reference maximum over the chunks
+    float M = -INFINITY;
+    for (int i = tid; i < nch; i += 512) { const float mi = src[i * stride]; wgt[i] = mi; M = fmaxf(M, mi); }
+    red[tid] = M;
+    __syncthreads();
+    for (int d = 256; d >= 1; d >>= 1) {
+        if (tid < d) red[tid] = fmaxf(red[tid], red[tid + d]);
+        __syncthreads();
+    }
+    M = red[0];
+    __syncthreads();
+    // per-chunk weights and the denominator
+    float den = 0.0f;
+    for (int i = tid; i < nch; i += 512) {
+        const float mi = wgt[i];
+        const float w = (mi == -INFINITY || M == -INFINITY) ? 0.0f : exp2_fast(mi - M);
+        wgt[i] = w;
+        den += src[i * stride + 1] * w;
+    }
+    den_part[tid] = den;
+    __syncthreads();
+    for (int d = 256; d >= 1; d >>= 1) {
+        if (tid < d) den_part[tid] += den_part[tid + d];
+        __syncthreads();
+    }
+    den = den_part[0];
+    // numerator: channel ch, chunks cj, cj+4, ...
+    float num = 0.0f;
+    for (int i = cj; i < nch; i += 4) num = fmaf(src[i * stride + 4 + ch], wgt[i], num);
+    red[tid] = num;
+    __syncthreads();
+    if (tid < 128) {
+        num = (red[tid] + red[tid + 128]) + (red[tid + 256] + red[tid + 384]);
+        const size_t qi = (size_t)r * kv.num_q_heads + h * G + g;
+        out[qi * kHeadDim + ch] = den > 0.0f ? num / den : 0.0f;
+        if (ch == 0) {
+            n_selected[qi] = n;
+            mass_est[qi] = P;
+            if (g == 0) {
+                int mx = 0;
+                for (int x = 0; x < G; ++x) {
+                    const unsigned long long sx = ctl->stop[x];
+                    const int nx = (sx != ~0ull && (int)(sx >> 32) <= N) ? (int)(sx >> 32) : N;
+                    mx = max(mx, nx);
+                }
+                if (blocks_read) blocks_read[s] = mx;
+                if (traffic_out) { traffic_out[2 * s] = ctl->k_blocks; traffic_out[2 * s + 1] = mx; }
+            }
+        }
+    }
+}
+
+template <int DT, int G>
+static hipError_t launch_attend_t(const KvView &kv, const DecodeWs &ws, const DecodePlan &plan, hipStream_t st) {
+    attend_kernel<DT, G><<<dim3(plan.max_chunks, kv.batch * kv.num_kv_heads), 256, 0, st>>>(kv, ws, plan.chunk_blocks);
+    return hipGetLastError();
+}
+
+hipError_t launch_attend(const KvView &kv, int dtype, int G, const DecodeWs &ws, const DecodePlan &plan,
+                         hipStream_t st) {
+#define PSA_CASE(DT, GG) \
+    if (dtype == DT && G == GG) return launch_attend_t<DT, GG>(kv, ws, plan, st);
+    PSA_CASE(0, 1) PSA_CASE(0, 2) PSA_CASE(0, 4) PSA_CASE(0, 8)
+    PSA_CASE(1, 1) PSA_CASE(1, 2) PSA_CASE(1, 4) PSA_CASE(1, 8)
+#undef PSA_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_finalize(const KvView &kv, const DecodeWs &ws, int G, int CB, float *out,
+                           int32_t *n_selected, float *mass_est, int32_t *blocks_read,
+                           int32_t *traffic_out, hipStream_t st) {
+    finalize_kernel<<<kv.batch * kv.num_kv_heads * G, 512, 0, st>>>(kv, ws, G, CB, out, n_selected, mass_est,
+                                                                    blocks_read, traffic_out);
+    return hipGetLastError();
+}
+
+}  // namespace psa

@@ -131,3 +131,29 @@ def test_repeated_calls_are_bitwise_identical(psa, case):
     b = gc.run_gpu_decode(li, cfg.threshold, 1)
     assert torch.equal(a.out, b.out) and torch.equal(a.n_selected, b.n_selected)
     assert torch.equal(a.mass_est, b.mass_est) and torch.equal(a.order, b.order)
+
+
+def test_bucket_ranking_equals_bitonic_ranking(psa, case):
+    """The two ranking paths of the order kernel implement the same total order."""
+    name, cfg, li, pb = case
+    a = gc.run_gpu_decode(li, cfg.threshold, 1)
+    b = gc.run_gpu_decode(li, cfg.threshold, 1, tuning=psa.Tuning(force_bitonic=1))
+    assert torch.equal(a.order, b.order) and torch.equal(a.n_selected, b.n_selected)
+    assert torch.equal(a.out, b.out)
+
+
+def test_degenerate_scores_rank_by_block_index(psa):
+    """All keys equal: every score ties, the ranking must be the identity (ties go to the smaller
+    logical block) -- this drives the order kernel through its large-bucket fallback -- and the
+    result is plain attention over a prefix."""
+    cfg = get_config(3).scaled(batch=2, ctx=40000, layers=1)
+    li = generate_layer(cfg, device="cuda")
+    li.k_pool[...] = li.k_pool[0, 0, 0].clone()
+    pb = gc.to_problem(li)
+    gpu = gc.run_gpu_decode(li, 0.5, 1)
+    N = pb.num_blocks()
+    order = gpu.order.cpu().numpy()
+    for r in range(2):
+        assert np.array_equal(order[r, :, :N[r]], np.tile(np.arange(N[r]), (cfg.num_kv_heads, 1)))
+    rep = gc.check_decode_against_oracle(pb, gpu, 0.5, 1)
+    assert rep.set_equal + rep.stop_flips == rep.heads
