@@ -127,6 +127,7 @@ static int before(uint16_t a, uint16_t b, int dtype) { /* a strictly below b in 
 void oracle_block_metadata(const oracle_shape *sh, const uint16_t *k_pool, const int32_t *page_fill,
                            uint16_t *meta) {
     const int H = sh->num_kv_heads, T = sh->page_size, D = sh->head_dim;
+#pragma omp parallel for schedule(static)
     for (int p = 0; p < sh->num_pages; ++p) {
         int fill = page_fill ? page_fill[p] : T;
         if (fill > T) fill = T;
