@@ -19,7 +19,7 @@
  *     What the host can see is checked there (null required pointer, shapes, threshold outside
  *     [0,1] or NaN, check_granularity < 1, workspace too small).  What only the device can see
  *     (a block-table entry outside [0,num_pages), a context longer than max_blocks_per_seq pages,
- *     a negative context length, a bounded in-kernel wait that ran out) is clamped by the
+ *     a negative context length, an idle worker whose bounded polling ran out) is clamped by the
  *     kernels, which set a sticky bit in the workspace that psa_read_device_error returns.
  *   - Element type of Q, K, V and metadata: IEEE binary16 or bfloat16, 2 bytes.
  *   - Supported shapes: head_dim == 128, page_size == 16, num_q_heads / num_kv_heads in
@@ -50,7 +50,7 @@ typedef enum { PSA_F16 = 0, PSA_BF16 = 1 } psa_dtype;
 enum {
     PSA_DEVERR_PAGE_RANGE = 1,   /* block-table entry outside [0, num_pages): page 0 was used   */
     PSA_DEVERR_CTX_RANGE = 2,    /* ctx_len < 0 or > 16*max_blocks_per_seq: clamped             */
-    PSA_DEVERR_WAIT_EXPIRED = 4  /* a bounded in-kernel wait ran out: results are not reliable  */
+    PSA_DEVERR_WAIT_EXPIRED = 4  /* a worker's bounded polling ran out: results are not reliable */
 };
 
 /* Shapes and layout of ONE layer's paged KV cache (PagedAttention layout, Sec. 2.1 "KV Cache"). */
@@ -70,18 +70,19 @@ typedef struct {
 } psa_kv_desc;
 
 /* Tuning knobs of psa_decode_attention; all zero = library defaults.  They change how much is read
- * speculatively and how work is cut, never the result. */
+ * speculatively and how work is cut, never which blocks are selected. */
 typedef struct {
-    int32_t chunk_blocks;   /* ranked blocks per work item, 8..64 (default 32)                    */
-    int32_t window_chunks;  /* least number of work items of one (request, KV head) handed out past
-                               its resolved ones; the window grows to half the resolved count, at
-                               most 64 (default: from the number of streams)                      */
-    int32_t spin_limit;     /* polls before a bounded in-kernel wait gives up (default 1<<22)     */
-    int32_t force_bitonic;  /* 1: always rank with the bitonic network (testing); 0: automatic    */
+    int32_t chunk_blocks;   /* ranked blocks per work item: a multiple of 4 in 8..64 (default 32)      */
+    int32_t window_chunks;  /* least number of chunks of one (request, KV head) handed out beyond the
+                               chunks already folded into the stop rule; the window grows to half the
+                               folded count, at most 256 (default: from the number of streams)        */
+    int32_t spin_limit;     /* polls of a waiting workgroup before it gives up (default 1<<17)        */
+    int32_t force_bitonic;  /* 1: always rank with the bitonic network (testing); 0: automatic        */
+    int32_t workgroups;     /* workgroups of the persistent selection kernel (default 2 per CU)       */
     void *phase_events;     /* host pointer: NULL, or hipEvent_t[6] the call records on `stream`
                                before scoring and after each of its kernels: scoring, ranking,
                                selection (key pass), attention (value pass), final merge
-                               (profiling aid)                                                    */
+                               (profiling aid)                                                        */
 } psa_tuning;
 
 /* Bytes of workspace psa_decode_attention needs for this descriptor and tuning (NULL = defaults);

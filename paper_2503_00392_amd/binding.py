@@ -35,8 +35,8 @@ class _KvDesc(C.Structure):
 
 
 class _Tuning(C.Structure):
-    _fields_ = [("chunk_blocks", C.c_int32), ("window_chunks", C.c_int32),
-                ("spin_limit", C.c_int32), ("force_bitonic", C.c_int32), ("phase_events", C.c_void_p)]
+    _fields_ = [("chunk_blocks", C.c_int32), ("window_chunks", C.c_int32), ("spin_limit", C.c_int32),
+                ("force_bitonic", C.c_int32), ("workgroups", C.c_int32), ("phase_events", C.c_void_p)]
 
 
 @dataclass
@@ -45,11 +45,13 @@ class Tuning:
     window_chunks: int = 0
     spin_limit: int = 0
     force_bitonic: int = 0
+    workgroups: int = 0
     phase_events: object = None   # ctypes array of 6 hipEvent_t (c_void_p), or None
 
     def c(self) -> _Tuning:
         ev = C.cast(self.phase_events, C.c_void_p) if self.phase_events is not None else None
-        return _Tuning(self.chunk_blocks, self.window_chunks, self.spin_limit, self.force_bitonic, ev)
+        return _Tuning(self.chunk_blocks, self.window_chunks, self.spin_limit, self.force_bitonic,
+                       self.workgroups, ev)
 
 
 _lib = None

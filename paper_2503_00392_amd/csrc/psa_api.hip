@@ -76,12 +76,13 @@ psa_status psa_decode_attention(const psa_kv_desc *d, const void *q, const void 
     if (!(threshold >= 0.0f && threshold <= 1.0f)) return PSA_ERR_INVALID_ARG;   // also rejects NaN
     if (check_granularity < 1) return PSA_ERR_INVALID_ARG;
     if (d->max_blocks_per_seq > psa::kMaxBlocks) return PSA_ERR_UNSUPPORTED;
-    if (tuning && (tuning->chunk_blocks < 0 || tuning->window_chunks < 0 || tuning->spin_limit < 0))
-        return PSA_ERR_INVALID_ARG;
-    if (tuning && (tuning->force_bitonic < 0 || tuning->force_bitonic > 1)) return PSA_ERR_INVALID_ARG;
-    if (tuning && tuning->chunk_blocks != 0 &&
-        (tuning->chunk_blocks < 8 || tuning->chunk_blocks > psa::kMaxChunkBlocks))
-        return PSA_ERR_INVALID_ARG;
+    if (tuning) {
+        const int cb = tuning->chunk_blocks;
+        if (cb != 0 && (cb < 8 || cb > psa::kMaxChunkBlocks || cb % 4 != 0)) return PSA_ERR_INVALID_ARG;
+        if (tuning->window_chunks < 0 || tuning->spin_limit < 0 || tuning->workgroups < 0)
+            return PSA_ERR_INVALID_ARG;
+        if (tuning->force_bitonic < 0 || tuning->force_bitonic > 1) return PSA_ERR_INVALID_ARG;
+    }
     if (d->batch == 0) return PSA_OK;
     if (!q || !out || !n_selected || !mass_est || !workspace) return PSA_ERR_INVALID_ARG;
     if (d->num_pages > 0 && !meta) return PSA_ERR_INVALID_ARG;

@@ -1,5 +1,5 @@
 // Host side of psa_decode_attention: workspace layout, launch plan and the kernel sequence
-//   clear -> score (Algorithm 1 line 5) -> order (line 6) -> select (lines 7-18, key side) ->
+//   score (Algorithm 1 line 5) -> order (line 6) -> select (lines 7-18, key side and stop rule) ->
 //   attend (value side of lines 10-12) -> finalize (line 19),
 // all enqueued on one stream with no host involvement in between.
 #include "psa_host.h"
@@ -25,17 +25,15 @@ DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t) {
     DecodePlan p;
     const int S = d->batch * d->num_kv_heads;
     p.chunk_blocks = (t && t->chunk_blocks) ? t->chunk_blocks : 32;
-    if (p.chunk_blocks < 8) p.chunk_blocks = 8;
-    if (p.chunk_blocks > kMaxChunkBlocks) p.chunk_blocks = kMaxChunkBlocks;
-    p.persistent_wgs = compute_units() * 2;   // 512-thread workgroups, two per CU
+    p.persistent_wgs = (t && t->workgroups > 0) ? t->workgroups : compute_units() * 2;   // 512-thread workgroups
     if (t && t->window_chunks > 0) {
         p.window_chunks = t->window_chunks;
     } else {
-        // half of the workgroups the persistent grid has per stream: the window grows from there
-        int w = p.persistent_wgs / (2 * (S > 0 ? S : 1));
-        p.window_chunks = w < 2 ? 2 : (w > 16 ? 16 : w);
+        // about 48 MiB of key slices in flight over all streams, 2 to 32 chunks per stream
+        const long long per_stream = (48ll << 20) / ((long long)(S > 0 ? S : 1) * p.chunk_blocks * kSliceBytes);
+        p.window_chunks = per_stream < 2 ? 2 : (per_stream > 32 ? 32 : (int)per_stream);
     }
-    p.spin_limit = (t && t->spin_limit > 0) ? t->spin_limit : (1 << 22);
+    p.spin_limit = (t && t->spin_limit > 0) ? t->spin_limit : (1 << 17);
     p.max_chunks = (d->max_blocks_per_seq + p.chunk_blocks - 1) / p.chunk_blocks;
     if (p.max_chunks < 1) p.max_chunks = 1;
     p.force_bitonic = t ? t->force_bitonic : 0;
@@ -44,7 +42,7 @@ DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t) {
 }
 
 struct WsLayout {
-    size_t header, ctl, scores, order, ranked_page, agg, logits, partial, total;
+    size_t header, ctl, scores, order, ranked_page, agg, block_lse, logits, partial, total;
 #ifdef PSA_ENABLE_TRACE
     size_t trace;
 #endif
@@ -62,10 +60,11 @@ static WsLayout layout(const psa_kv_desc *d, const DecodePlan &p) {
     L.order = at;       at = align_up(at + S * MB * 4, 256);
     L.ranked_page = at; at = align_up(at + S * MB * 4, 256);
     L.agg = at;         at = align_up(at + S * p.max_chunks * G * 8, 256);
+    L.block_lse = at;   at = align_up(at + S * MB * G * 4, 256);
     L.logits = at;      at = align_up(at + S * MB * kPage * G * 4, 256);
     L.partial = at;     at = align_up(at + S * p.max_chunks * G * kPartialStride * 4, 256);
 #ifdef PSA_ENABLE_TRACE
-    L.trace = at;       at = align_up(at + (size_t)(1 + kTraceRecords) * 64, 256);
+    L.trace = at;       at = align_up(at + (size_t)(2 + kTraceRecords) * 32, 256);
 #endif
     L.total = at;
     return L;
@@ -90,22 +89,23 @@ hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const Decode
     ws.order = reinterpret_cast<int32_t *>(base + L.order);
     ws.ranked_page = reinterpret_cast<int32_t *>(base + L.ranked_page);
     ws.agg = reinterpret_cast<unsigned long long *>(base + L.agg);
+    ws.block_lse = reinterpret_cast<float *>(base + L.block_lse);
     ws.logits = reinterpret_cast<float *>(base + L.logits);
     ws.partial = reinterpret_cast<float *>(base + L.partial);
     ws.max_chunks = plan.max_chunks;
+    ws.max_units = plan.max_chunks;
 #ifdef PSA_ENABLE_TRACE
     ws.trace = reinterpret_cast<unsigned long long *>(base + L.trace);
-    clear_words_kernel<<<1, 64, 0, st>>>(reinterpret_cast<int32_t *>(ws.trace), 2);
+    (void)hipMemsetAsync(ws.trace, 0, (size_t)(2 + kTraceRecords) * 32, st);
 #endif
     const int G = d->num_q_heads / d->num_kv_heads;
     if (kv.batch == 0) return hipSuccess;
     hipEvent_t *ev = plan.events;
     hipError_t e;
-    clear_words_kernel<<<1, 64, 0, st>>>(ws.header, 64);
     if (ev) (void)hipEventRecord(ev[0], st);
     if ((e = launch_score(kv, d->dtype, G, a.q, a.meta, ws, a.scores_out, st)) != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);
-    if ((e = launch_order(kv, ws, G, plan.force_bitonic, a.order_out, st)) != hipSuccess) return e;
+    if ((e = launch_order(kv, ws, G, plan.chunk_blocks, plan.force_bitonic, a.order_out, st)) != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[2], st);
     if ((e = launch_select(kv, d->dtype, G, a.q, ws, a.threshold, a.check_granularity, plan, st)) != hipSuccess)
         return e;

@@ -14,7 +14,7 @@ constexpr int kRowBytes = 256;    // one token's key (or value) for one head
 constexpr int kSliceBytes = 4096; // one (page, KV head) K or V slice
 constexpr int kMetaBytes = 512;   // one (page, KV head) metadata record: min[128] | max[128]
 constexpr int kMaxBlocks = 8192;  // ranking limit per request (128K tokens)
-constexpr int kMaxChunkBlocks = 64;
+constexpr int kMaxChunkBlocks = 64;   // key chunk and value unit, in blocks, at most
 
 // 1/sqrt(128) * log2(e): logits are carried in log2 units so that exp is one v_exp_f32.
 constexpr float kScaleLog2 = 0.08838834764831845f * 1.4426950408889634f;
@@ -31,14 +31,35 @@ struct KvView {
 };
 
 // ---- workspace of psa_decode_attention -----------------------------------------------------
-// Per-stream control block ("stream" = one (request, KV head) pair).
+// "Stream" = one (request, KV head) pair: one ranking, G query heads.
+// "Chunk" = `CB` consecutive ranked blocks: the unit in which keys are read and folded into the
+// stop rule, and in which values are read.
+//
+// Per-stream control block of the progressive kernel: four 128-byte lines, so that the two ticket
+// counters, the progress words that waiting waves poll, and the fold's own state never share a
+// cache line (accesses to one line are served one after the other).
+constexpr int32_t kUnknownTotal = 0x7fffffff;
 struct alignas(128) StreamCtl {
-    int32_t next_chunk;   // ticket: next chunk of this stream to hand out
-    int32_t done_chunk;   // smallest chunk index in which every head of the group had stopped
-    int32_t resolved;     // chunks of this stream that have evaluated the stop rule
-    int32_t k_blocks;     // K blocks loaded (traffic accounting)
-    int32_t pad[4];
-    unsigned long long stop[8];  // per head: (n << 32) | float bits of P_acc, minimum over chunks
+    // line 0: key tickets
+    int32_t k_next;     // next key chunk to hand out (fetch-and-add)
+    int32_t pad0[31];
+    // line 1: progress, written by the folding wave only, each as ONE 64-bit store
+    unsigned long long key_progress;    // low: frontier = key chunks folded into the stop rule so far;
+                                        // high: k_limit = key chunks worth reading (all of them until the
+                                        // fold has finished, then what it used)
+    unsigned long long value_progress;  // low: v_avail = value units released so far;
+                                        // high: v_total = value units of the stream, kUnknownTotal until
+                                        // every head has stopped or the blocks ran out
+    int32_t pad1[28];
+    // line 2: value tickets
+    int32_t v_next;     // next value unit to hand out (compare-and-swap, never beyond v_avail)
+    int32_t k_blocks;   // key slices loaded (traffic accounting)
+    int32_t attached;   // waves working on this stream beyond its first ones (joiners)
+    int32_t pad2[29];
+    // line 3: fold state, owned by the folding wave
+    float Lacc[8];               // per head: log2 of AS_acc over the folded chunks
+    float Lmin[8];               // per head: log2 of AS_min over the folded chunks
+    unsigned long long stop[8];  // per head: (n << 32) | float bits of P_acc at the stop; ~0 = not stopped
 };
 
 struct DecodeWs {
@@ -48,21 +69,25 @@ struct DecodeWs {
     int32_t *order;         // [S][max_blocks]  ranked logical blocks
     int32_t *ranked_page;   // [S][max_blocks]  physical page of each ranked block
     unsigned long long *agg;  // [S][max_chunks][G]  (L_chunk, Lmin_chunk) as two floats, or the NaN sentinel
+    float *block_lse;       // [S][max_blocks][G]  log2 of each ranked block's AS (Algorithm 1 line 10)
     float *logits;          // [S][max_blocks][G][16]  scaled logits (log2 units) by ranked block
     float *partial;         // [S][max_chunks][G][kPartialStride]
-    int32_t max_chunks;
+    int32_t max_chunks;     // chunks per stream at most
+    int32_t max_units;      // = max_chunks (stride of `partial`)
 #ifdef PSA_ENABLE_TRACE
-    unsigned long long *trace;   // [0] record count, then 8 words per processed chunk (tuning aid)
+    unsigned long long *trace;   // [0] record count, then 4 words per record (tuning aid)
 #endif
 };
 #ifdef PSA_ENABLE_TRACE
-constexpr int kTraceRecords = 1 << 16;
-#define PSA_TRACE_STAMP(var) const unsigned long long var = wall_clock64()
-#else
-#define PSA_TRACE_STAMP(var)
+constexpr int kTracePerWave = 96;
+constexpr int kTraceRecords = 4096 * kTracePerWave;   // up to 4096 waves
 #endif
 constexpr int kPartialStride = 132;  // M, l, pad, pad, acc[128]
-constexpr unsigned long long kAggSentinel = 0xFFFFFFFFFFFFFFFFull;  // both halves NaN: never a value
+// A chunk word holds (L_chunk, Lmin_chunk) as two floats once the chunk is published.  Before that
+// it holds one of two NaN patterns no computation produces: "not published", or -- word 0 only --
+// "not published, and the fold stopped here": whoever publishes over that one carries on folding.
+constexpr unsigned long long kAggSentinel = 0xFFFFFFFFFFFFFFFFull;
+constexpr unsigned long long kAggArmed = 0xFFFFFFFFFFFFFFFEull;
 
 __device__ __forceinline__ void set_error(int32_t *header, int bit) { atomicOr(&header[1], bit); }
 
@@ -176,6 +201,14 @@ __device__ __forceinline__ int ctx_clamped(const KvView &kv, int r, int32_t *hea
     if (ctx < 0) { set_error(header, PSA_DEVERR_CTX_RANGE); ctx = 0; }
     if (ctx > kv.max_blocks * kPage) { set_error(header, PSA_DEVERR_CTX_RANGE); ctx = kv.max_blocks * kPage; }
     return ctx;
+}
+
+__device__ __forceinline__ int ctx_clamped_quiet(const KvView &kv, int r) {
+    const int ctx = kv.ctx_lens[r];
+    return ctx < 0 ? 0 : (ctx > kv.max_blocks * kPage ? kv.max_blocks * kPage : ctx);
+}
+__device__ __forceinline__ int clamp_page_quiet(int page, int num_pages) {
+    return (unsigned)page >= (unsigned)num_pages ? 0 : page;
 }
 
 }  // namespace psa

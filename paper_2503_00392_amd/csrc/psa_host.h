@@ -38,7 +38,7 @@ hipError_t launch_metadata(const psa_kv_desc *d, void *meta, const int32_t *page
 
 // psa_decode.hip
 struct DecodePlan {
-    int chunk_blocks;
+    int chunk_blocks;     // CB: ranked blocks per chunk (keys and values alike)
     int window_chunks;
     int spin_limit;
     int max_chunks;
@@ -65,13 +65,13 @@ hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const Decode
 // psa_score.hip, psa_order.hip, psa_select.hip, psa_values.hip: the kernels of one decode call
 hipError_t launch_score(const KvView &kv, int dtype, int G, const void *q, const void *meta,
                         const DecodeWs &ws, float *scores_out, hipStream_t st);
-hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int force_bitonic,
+hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int KU, int force_bitonic,
                         int32_t *order_out, hipStream_t st);
 hipError_t launch_select(const KvView &kv, int dtype, int G, const void *q, const DecodeWs &ws, float eps,
                          int m, const DecodePlan &plan, hipStream_t st);
 hipError_t launch_attend(const KvView &kv, int dtype, int G, const DecodeWs &ws, const DecodePlan &plan,
                          hipStream_t st);
-hipError_t launch_finalize(const KvView &kv, const DecodeWs &ws, int G, int CB, float *out,
+hipError_t launch_finalize(const KvView &kv, const DecodeWs &ws, int G, int VU, float *out,
                            int32_t *n_selected, float *mass_est, int32_t *blocks_read,
                            int32_t *traffic_out, hipStream_t st);
 

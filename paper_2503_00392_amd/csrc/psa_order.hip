@@ -14,7 +14,8 @@
 // to a bitonic network over 64-bit (key, index) words: compare distances below 8 stay in registers,
 // below 512 go through wave shuffles, the rest through LDS.  Both paths give the same total order.
 //
-// The kernel also resets the stream's control block and chunk aggregates for the progressive kernel.
+// The kernel also resets the stream's control block and chunk words for the progressive kernel and
+// reports out-of-range contexts and block-table entries.
 // grid (S), Np/8 threads, Np*8 bytes of dynamic LDS; Np = power of two >= max(512, max_blocks).
 #include <limits.h>
 
@@ -88,26 +89,30 @@ __device__ void bitonic_sort(unsigned long long (&e)[8], unsigned long long *lds
     }
 }
 
-__global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int G, int Np,
+__global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int G, int KU, int Np,
                                                       int force_bitonic,
                                                       int32_t *__restrict__ order_out) {
     extern __shared__ unsigned long long lds_raw[];
     const int s = blockIdx.x, r = s / kv.num_kv_heads;
     const int tid = threadIdx.x, nthreads = blockDim.x, lane = tid & 63, wave = tid >> 6;
     const int nwaves = nthreads >> 6;
-    int ctx = kv.ctx_lens[r];
-    ctx = ctx < 0 ? 0 : (ctx > kv.max_blocks * kPage ? kv.max_blocks * kPage : ctx);
+    // the scoring kernel clamps silently (it clears the error word); out-of-range inputs are reported here
+    const int ctx = (tid == 0) ? ctx_clamped(kv, r, ws.header) : ctx_clamped_quiet(kv, r);
     const int N = (ctx + kPage - 1) / kPage;
 
     // ---- reset of the progressive kernel's per-stream state ------------------------------------
     if (tid == 0) {
         StreamCtl *c = &ws.ctl[s];
-        c->next_chunk = 0; c->done_chunk = INT_MAX; c->resolved = 0; c->k_blocks = 0;
-        for (int g = 0; g < 8; ++g) c->stop[g] = ~0ull;
+        const unsigned nch = (unsigned)((N + KU - 1) / KU);
+        c->k_next = 0; c->v_next = 0; c->k_blocks = 0; c->attached = 0;
+        c->key_progress = (unsigned long long)nch << 32;                                  // frontier 0
+        c->value_progress = (unsigned long long)(N == 0 ? 0u : (unsigned)kUnknownTotal) << 32;   // nothing released
+        for (int g = 0; g < 8; ++g) { c->Lacc[g] = -INFINITY; c->Lmin[g] = INFINITY; c->stop[g] = ~0ull; }
     }
     {
         unsigned long long *a = ws.agg + (size_t)s * ws.max_chunks * G;
-        for (int i = tid; i < ws.max_chunks * G; i += nthreads) a[i] = kAggSentinel;
+        // chunk 0 starts out as the place where the fold waits: its publisher starts folding
+        for (int i = tid; i < ws.max_chunks * G; i += nthreads) a[i] = (i == 0) ? kAggArmed : kAggSentinel;
     }
 
     // LDS carve-up of the bucket path (7*Np bytes + scratch in the last Np bytes)
@@ -230,12 +235,12 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         for (int p = N + tid; p < kv.max_blocks; p += nthreads) oout[p] = -1;
 }
 
-hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int force_bitonic,
+hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int KU, int force_bitonic,
                         int32_t *order_out, hipStream_t st) {
     const int S = kv.batch * kv.num_kv_heads;
     int Np = 512;
     while (Np < kv.max_blocks) Np <<= 1;
-    order_kernel<<<S, Np / 8, (size_t)Np * 8, st>>>(kv, ws, G, Np, force_bitonic, order_out);
+    order_kernel<<<S, Np / 8, (size_t)Np * 8, st>>>(kv, ws, G, KU, Np, force_bitonic, order_out);
     return hipGetLastError();
 }
 

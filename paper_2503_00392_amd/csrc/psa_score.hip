@@ -18,7 +18,10 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
     const int s = blockIdx.y, r = s / kv.num_kv_heads, h = s % kv.num_kv_heads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, row = lane >> 4, cl = lane & 15;
     const int is_max = cl >> 3, slot = cl & 7;
-    const int ctx = ctx_clamped(kv, r, header);
+    // first kernel of a decode call: it clears the sticky error word and clamps silently; the
+    // ranking kernel, which sees the same table entries and contexts, reports them
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 2) header[threadIdx.x] = 0;
+    const int ctx = ctx_clamped_quiet(kv, r);
     const int N = (ctx + kPage - 1) / kPage;
     const int base = blockIdx.x * 64 + wave * 16;
     if (base >= N) return;
@@ -43,7 +46,7 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
     for (int it = 0; it < 4; ++it) {
         const int b = base + it * 4 + row;
         if (b < N) {
-            const int page = clamp_page(table[b], kv.num_pages, header);
+            const int page = clamp_page_quiet(table[b], kv.num_pages);
             const uint8_t *mp = meta + ((size_t)page * kv.num_kv_heads + h) * kMetaBytes + is_max * 256 + slot * 32;
             ma[it] = ld16(mp);
             mb[it] = ld16(mp + 16);

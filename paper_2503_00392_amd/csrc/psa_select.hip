@@ -2,130 +2,264 @@
 // blocks, computes the exact scaled logits q.k/sqrt(d) of each block from its key slice, keeps them
 // for the value pass, and decides on the GPU where every query head stops.
 //
-// A "stream" is one (request, KV head) pair: one ranking, G query heads.  A "chunk" is `CB`
-// consecutive ranked blocks of a stream, the unit of work of a workgroup.
+// Terms.  "Stream": one (request, KV head) pair -- one ranking, G query heads.  "Chunk": CB
+// consecutive ranked blocks, the unit of work of a workgroup.
 //
-// Work distribution: a persistent grid of workgroups.  Each stream hands out its chunks in order
-// through an atomic ticket of its own, so whoever holds chunk c knows that every earlier chunk of
-// that stream is held by a workgroup that is running or has finished: waiting on earlier chunks
-// cannot deadlock, whatever the number of resident workgroups.  A workgroup stays with a stream
-// while that stream has chunks to hand out inside its read-ahead window, and otherwise moves on,
-// round-robin, to the next stream that has; it leaves when no stream has anything left.
-// The window -- chunks handed out beyond the resolved ones -- is max(window_chunks, resolved/2),
-// at most 64: it bounds the keys read beyond the stop to a fixed amount for streams that stop early
-// and to a fraction of what was needed for streams that go deep.
-//
-// For one chunk, a workgroup (8 waves)
-//   1. reads its blocks' key slices (each wave keeps 4 slices = 16 KiB in flight), computes the
+// A persistent grid of workgroups (8 waves each).  A workgroup attached to a stream repeats:
+//   1. take the stream's next chunk ticket (fetch-and-add), but only while the read-ahead window
+//      is open -- chunks handed out beyond the fold's frontier are at most max(window, frontier/2),
+//      256 at most, which bounds the keys read beyond the stop;
+//   2. read the chunk's key slices (each wave keeps 4 slices = 16 KiB in flight), compute the
 //      scaled logits of all G heads as a 16-token x 16-head x 128-channel product on the matrix
-//      cores (heads beyond G are zero columns), writes them to the workspace, and reduces each
+//      cores (heads beyond G are zero columns), store them for the value pass, and reduce each
 //      block's log-sum-exp L_b (= log AS of line 10);
-//   2. publishes the chunk's aggregate (log-sum-exp and minimum of its L_b) as one 64-bit word per
-//      head, then reads the aggregates of all earlier chunks and folds them in a fixed order into
-//      the exclusive prefix (AS_acc, AS_min of lines 12-13 at the chunk's first block);
-//   3. scans its own blocks to get P_acc (lines 15-16) at every position it owns, finds the first
-//      admissible position with P_acc > eps (line 17) per head and records it with a 64-bit
-//      atomic minimum; the global minimum over chunks is the head's stop.
-// Every wait is bounded by `spin_limit` polls; running out marks the stream finished, sets the
-// sticky error bit and lets every workgroup leave.
+//   3. publish the chunk's (log-sum-exp, minimum) of L_b per head as one 64-bit word per head.
+// THE FOLD applies lines 12-17 strictly in rank order: AS_acc, AS_min, N_left and P_acc at the end
+// of each published chunk after the frontier and, in the first chunk where P_acc exceeds the
+// threshold, block by block to find the head's exact stop.  It is a token: exactly one wave at a
+// time folds.  When it reaches a chunk that is not yet published it marks that chunk's word "the
+// fold waits here" and its workgroup goes back to key work; the workgroup that later publishes over
+// the mark (an atomic exchange tells it) picks the fold up from the state left in the control
+// block.  So no workgroup ever waits for another one, nobody polls for the fold, nothing is locked.
+// Once every head has stopped (or the blocks ran out) the fold closes the stream: tickets beyond
+// what it used are dropped.  A workgroup whose stream has handed out all its chunks joins another
+// stream that still has some (a bounded number of joiners per stream), or leaves.
 //
-// Every reduction has a fixed order, so results are bitwise reproducible although the scheduling
-// is dynamic.
+// Communication between workgroups: every shared word is read and written with relaxed agent-scope
+// atomics (coherent accesses); a writer waits for its data stores to complete before it stores the
+// word that announces them (chunk word 0, the progress words, the fold mark), and a reader looks at
+// the announcing word before it issues the loads that depend on it.  Accesses to one cache line are
+// served one at a time (tens of nanoseconds each), which is why one thread per workgroup touches the
+// stream's control block about once per chunk and the fold hand-over goes through the chunks' own
+// words.  The logits are plain stores: their reader is the next kernel.
+//
+// Every fold is sequential in rank order and every reduction has a fixed shape, so results are
+// bitwise reproducible although the scheduling is dynamic.
 #include <limits.h>
 
-#include "psa_attend.h"
 #include "psa_host.h"
 
 namespace psa {
 
+// ---- agent-scope atomics ---------------------------------------------------------------------
 __device__ __forceinline__ int ld_relaxed(const int32_t *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ unsigned long long ld_relaxed(const unsigned long long *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ float ld_relaxed(const float *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_relaxed(int32_t *p, int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ void st_relaxed(unsigned long long *p, unsigned long long v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ void st_relaxed(float *p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Every word one wave writes and another reads inside this kernel travels through the relaxed
+// agent-scope atomics above (cache-coherent accesses), never through plain loads and stores, so no
+// cache write-back or invalidation is ever needed.  What remains is ORDER: a wave's earlier
+// stores must have completed before the store that announces them is issued.
+__device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ unsigned long long pack2(float a, float b) {
     return ((unsigned long long)__float_as_uint(b) << 32) | __float_as_uint(a);
 }
+__device__ __forceinline__ unsigned long long shfl_u64(unsigned long long v, int src) {
+    const int lo = __shfl((int)(v & 0xffffffffull), src);
+    const int hi = __shfl((int)(v >> 32), src);
+    return ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo;
+}
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 constexpr int kBatch = 4;            // key slices a wave keeps in flight
 constexpr int kSelectThreads = 512;  // 8 waves: a 32-block chunk is one batch per wave
+constexpr int kMaxWindow = 256;      // chunks handed out beyond the frontier, at most
+constexpr int kMaxJoiners = 32;      // workgroups that may join a stream beyond its first ones
 
+// Tokens of stream s's request, clamped like everywhere else.
+__device__ __forceinline__ int stream_ctx(const KvView &kv, int s) {
+    const int ctx = kv.ctx_lens[s / kv.num_kv_heads];
+    return ctx < 0 ? 0 : (ctx > kv.max_blocks * kPage ? kv.max_blocks * kPage : ctx);
+}
 
-#ifdef PSA_ENABLE_TRACE
-// One record per processed chunk: ids, then 100 MHz timestamps of begin / K done / resolved.
-#define PSA_TRACE_EMIT(CNT)                                                                  \
-    if (threadIdx.x == 0) {                                                                  \
-        const unsigned long long slot_ = atomicAdd(ws.trace, 1ull);                          \
-        if (slot_ < (unsigned long long)kTraceRecords) {                                     \
-            unsigned long long *rec_ = ws.trace + 8 + slot_ * 8;                             \
-            rec_[0] = ((unsigned long long)s << 32) | (unsigned)c;                           \
-            rec_[1] = ((unsigned long long)blockIdx.x << 32) | (unsigned)(CNT);              \
-            rec_[2] = t_begin; rec_[3] = t_kdone; rec_[4] = wall_clock64(); rec_[5] = rec_[4]; \
-        }                                                                                    \
-    }
-#else
-#define PSA_TRACE_EMIT(CNT)
-#endif
+__device__ __forceinline__ int window_of(int window, int frontier) {
+    const int w = max(window, frontier >> 1);
+    return w > kMaxWindow ? kMaxWindow : w;
+}
+
+// P_acc of Algorithm 1 lines 15-16 in the log2 domain: AS_acc / (AS_acc + AS_min * N_left).
+__device__ __forceinline__ float p_acc(float Lacc, float Lmin, int n_left) {
+    return 1.0f / (1.0f + (float)n_left * exp2_fast(Lmin - Lacc));
+}
+
+__device__ __forceinline__ void nap(int tries) {
+    // grows from about half a microsecond to about twelve
+    __builtin_amdgcn_s_sleep(20);
+    if (tries > 1) __builtin_amdgcn_s_sleep(60);
+    if (tries > 3) __builtin_amdgcn_s_sleep(127);
+    if (tries > 6) { __builtin_amdgcn_s_sleep(127); __builtin_amdgcn_s_sleep(127); }
+}
 
 template <int G>
 struct SelectShared {
     float Lb[kMaxChunkBlocks][G];          // per-block log2-sum-exp2
     int page[kMaxChunkBlocks];
     int valid[kMaxChunkBlocks];
-    int cnt[G];
-    int stopped[G];
-    int w_first[8];
-    int w_busy[8];
-    int chunk;
-    int state;
-    int abort_flag;
+    int what;                              // 0: chunk `item`; 2: nothing right now; 3: all handed out; 4: give up
+    int item;
+    int next;                              // stream to join, -1 = leave
 };
 
-// Blocks of stream s's request, clamped like everywhere else.
-__device__ __forceinline__ int stream_ctx(const KvView &kv, int s) {
-    int ctx = kv.ctx_lens[s / kv.num_kv_heads];
-    return ctx < 0 ? 0 : (ctx > kv.max_blocks * kPage ? kv.max_blocks * kPage : ctx);
+// =================================================================================================
+// The fold (Algorithm 1 lines 12-18 in rank order).  Called by wave 0 of the workgroup that
+// published over the fold mark.  Lane g < G carries head g: (L_acc, L_min) over the folded chunks and the head's stop.
+// Leaves either with the stream's key side closed, or with the mark on the first unpublished chunk.
+// =================================================================================================
+template <int G>
+__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU) {
+    const int lane = threadIdx.x & 63;
+    StreamCtl *ctl = &ws.ctl[s];
+    const int ctx = stream_ctx(kv, s);
+    const int N = (ctx + kPage - 1) / kPage;
+    const int nch = (N + KU - 1) / KU;
+    int fr = uniform((int)(ld_relaxed(&ctl->key_progress) & 0xffffffffull));
+    int fr_pub = fr;                           // frontier as the progress word shows it
+    float Lacc = -INFINITY, Lmin = INFINITY;
+    unsigned long long stop = 0ull;            // lanes >= G count as stopped
+    if (lane < G) {
+        Lacc = ld_relaxed(&ctl->Lacc[lane]);
+        Lmin = ld_relaxed(&ctl->Lmin[lane]);
+        stop = ld_relaxed(&ctl->stop[lane]);
+    }
+    constexpr int CPR = 64 / G;                // chunks per load round: lane = (chunk j, head)
+    const unsigned long long *agg = ws.agg + (size_t)s * ws.max_chunks * G;
+    const int hg = lane < G ? lane : 0;
+    bool finished = false;
+    int walked = fr;
+    while (!finished) {
+        unsigned long long v[4];
+        int k = 0;
+        bool gap = false;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int ci = fr + u * CPR + lane / G;
+            v[u] = (ci < nch) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const unsigned long long pub = __ballot(v[u] < kAggArmed);
+            const int ones = (pub == ~0ull) ? 64 : (__ffsll((long long)~pub) - 1);
+            const int ku = ones / G;           // leading chunks of this round with all G words published
+            if (!gap) k += ku;
+            if (ku < CPR) gap = true;
+        }
+        if (k > 0) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            for (int j = 0; j < CPR; ++j) {
+                const int i = u * CPR + j;
+                if (i >= k || finished) break;
+                const unsigned long long a = shfl_u64(v[u], j * G + hg);
+                if (stop == ~0ull) {
+                    const float L2 = lse2(Lacc, __uint_as_float((uint32_t)(a & 0xffffffffull)));
+                    const float M2 = fminf(Lmin, __uint_as_float((uint32_t)(a >> 32)));
+                    const int cidx = fr + i;
+                    const int n_end = min((cidx + 1) * KU, N);
+                    if (p_acc(L2, M2, N - n_end) > eps) {
+                        // the stop may lie in this chunk: block by block, in rank order
+                        const int b0 = cidx * KU;
+                        const float *lb = ws.block_lse + ((size_t)s * kv.max_blocks + b0) * G + lane;
+                        float fl = Lacc, fm = Lmin;
+                        for (int t = 0; t < n_end - b0; ++t) {
+                            const float Lb = ld_relaxed(&lb[(size_t)t * G]);
+                            fl = lse2(fl, Lb);
+                            fm = fminf(fm, Lb);
+                            const int nn = b0 + t + 1;
+                            if (nn % m == 0 || nn == N) {
+                                const float P = p_acc(fl, fm, N - nn);
+                                if (P > eps) {
+                                    stop = ((unsigned long long)nn << 32) | __float_as_uint(P);
+                                    break;
+                                }
+                            }
+                        }
+                    }
+                    Lacc = L2;
+                    Lmin = M2;
+                }
+                walked = fr + i + 1;
+                if (__ballot(stop == ~0ull) == 0ull) finished = true;
+            }
+        }
+        }
+        fr = walked;
+        if (fr >= nch) finished = true;
+        if (finished) break;
+        // leave the state and the progress words behind: waiting key workers and value workers move on
+        if (lane < G) {
+            st_relaxed(&ctl->Lacc[lane], Lacc);
+            st_relaxed(&ctl->Lmin[lane], Lmin);
+            st_relaxed(&ctl->stop[lane], stop);
+        }
+        stores_done();
+        if (lane == 0 && walked != fr_pub) {
+            st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)nch << 32) | (unsigned)walked);
+            st_relaxed(&ctl->value_progress,
+                       ((unsigned long long)(unsigned)kUnknownTotal << 32) | (unsigned)(walked));
+        }
+        fr_pub = walked;
+        if (!gap) continue;            // all 4 rounds were published: load the next ones
+        // chunk fr is not published: mark it; if it was published meanwhile the mark fails and the
+        // fold simply carries on
+        stores_done();
+        unsigned long long seen = 0;
+        if (lane == 0) {
+            unsigned long long expected = kAggSentinel;
+            __hip_atomic_compare_exchange_strong(const_cast<unsigned long long *>(&agg[(size_t)fr * G]), &expected,
+                                                 kAggArmed, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+            seen = expected;
+        }
+        if (uniform((int)(seen == kAggSentinel))) return;     // marked: the chunk's publisher carries on
+    }
+    // every head has stopped, or the blocks ran out: close the key side, release the last value units
+    if (lane < G) st_relaxed(&ctl->stop[lane], stop);
+    int nmax = (lane < G) ? ((stop == ~0ull) ? N : (int)(stop >> 32)) : 0;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) nmax = max(nmax, __shfl_xor(nmax, d));
+    const int vt = (nmax + KU - 1) / KU;
+    stores_done();
+    if (lane == 0) {
+        st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)walked << 32) | (unsigned)walked);
+        st_relaxed(&ctl->value_progress, ((unsigned long long)(unsigned)vt << 32) | (unsigned)vt);
+    }
 }
 
-// 0: stream s can hand out a chunk now; 1: it is at its read-ahead window; 2: nothing left to do.
-// The window grows with the stream's progress: max(window, resolved/2), at most 64 chunks.
-__device__ __forceinline__ int classify_stream(const KvView &kv, const DecodeWs &ws, int s, int CB,
-                                               int window) {
-    const int N = (stream_ctx(kv, s) + kPage - 1) / kPage;
-    const int nch = (N + CB - 1) / CB;
-    const StreamCtl *ctl = &ws.ctl[s];
-    const int nx = ld_relaxed(&ctl->next_chunk);
-    if (nx >= nch || nx > ld_relaxed(&ctl->done_chunk)) return 2;
-    const int res = ld_relaxed(&ctl->resolved);
-    int w = max(window, res >> 1);
-    w = w > 64 ? 64 : w;
-    if (nx >= res + w) return 1;
-    return 0;
-}
-
+// =================================================================================================
+// Key work of one workgroup: chunk c of stream s.  Ends with the chunk published; wave 0 carries
+// the fold on if it was waiting for this chunk.
+// =================================================================================================
 template <int DT, int G>
 __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8_t *__restrict__ q,
-                              const DecodeWs &ws, float eps, int m, int CB, int spin_limit, int s, int c) {
+                              const DecodeWs &ws, float eps, int m, int CB, int s, int c) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = s / kv.num_kv_heads, h = s % kv.num_kv_heads;
     const int ctx = stream_ctx(kv, s);
     const int N = (ctx + kPage - 1) / kPage;
     const int start = c * CB;
     const int nblk = min(CB, N - start);
-    StreamCtl *ctl = &ws.ctl[s];
+    const size_t row0 = (size_t)s * kv.max_blocks + start;
 
-    PSA_TRACE_STAMP(t_begin);
-    if (tid == 0) sh.abort_flag = 0;
-    for (int idx = tid; idx < kMaxChunkBlocks * G; idx += kSelectThreads) {   // blocks beyond nblk take no part
-        const int i = idx / G, g = idx % G;
-        if (i >= nblk) sh.Lb[i][g] = -INFINITY;
+    // physical page and valid-token count of each ranked block of the chunk -> LDS
+    if (tid < nblk) {
+        sh.page[tid] = ws.ranked_page[row0 + tid];
+        sh.valid[tid] = min(kPage, ctx - ws.order[row0 + tid] * kPage);
     }
-    float *lg_out = ws.logits + ((size_t)s * kv.max_blocks + start) * (kPage * G);
-    lds_barrier();
     // B operand of the QK^T product: column n = lane%16 is query head n (zero beyond the group),
     // k block kq = lane/16; for step kk the lane holds channels 8*(4*kk + kq) .. +7.
     const int n = lane & 15, kq = lane >> 4;
@@ -136,9 +270,11 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
         if (n < G)
             qb[kk] = ld16(q + ((size_t)(r * kv.num_q_heads + h * G + n) * kHeadDim + (4 * kk + kq) * 8) * 2);
     }
+    float *lg_out = ws.logits + row0 * (kPage * G);
+    lds_barrier();
 
-    // ---- 1. keys: wave w takes blocks [32*it + 4*w, +4).  A operand: row n = token n of the block,
-    //         same channel assignment as the queries; 64 contiguous bytes per token and step. --------
+    // ---- keys: wave w takes blocks [32*it + 4*w, +4).  A operand: row n = token n of the block,
+    //      same channel assignment as the queries; 64 contiguous bytes per token and step. ------------
     for (int i0 = wave * kBatch; i0 < nblk; i0 += (kSelectThreads / 64) * kBatch) {
         uint4 ka[kBatch][4];
 #pragma unroll
@@ -178,151 +314,35 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
         }
     }
     lds_barrier();
-    PSA_TRACE_STAMP(t_kdone);
-
-    // ---- 2 + 3. aggregate, prefix, stop rule: wave w serves head w ------------------------------
-    for (int g = wave; g < G; g += kSelectThreads / 64) {
-        // the head's best known stop so far; only a hint (it may be stale), requested early
-        const unsigned long long known = ld_relaxed(&ctl->stop[g]);
-        const float L = sh.Lb[lane][g];                       // -inf beyond nblk
-        float accL = L, mn = (lane < nblk) ? L : INFINITY;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const float oL = __shfl_up(accL, d), om = __shfl_up(mn, d);
-            if (lane >= d) { accL = lse2(accL, oL); mn = fminf(mn, om); }
-        }
-        const float Lagg = __shfl(accL, 63), Mnagg = __shfl(mn, 63);
-        unsigned long long *agg = ws.agg + (size_t)s * ws.max_chunks * G;
-        if (lane == 0) st_relaxed(&agg[(size_t)c * G + g], pack2(Lagg, Mnagg));
-
-        // exclusive prefix over chunks 0..c-1, folded in a fixed order: lane l folds chunks l, l+64, ...
-        // in ascending order, then the lanes are combined by a butterfly.  Four aggregates per lane
-        // are requested at once; one still missing is polled.
-        float pL = -INFINITY, pMin = INFINITY;
-        int bad = 0;
-        for (int j0 = lane; j0 < c && !bad; j0 += 256) {
-            unsigned long long v[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                v[u] = (j0 + 64 * u < c) ? ld_relaxed(&agg[(size_t)(j0 + 64 * u) * G + g]) : 0ull;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int j = j0 + 64 * u;
-                if (j < c && !bad) {
-                    int spins = 0;
-                    while (v[u] == kAggSentinel) {
-                        ++spins;
-                        if ((spins & 7) == 0 && ld_relaxed(&ctl->done_chunk) < c) { bad = 1; break; }
-                        if (spins > spin_limit) { bad = 2; break; }
-                        __builtin_amdgcn_s_sleep(16);
-                        v[u] = ld_relaxed(&agg[(size_t)j * G + g]);
-                    }
-                    if (!bad) {
-                        pL = lse2(pL, __uint_as_float((uint32_t)(v[u] & 0xffffffffull)));
-                        pMin = fminf(pMin, __uint_as_float((uint32_t)(v[u] >> 32)));
-                    }
-                }
-            }
-        }
-        const int any_bad = __any(bad != 0);
-        if (__any(bad == 2)) {
-            if (lane == 0) { set_error(ws.header, PSA_DEVERR_WAIT_EXPIRED); atomicMin(&ctl->done_chunk, -1); }
-        }
-        if (any_bad) { if (lane == 0) sh.abort_flag = 1; break; }
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) {
-            pL = lse2(pL, __shfl_xor(pL, d));
-            pMin = fminf(pMin, __shfl_xor(pMin, d));
-        }
-
-        // P_acc at position n = start + lane + 1 (after this lane's block)
-        const float Lacc_n = lse2(pL, accL), Lmin_n = fminf(pMin, mn);
-        const int n = start + lane + 1;
-        const float P = 1.0f / (1.0f + (float)(N - n) * exp2_fast(Lmin_n - Lacc_n));
-        const bool adm = (lane < nblk) && ((n % m) == 0 || n == N);
-        const unsigned long long hits = __ballot(adm && (P > eps));
-        // position n = start is also this chunk's to test when it is admissible
-        int ls = -1;
-        float Ps = 0.0f;
-        if (c > 0 && (start % m) == 0) {
-            const float P0 = 1.0f / (1.0f + (float)(N - start) * exp2_fast(pMin - pL));
-            if (P0 > eps) { ls = start; Ps = P0; }
-        }
-        if (ls < 0 && hits) {
-            const int f = __ffsll((long long)hits) - 1;
-            ls = start + f + 1;
-            Ps = __shfl(P, f);
-        }
-        int cnt = nblk, stopped = 0;
-        if (ls >= 0) {
-            cnt = ls - start;
-            stopped = 1;
-            if (lane == 0) atomicMin(&ctl->stop[g], ((unsigned long long)ls << 32) | __float_as_uint(Ps));
-        }
-        if ((known >> 32) <= (unsigned long long)start) { cnt = 0; stopped = 1; }
-        if (lane == 0) { sh.cnt[g] = cnt; sh.stopped[g] = stopped; }
-    }
+    // the blocks' L_b, for the fold's block-by-block pass; complete before the chunk is published
+    for (int idx = tid; idx < nblk * G; idx += kSelectThreads)
+        st_relaxed(&ws.block_lse[row0 * G + idx], sh.Lb[idx / G][idx % G]);
+    stores_done();
     lds_barrier();
-    if (sh.abort_flag) return;
-    int maxcnt = 0;
-    {
-        int all = 1;
-#pragma unroll
-        for (int g = 0; g < G; ++g) { maxcnt = max(maxcnt, sh.cnt[g]); all &= sh.stopped[g]; }
-        if (tid == 0) {
-            if (all) atomicMin(&ctl->done_chunk, c);
-            atomicAdd(&ctl->resolved, 1);
-            atomicAdd(&ctl->k_blocks, nblk);
+    if (wave != 0) return;
+
+    // ---- publish: the chunk's fold over its own blocks in rank order, one lane per head ------------------
+    float aggL = -INFINITY, aggMin = INFINITY;
+    if (lane < G)
+        for (int i = 0; i < nblk; ++i) {
+            const float Lb = sh.Lb[i][lane];
+            aggL = lse2(aggL, Lb);
+            aggMin = fminf(aggMin, Lb);
         }
-    }
-    PSA_TRACE_EMIT(maxcnt);
+    unsigned long long w = pack2(aggL, aggMin);
+    if (w >= kAggArmed) w = kAggArmed - 1;     // a NaN that happens to look like one of the marks
+    unsigned long long *cw = &ws.agg[((size_t)s * ws.max_chunks + c) * G];
+    if (lane >= 1 && lane < G) st_relaxed(cw + lane, w);
+    stores_done();                              // words 1..G-1 are in place before word 0 is exchanged in
+    unsigned long long old = 0;
+    if (lane == 0) old = __hip_atomic_exchange(cw, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (uniform((int)(old == kAggArmed))) fold_stream<G>(kv, ws, s, eps, m, CB);
 }
 
-// Holder of ticket c waits here until the chunk is inside the stream's read-ahead window
-// (1), or learns that the stream finished before it (0).  One thread polls, with a sleep.
-__device__ int wait_for_window(const DecodeWs &ws, StreamCtl *ctl, int c, int window, int spin_limit) {
-    int spins = 0;
-    while (true) {
-        if (ld_relaxed(&ctl->done_chunk) < c) return 0;
-        const int res = ld_relaxed(&ctl->resolved);
-        int w = max(window, res >> 1);
-        w = w > 64 ? 64 : w;
-        if (c < res + w) return 1;
-        if (++spins > spin_limit) {
-            set_error(ws.header, PSA_DEVERR_WAIT_EXPIRED);
-            atomicMin(&ctl->done_chunk, -1);
-            return 0;
-        }
-        __builtin_amdgcn_s_sleep(32);
-    }
-}
-
-// Physical page and valid-token count of each ranked block of chunk c of stream s -> LDS.
-template <int G>
-__device__ __forceinline__ void stage_chunk_pages(SelectShared<G> &sh, const KvView &kv, const DecodeWs &ws,
-                                                  int s, int c, int CB, int lane_in_group) {
-    const int ctx = stream_ctx(kv, s);
-    const int N = (ctx + kPage - 1) / kPage;
-    const int start = c * CB, nblk = min(CB, N - start);
-    const int i = lane_in_group;
-    if (i < kMaxChunkBlocks) {
-        int page = 0, valid = 0;
-        if (i < nblk) {
-            const size_t at = (size_t)s * kv.max_blocks + start + i;
-            page = ws.ranked_page[at];
-            valid = min(kPage, ctx - ws.order[at] * kPage);
-        }
-        sh.page[i] = page;
-        sh.valid[i] = valid;
-    }
-}
-
-// The persistent scheduler.  grid = two workgroups per CU; 512 threads.  A workgroup starts at its
-// home stream (blockIdx % S) and keeps taking that stream's next chunk ticket; when a ticket shows
-// that the stream has nothing left (past its last block, or past a chunk in which every head had
-// stopped) it looks, round-robin, for the next stream that has work, preferring one whose window
-// is open, and leaves when there is none.  The holder of a ticket beyond the stream's window waits
-// for the window before it reads any key; the chunk's page numbers are fetched during that wait.
+// =================================================================================================
+// The persistent scheduler.  grid = two workgroups per CU; 512 threads.  Thread 0 decides what the
+// workgroup does next and tells the others through LDS.
+// =================================================================================================
 template <int DT, int G>
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(KvView kv, const uint8_t *__restrict__ q,
                                                                 DecodeWs ws, float eps, int m, int CB,
@@ -331,47 +351,81 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(KvView kv, const
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = kv.batch * kv.num_kv_heads;
     int home = blockIdx.x % S;
+    bool joined = false;
     while (true) {
-        // ---- next ticket of the home stream; wave 1 stages its pages while thread 0 waits --------
         StreamCtl *ctl = &ws.ctl[home];
         const int N = (stream_ctx(kv, home) + kPage - 1) / kPage;
-        if (tid == 0) sh.chunk = atomicAdd(&ctl->next_chunk, 1);
-        lds_barrier();
-        const int c = sh.chunk;
-        int go = 0;
-        if (c * CB < N) {
-            if (tid == 0) sh.state = wait_for_window(ws, ctl, c, window, spin_limit);
-            if (wave == 1) stage_chunk_pages<G>(sh, kv, ws, home, c, CB, lane);
-            lds_barrier();
-            go = sh.state;
-        }
-        if (go) {
-            process_chunk<DT, G>(sh, kv, q, ws, eps, m, CB, spin_limit, home, c);
-            lds_barrier();
-            continue;
-        }
-        lds_barrier();
-        // ---- the home stream is finished: first stream in rotation order that has work -----------------
-        int first_open = INT_MAX, first_busy = INT_MAX;
-        for (int b0 = 0; b0 < S && first_open == INT_MAX; b0 += kSelectThreads) {
-            int st = 2;
-            if (b0 + tid < S) st = classify_stream(kv, ws, (home + b0 + tid) % S, CB, window);
-            const unsigned long long open = __ballot(st == 0), busy = __ballot(st == 1);
-            if (lane == 0) {
-                sh.w_first[wave] = open ? b0 + wave * 64 + (__ffsll((long long)open) - 1) : INT_MAX;
-                sh.w_busy[wave] = busy ? b0 + wave * 64 + (__ffsll((long long)busy) - 1) : INT_MAX;
+        int tries = 0, k_loaded = 0;
+        while (true) {
+            if (tid == 0) {
+                int what = 3, item = -1;
+                const unsigned long long kp = ld_relaxed(&ctl->key_progress);
+                const int fr = (int)(kp & 0xffffffffull), lim = (int)(kp >> 32);
+                const int nx = ld_relaxed(&ctl->k_next);
+                if (nx < lim) {
+                    what = 2;
+                    if (nx < fr + window_of(window, fr)) {
+                        item = atomicAdd(&ctl->k_next, 1);
+                        if (item < lim) what = 0;   // (lim can only have shrunk: a stale pass reads a chunk nobody needs)
+                    }
+                    if (what == 2 && ++tries > spin_limit) what = 4;
+                }
+                sh.what = what;
+                sh.item = item;
             }
             lds_barrier();
-#pragma unroll
-            for (int w = 0; w < kSelectThreads / 64; ++w) {
-                first_open = min(first_open, sh.w_first[w]);
-                first_busy = min(first_busy, sh.w_busy[w]);
+            const int what = sh.what, item = sh.item;
+            if (what == 0) {
+                process_chunk<DT, G>(sh, kv, q, ws, eps, m, CB, home, item);
+                k_loaded += min(CB, N - item * CB);
+                tries = 0;
+            } else if (what == 2) {
+                nap(tries);
+            } else {
+                break;
             }
-            lds_barrier();
+            lds_barrier();      // everyone has read sh.what before thread 0 decides again
         }
-        const int first = first_open != INT_MAX ? first_open : first_busy;
-        if (first == INT_MAX) break;               // every stream is finished
-        home = (home + first) % S;
+        lds_barrier();
+        if (tid == 0) {
+            if (k_loaded) atomicAdd(&ctl->k_blocks, k_loaded);
+            if (joined) atomicAdd(&ctl->attached, -1);
+            if (sh.what == 4) set_error(ws.header, PSA_DEVERR_WAIT_EXPIRED);
+        }
+        if (sh.what == 4) break;
+        // ---- the stream has handed out all its chunks: join one that has some and room, or leave ---------------
+        if (wave == 0) {
+            int next = -1;
+            const int off0 = 1 + (int)((blockIdx.x * 40503u) % (unsigned)S);     // where this workgroup starts looking
+            for (int b0 = 0; b0 < S && next < 0; b0 += 64) {
+                int open = 0, cand = 0;
+                if (b0 + lane < S) {
+                    cand = (home + off0 + b0 + lane) % S;
+                    const StreamCtl *o = &ws.ctl[cand];
+                    open = ld_relaxed(&o->k_next) < (int)(ld_relaxed(&o->key_progress) >> 32) &&
+                           ld_relaxed(&o->attached) < kMaxJoiners;
+                }
+                unsigned long long mask = __ballot(open);
+                while (mask && next < 0) {
+                    const int src = __ffsll((long long)mask) - 1;
+                    const int c2 = __shfl(cand, src);
+                    int ok = 0;
+                    if (lane == 0) {
+                        ok = atomicAdd(&ws.ctl[c2].attached, 1) < kMaxJoiners;
+                        if (!ok) atomicAdd(&ws.ctl[c2].attached, -1);
+                    }
+                    if (uniform(ok)) next = c2;
+                    mask &= mask - 1;
+                }
+            }
+            if (lane == 0) sh.next = next;
+        }
+        lds_barrier();
+        const int next = sh.next;
+        lds_barrier();
+        if (next < 0) break;
+        home = next;
+        joined = true;
     }
 }
 

@@ -7,7 +7,9 @@
 // actually selected are read.
 //   attend_kernel    one workgroup per (chunk, stream): p = exp(logit - chunk max), partial
 //                    numerator sum_t p_t v_t per head, exp-sum and reference maximum
-//   finalize_kernel  merges a head's chunks (the online-softmax merge of line 11, all at once)
+//   finalize_kernel  merges a head's chunks (the online-softmax merge of line 11, all at once):
+//                    out_g = sum over the chunks of the head's own prefix of the partial numerators,
+//                    over the sum of the partial exp-sums, both rescaled to one reference maximum
 #include "psa_attend.h"
 #include "psa_host.h"
 
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int
             for (int x = 0; x < 8; ++x) sh.st_acc[wave][g][cl * 8 + x] = acc[g][x];
     }
     lds_barrier();
-    float *dst = ws.partial + ((size_t)s * ws.max_chunks + c) * G * kPartialStride;
+    float *dst = ws.partial + ((size_t)s * ws.max_units + c) * G * kPartialStride;
     for (int idx = tid; idx < G * kHeadDim; idx += 256) {
         const int g = idx / kHeadDim, ch = idx % kHeadDim;
         dst[g * kPartialStride + 4 + ch] =
@@ -173,22 +175,22 @@ __global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int
     }
 }
 
+constexpr int kUnitLanes = 16;   // value units merged side by side by one workgroup
+
 // =================================================================================================
-// Finalize: out_g = sum over the chunks of the head's own prefix of the partial numerators, over
-// the sum of the partial exp-sums, both rescaled to one reference.
-// grid (S*G), 512 threads = 4 chunk lanes x 128 channels; chunk lane j takes chunks j, j+4, ...
-// =================================================================================================
-__global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, int G, int CB,
+// grid (S*G), 512 threads = 16 unit lanes x 32 channel quads; unit lane j takes units j, j+16, ...
+// in ascending order, and the 16 lanes are then added in a fixed order.
+__global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, int G, int VU,
                                                        float *__restrict__ out,
                                                        int32_t *__restrict__ n_selected,
                                                        float *__restrict__ mass_est,
                                                        int32_t *__restrict__ blocks_read,
                                                        int32_t *__restrict__ traffic_out) {
     __shared__ float red[512];
-    __shared__ float wgt[1024];          // per-chunk rescale factor (max_chunks <= 1024)
-    __shared__ float den_part[512];
+    __shared__ float wgt[kMaxBlocks / 4];        // per-unit rescale factor (value units are >= 4 blocks)
+    __shared__ __attribute__((aligned(16))) float num_part[kUnitLanes][kHeadDim];
     const int s = blockIdx.x / G, g = blockIdx.x % G, tid = threadIdx.x;
-    const int ch = tid & 127, cj = tid >> 7;
+    const int cq = tid & 31, uj = tid >> 5;
     const int r = s / kv.num_kv_heads, h = s % kv.num_kv_heads;
     int ctx = kv.ctx_lens[r];
     ctx = ctx < 0 ? 0 : (ctx > kv.max_blocks * kPage ? kv.max_blocks * kPage : ctx);
@@ -198,13 +200,13 @@ __global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, i
     int n = N;
     float P = N > 0 ? 1.0f : 0.0f;
     if (st != ~0ull && (int)(st >> 32) <= N) { n = (int)(st >> 32); P = __uint_as_float((uint32_t)st); }
-    const int nch = (n + CB - 1) / CB;
-    const float *src = ws.partial + ((size_t)s * ws.max_chunks * G + g) * kPartialStride;
+    const int nun = (n + VU - 1) / VU;
+    const float *src = ws.partial + ((size_t)s * ws.max_units * G + g) * kPartialStride;
     const size_t stride = (size_t)G * kPartialStride;
 
-    // reference maximum over the chunks
+    // reference maximum over the units
     float M = -INFINITY;
-    for (int i = tid; i < nch; i += 512) { const float mi = src[i * stride]; wgt[i] = mi; M = fmaxf(M, mi); }
+    for (int i = tid; i < nun; i += 512) { const float mi = src[i * stride]; wgt[i] = mi; M = fmaxf(M, mi); }
     red[tid] = M;
     __syncthreads();
     for (int d = 256; d >= 1; d >>= 1) {
@@ -213,31 +215,48 @@ __global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, i
     }
     M = red[0];
     __syncthreads();
-    // per-chunk weights and the denominator
+    // per-unit weights and the denominator
     float den = 0.0f;
-    for (int i = tid; i < nch; i += 512) {
+    for (int i = tid; i < nun; i += 512) {
         const float mi = wgt[i];
         const float w = (mi == -INFINITY || M == -INFINITY) ? 0.0f : exp2_fast(mi - M);
         wgt[i] = w;
         den += src[i * stride + 1] * w;
     }
-    den_part[tid] = den;
+    red[tid] = den;
     __syncthreads();
     for (int d = 256; d >= 1; d >>= 1) {
-        if (tid < d) den_part[tid] += den_part[tid + d];
+        if (tid < d) red[tid] += red[tid + d];
         __syncthreads();
     }
-    den = den_part[0];
-    // numerator: channel ch, chunks cj, cj+4, ...
-    float num = 0.0f;
-    for (int i = cj; i < nch; i += 4) num = fmaf(src[i * stride + 4 + ch], wgt[i], num);
-    red[tid] = num;
+    den = red[0];
+    // numerator: channels 4*cq .. 4*cq+3, units uj, uj+16, ...; four loads in flight per thread
+    float4 num = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (int i0 = uj; i0 < nun; i0 += 4 * kUnitLanes) {
+        float4 a[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int i = i0 + k * kUnitLanes;
+            a[k] = (i < nun) ? *reinterpret_cast<const float4 *>(src + i * stride + 4 + 4 * cq)
+                             : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int i = i0 + k * kUnitLanes;
+            const float w = (i < nun) ? wgt[i] : 0.0f;
+            num.x = fmaf(a[k].x, w, num.x); num.y = fmaf(a[k].y, w, num.y);
+            num.z = fmaf(a[k].z, w, num.z); num.w = fmaf(a[k].w, w, num.w);
+        }
+    }
+    *reinterpret_cast<float4 *>(&num_part[uj][4 * cq]) = num;
     __syncthreads();
-    if (tid < 128) {
-        num = (red[tid] + red[tid + 128]) + (red[tid + 256] + red[tid + 384]);
+    if (tid < kHeadDim) {
+        float t = 0.0f;
+#pragma unroll
+        for (int j = 0; j < kUnitLanes; ++j) t += num_part[j][tid];
         const size_t qi = (size_t)r * kv.num_q_heads + h * G + g;
-        out[qi * kHeadDim + ch] = den > 0.0f ? num / den : 0.0f;
-        if (ch == 0) {
+        out[qi * kHeadDim + tid] = den > 0.0f ? t / den : 0.0f;
+        if (tid == 0) {
             n_selected[qi] = n;
             mass_est[qi] = P;
             if (g == 0) {
@@ -270,10 +289,10 @@ hipError_t launch_attend(const KvView &kv, int dtype, int G, const DecodeWs &ws,
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_finalize(const KvView &kv, const DecodeWs &ws, int G, int CB, float *out,
+hipError_t launch_finalize(const KvView &kv, const DecodeWs &ws, int G, int VU, float *out,
                            int32_t *n_selected, float *mass_est, int32_t *blocks_read,
                            int32_t *traffic_out, hipStream_t st) {
-    finalize_kernel<<<kv.batch * kv.num_kv_heads * G, 512, 0, st>>>(kv, ws, G, CB, out, n_selected, mass_est,
+    finalize_kernel<<<kv.batch * kv.num_kv_heads * G, 512, 0, st>>>(kv, ws, G, VU, out, n_selected, mass_est,
                                                                     blocks_read, traffic_out);
     return hipGetLastError();
 }
