@@ -79,7 +79,7 @@ struct DecodeWs {
 #endif
 };
 #ifdef PSA_ENABLE_TRACE
-constexpr int kTracePerWave = 96;
+constexpr int kTracePerWave = 256;
 constexpr int kTraceRecords = 4096 * kTracePerWave;   // up to 4096 waves
 #endif
 constexpr int kPartialStride = 132;  // M, l, pad, pad, acc[128]

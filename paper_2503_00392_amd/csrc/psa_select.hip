@@ -76,6 +76,23 @@ __device__ __forceinline__ unsigned long long shfl_u64(unsigned long long v, int
 }
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
+#ifdef PSA_ENABLE_TRACE
+// Tuning aid (not built by default): every workgroup keeps its own list of records (kind, stream,
+// index, begin, end; 100 MHz timestamps), so tracing adds no shared traffic.
+#define PSA_TRACE(KIND, S, IDX, T0)                                                            \
+    if (threadIdx.x == 0 && trace_n < kTracePerWave) {                                         \
+        unsigned long long *rec_ = ws.trace + 8 + ((size_t)blockIdx.x * kTracePerWave + trace_n) * 4; \
+        rec_[0] = ((unsigned long long)(KIND) << 56) | ((unsigned long long)(S) << 32) | (unsigned)(IDX); \
+        rec_[1] = (unsigned long long)blockIdx.x;                                              \
+        rec_[2] = (T0); rec_[3] = wall_clock64();                                              \
+        ++trace_n;                                                                             \
+    }
+#define PSA_NOW() wall_clock64()
+#else
+#define PSA_TRACE(KIND, S, IDX, T0)
+#define PSA_NOW() 0ull
+#endif
+
 constexpr int kBatch = 4;            // key slices a wave keeps in flight
 constexpr int kSelectThreads = 512;  // 8 waves: a 32-block chunk is one batch per wave
 constexpr int kMaxWindow = 256;      // chunks handed out beyond the frontier, at most
@@ -280,10 +297,16 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             if (i0 + u < nblk) {
+#ifdef PSA_EXP_COALESCED_K
+                const uint8_t *kp = kv.k_pool + ((size_t)sh.page[i0 + u] * kv.num_kv_heads + h) * kSliceBytes + lane * 16;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) ka[u][kk] = ld16(kp + kk * 1024);
+#else
                 const uint8_t *kp = kv.k_pool + ((size_t)sh.page[i0 + u] * kv.num_kv_heads + h) * kSliceBytes +
                                     n * kRowBytes + kq * 16;
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) ka[u][kk] = ld16(kp + kk * 64);
+#endif
             }
         }
 #pragma unroll
@@ -344,7 +367,7 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
 // workgroup does next and tells the others through LDS.
 // =================================================================================================
 template <int DT, int G>
-__global__ __launch_bounds__(kSelectThreads) void select_kernel(KvView kv, const uint8_t *__restrict__ q,
+__global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, const uint8_t *__restrict__ q,
                                                                 DecodeWs ws, float eps, int m, int CB,
                                                                 int window, int spin_limit) {
     __shared__ SelectShared<G> sh;
@@ -352,6 +375,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(KvView kv, const
     const int S = kv.batch * kv.num_kv_heads;
     int home = blockIdx.x % S;
     bool joined = false;
+    [[maybe_unused]] int trace_n = 0;
+    PSA_TRACE(5, home, 0, PSA_NOW());
     while (true) {
         StreamCtl *ctl = &ws.ctl[home];
         const int N = (stream_ctx(kv, home) + kPage - 1) / kPage;
@@ -376,11 +401,15 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(KvView kv, const
             lds_barrier();
             const int what = sh.what, item = sh.item;
             if (what == 0) {
+                [[maybe_unused]] const unsigned long long t0 = PSA_NOW();
                 process_chunk<DT, G>(sh, kv, q, ws, eps, m, CB, home, item);
+                PSA_TRACE(1, home, item, t0);
                 k_loaded += min(CB, N - item * CB);
                 tries = 0;
             } else if (what == 2) {
+                [[maybe_unused]] const unsigned long long t0 = PSA_NOW();
                 nap(tries);
+                PSA_TRACE(4, home, tries, t0);
             } else {
                 break;
             }
@@ -424,6 +453,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(KvView kv, const
         const int next = sh.next;
         lds_barrier();
         if (next < 0) break;
+        PSA_TRACE(6, next, home, PSA_NOW());
         home = next;
         joined = true;
     }
