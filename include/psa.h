@@ -61,7 +61,7 @@ typedef struct {
     int32_t head_dim;           /* d, must be 128                                                 */
     int32_t page_size;          /* tokens per KV block, must be 16                                */
     int32_t num_pages;          /* physical pages in each pool                                    */
-    int32_t max_blocks_per_seq; /* row stride of block_table                                      */
+    int32_t max_blocks_per_seq; /* row stride of block_table, >= 1 for the attention calls        */
     int32_t dtype;              /* psa_dtype of Q, K, V and metadata                              */
     const void *k_pool;         /* [num_pages][num_kv_heads][page_size][head_dim]                 */
     const void *v_pool;         /* same layout                                                    */

@@ -22,8 +22,8 @@ psa_status check_desc(const psa_kv_desc *d, bool need_tables, bool need_v) {
     if (d->num_pages > 0 && !d->k_pool) return PSA_ERR_INVALID_ARG;
     if (need_v && d->num_pages > 0 && !d->v_pool) return PSA_ERR_INVALID_ARG;
     if (need_tables && d->batch > 0) {
-        if (!d->ctx_lens) return PSA_ERR_INVALID_ARG;
-        if (d->max_blocks_per_seq > 0 && !d->block_table) return PSA_ERR_INVALID_ARG;
+        // a block table with at least one column, even if every request is empty
+        if (!d->ctx_lens || !d->block_table || d->max_blocks_per_seq < 1) return PSA_ERR_INVALID_ARG;
     }
     return PSA_OK;
 }

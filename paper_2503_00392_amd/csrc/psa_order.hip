@@ -9,14 +9,18 @@
 //   3. an element's final rank is its bucket's base plus the number of elements of the same bucket
 //      that precede it under (key, index) -- counted exactly, so the result does not depend on the
 //      order in which the LDS atomics arrived.
-// Buckets hold 8 elements on average.  If one bucket holds more than kBucketLimit elements
+// There are as many buckets as element slots, so a bucket holds about one element.  If one bucket
+// holds more than kBucketLimit elements
 // (near-identical scores) the quadratic in-bucket count would be slow, and the workgroup falls back
 // to a bitonic network over 64-bit (key, index) words: compare distances below 8 stay in registers,
 // below 512 go through wave shuffles, the rest through LDS.  Both paths give the same total order.
 //
+// With few streams several workgroups share one stream: each builds the bucket table (cheap) and
+// ranks its share of the elements (the expensive part, bound by LDS traffic).
+//
 // The kernel also resets the stream's control block and chunk words for the progressive kernel and
 // reports out-of-range contexts and block-table entries.
-// grid (S), Np/8 threads, Np*8 bytes of dynamic LDS; Np = power of two >= max(512, max_blocks).
+// grid (S), Np/8 threads, 10*Np + 512 bytes of dynamic LDS; Np = power of two >= max(512, max_blocks).
 #include <limits.h>
 
 #include "psa_host.h"
@@ -24,6 +28,14 @@
 namespace psa {
 
 constexpr int kBucketLimit = 192;
+
+#ifdef PSA_ENABLE_TRACE
+// Tuning aid (not built by default): phase timestamps of workgroup 0, 100 MHz.
+#define PSA_ORDER_STAMP(K)                                                                     \
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) ws.trace[8 + ((size_t)4095 * kTracePerWave + (K)) * 4 + 2] = wall_clock64();
+#else
+#define PSA_ORDER_STAMP(K)
+#endif
 
 __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int mask) {
     const int lo = __shfl_xor((int)(v & 0xffffffffull), mask);
@@ -93,15 +105,30 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
                                                       int force_bitonic,
                                                       int32_t *__restrict__ order_out) {
     extern __shared__ unsigned long long lds_raw[];
-    const int s = blockIdx.x, r = s / kv.num_kv_heads;
+    const int s = blockIdx.y, r = s / kv.num_kv_heads;
+    const int part = blockIdx.x, nparts = gridDim.x;
     const int tid = threadIdx.x, nthreads = blockDim.x, lane = tid & 63, wave = tid >> 6;
     const int nwaves = nthreads >> 6;
+    // everything this thread needs from memory, requested at once and before anything
+    // else: its 8 scores and table entries
+    const float *sc = ws.scores + (size_t)s * kv.max_blocks;
+    const int32_t *table = kv.block_table + (size_t)r * kv.max_blocks;
+    float scv[8];
+    int pg[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int p = tid * 8 + j;
+        const int pc = min(p, max(kv.max_blocks - 1, 0));   // clamped into the row, so that the loads need no branch
+        scv[j] = sc[pc];
+        pg[j] = table[pc];
+    }
     // the scoring kernel clamps silently (it clears the error word); out-of-range inputs are reported here
-    const int ctx = (tid == 0) ? ctx_clamped(kv, r, ws.header) : ctx_clamped_quiet(kv, r);
+    const int ctx = (tid == 0 && blockIdx.x == 0) ? ctx_clamped(kv, r, ws.header) : ctx_clamped_quiet(kv, r);
     const int N = (ctx + kPage - 1) / kPage;
+    PSA_ORDER_STAMP(0)
 
     // ---- reset of the progressive kernel's per-stream state ------------------------------------
-    if (tid == 0) {
+    if (tid == 0 && part == 0) {
         StreamCtl *c = &ws.ctl[s];
         const unsigned nch = (unsigned)((N + KU - 1) / KU);
         c->k_next = 0; c->v_next = 0; c->k_blocks = 0; c->attached = 0;
@@ -109,21 +136,19 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         c->value_progress = (unsigned long long)(N == 0 ? 0u : (unsigned)kUnknownTotal) << 32;   // nothing released
         for (int g = 0; g < 8; ++g) { c->Lacc[g] = -INFINITY; c->Lmin[g] = INFINITY; c->stop[g] = ~0ull; }
     }
-    {
+    if (part == 0) {
         unsigned long long *a = ws.agg + (size_t)s * ws.max_chunks * G;
         // chunk 0 starts out as the place where the fold waits: its publisher starts folding
         for (int i = tid; i < ws.max_chunks * G; i += nthreads) a[i] = (i == 0) ? kAggArmed : kAggSentinel;
     }
 
-    // LDS carve-up of the bucket path (7*Np bytes + scratch in the last Np bytes)
-    uint32_t *key_of = reinterpret_cast<uint32_t *>(lds_raw);                 // [Np] key by logical block
-    uint16_t *slot = reinterpret_cast<uint16_t *>(key_of + Np);               // [Np] logical block by slot
-    uint32_t *cnt = reinterpret_cast<uint32_t *>(slot + Np);                  // [NB]
-    uint32_t *base = cnt + nthreads;                                          // [NB]
-    uint32_t *scratch = base + nthreads;                                      // >= 64 words
-    const int NB = nthreads;                                                  // one bucket per thread
+    // LDS carve-up of the bucket path: 10*Np bytes + scratch
+    uint32_t *skey = reinterpret_cast<uint32_t *>(lds_raw);                   // [Np] key by slot
+    uint32_t *cnt = skey + Np;                                                // [Np + 4] bucket counts, then bases
+    uint16_t *slot = reinterpret_cast<uint16_t *>(cnt + Np + 4);              // [Np] logical block by slot
+    uint32_t *scratch = reinterpret_cast<uint32_t *>(slot + Np);              // 64 words
+    const int NB = Np;                                                        // one bucket per element slot
 
-    const float *sc = ws.scores + (size_t)s * kv.max_blocks;
     uint32_t key[8];
     uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
 #pragma unroll
@@ -131,23 +156,24 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         const int p = tid * 8 + j;
         key[j] = 0xFFFFFFFFu;
         if (p < N) {
-            key[j] = descending_key(sc[p]);
+            key[j] = descending_key(scv[j]);
             kmin = min(kmin, key[j]);
             kmax = max(kmax, key[j]);
         }
-        key_of[p] = key[j];
     }
-    cnt[tid] = 0;
+    *reinterpret_cast<uint4 *>(cnt + tid * 8) = make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4 *>(cnt + tid * 8 + 4) = make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
         kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, d));
         kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, d));
     }
     if (lane == 0) { scratch[wave] = kmin; scratch[16 + wave] = kmax; }
-    __syncthreads();
+    lds_barrier();
     kmin = 0xFFFFFFFFu; kmax = 0u;
     for (int w = 0; w < nwaves; ++w) { kmin = min(kmin, scratch[w]); kmax = max(kmax, scratch[16 + w]); }
     const float scale = (float)NB / ((float)(kmax - kmin) + 1.0f);
+    PSA_ORDER_STAMP(1)
 
     int bkt[8], arrival[8];
 #pragma unroll
@@ -160,58 +186,102 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
             arrival[j] = (int)atomicAdd(&cnt[b], 1u);
         }
     }
-    __syncthreads();
+    lds_barrier();
 
-    // exclusive scan of the bucket counts (bucket = thread) and the largest bucket
-    const uint32_t mine = cnt[tid];
+    PSA_ORDER_STAMP(2)
+    // exclusive scan of the bucket counts (8 buckets per thread) and the largest bucket
+    uint32_t c8[8];
+    {
+        const uint4 a = *reinterpret_cast<const uint4 *>(cnt + tid * 8), b4 = *reinterpret_cast<const uint4 *>(cnt + tid * 8 + 4);
+        c8[0] = a.x; c8[1] = a.y; c8[2] = a.z; c8[3] = a.w; c8[4] = b4.x; c8[5] = b4.y; c8[6] = b4.z; c8[7] = b4.w;
+    }
+    uint32_t mine = 0, biggest = 0, e8[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { e8[j] = mine; mine += c8[j]; biggest = max(biggest, c8[j]); }
     uint32_t incl = mine;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
         const uint32_t o = (uint32_t)__shfl_up((int)incl, d);
         if (lane >= d) incl += o;
     }
-    uint32_t biggest = mine;
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) biggest = max(biggest, (uint32_t)__shfl_xor((int)biggest, d));
     if (lane == 63) scratch[32 + wave] = incl;
     if (lane == 0) scratch[48 + wave] = biggest;
-    __syncthreads();
+    lds_barrier();
     uint32_t wave_off = 0, max_bucket = 0;
     for (int w = 0; w < nwaves; ++w) {
         if (w < wave) wave_off += scratch[32 + w];
         max_bucket = max(max_bucket, scratch[48 + w]);
     }
-    base[tid] = wave_off + incl - mine;
-    __syncthreads();
+    {
+        const uint32_t t0 = wave_off + incl - mine;
+        *reinterpret_cast<uint4 *>(cnt + tid * 8) = make_uint4(t0 + e8[0], t0 + e8[1], t0 + e8[2], t0 + e8[3]);
+        *reinterpret_cast<uint4 *>(cnt + tid * 8 + 4) = make_uint4(t0 + e8[4], t0 + e8[5], t0 + e8[6], t0 + e8[7]);
+        if (tid == 0) cnt[NB] = (uint32_t)N;
+    }
+    lds_barrier();
+    PSA_ORDER_STAMP(3)
+    const uint32_t *base = cnt;                                               // base[b] .. base[b+1]: bucket b's slots
 
-    const int32_t *table = kv.block_table + (size_t)r * kv.max_blocks;
     int32_t *ord = ws.order + (size_t)s * kv.max_blocks;
     int32_t *rpage = ws.ranked_page + (size_t)s * kv.max_blocks;
     int32_t *oout = order_out ? order_out + (size_t)s * kv.max_blocks : nullptr;
 
     if (max_bucket <= (uint32_t)kBucketLimit && !force_bitonic) {
+        uint32_t b0[8], cn[8], before[8], cmax = 0;
+        // every workgroup of the stream builds the whole slot table (arrival order may differ between
+        // them; the exact count below does not depend on it) ...
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            if (tid * 8 + j < N) slot[base[bkt[j]] + arrival[j]] = (uint16_t)(tid * 8 + j);
-        __syncthreads();
+        for (int j = 0; j < 8; ++j) {
+            b0[j] = base[bkt[j]];
+            cn[j] = 0;
+            before[j] = 0;
+            if (tid * 8 + j < N) {
+                slot[b0[j] + arrival[j]] = (uint16_t)(tid * 8 + j);
+                skey[b0[j] + arrival[j]] = key[j];
+            }
+        }
+        lds_barrier();
+        // ... and ranks its own share of the elements
+        const int per = (nthreads + nparts - 1) / nparts;
+        const bool mine_part = tid >= part * per && tid < (part + 1) * per;
+        if (mine_part) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                cn[j] = tid * 8 + j < N ? base[bkt[j] + 1] - b0[j] : 0u;
+                cmax = max(cmax, cn[j]);
+            }
+        }
+        PSA_ORDER_STAMP(4)
+        // the 8 elements walk their buckets side by side, so their LDS reads overlap; the slot's block
+        // index is needed only to break a tie
+        for (uint32_t i = 0; i < cmax; ++i) {
+            uint32_t ko[8], so[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {              // reads past a bucket's end stay inside the table
+                const uint32_t at = min(b0[j] + i, (uint32_t)(Np - 1));
+                ko[j] = skey[at];
+                so[j] = slot[at];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool first = ko[j] < key[j] || (ko[j] == key[j] && so[j] < (uint32_t)(tid * 8 + j));
+                before[j] += (i < cn[j] && first) ? 1u : 0u;
+            }
+        }
+        PSA_ORDER_STAMP(5)
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int p = tid * 8 + j;
-            if (p < N) {
-                const uint32_t b0 = base[bkt[j]], c = cnt[bkt[j]];
-                uint32_t before = 0;
-                for (uint32_t i = 0; i < c; ++i) {
-                    const uint32_t other = slot[b0 + i];
-                    const uint32_t ko = key_of[other];
-                    before += (ko < key[j] || (ko == key[j] && other < (uint32_t)p)) ? 1u : 0u;
-                }
-                const uint32_t rank = b0 + before;
+            if (p < N && mine_part) {
+                const uint32_t rank = b0[j] + before[j];
                 ord[rank] = p;
-                rpage[rank] = clamp_page(table[p], kv.num_pages, ws.header);
+                rpage[rank] = clamp_page(pg[j], kv.num_pages, ws.header);
                 if (oout) oout[rank] = p;
             }
         }
-    } else {
+    } else if (part == 0) {     // (uniform over the workgroup) the fallback is one workgroup's work
         __syncthreads();   // everyone is done with the bucket arrays before LDS is reused
         unsigned long long e[8];
 #pragma unroll
@@ -231,8 +301,9 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
             }
         }
     }
-    if (oout)
+    if (oout && part == 0)
         for (int p = N + tid; p < kv.max_blocks; p += nthreads) oout[p] = -1;
+    PSA_ORDER_STAMP(6)
 }
 
 hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int KU, int force_bitonic,
@@ -240,7 +311,19 @@ hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int KU, int
     const int S = kv.batch * kv.num_kv_heads;
     int Np = 512;
     while (Np < kv.max_blocks) Np <<= 1;
-    order_kernel<<<S, Np / 8, (size_t)Np * 8, st>>>(kv, ws, G, KU, Np, force_bitonic, order_out);
+    const size_t lds = (size_t)Np * 10 + 512;
+    static bool raised = false;       // more than 64 KiB of dynamic LDS has to be asked for once
+    if (!raised) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(order_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kMaxBlocks * 10 + 512) != hipSuccess)
+            return hipErrorInvalidValue;
+        raised = true;
+    }
+    // with few streams, up to 4 workgroups share a stream's ranking
+    int parts = 256 / (S > 0 ? S : 1);
+    parts = parts < 1 ? 1 : (parts > 4 ? 4 : parts);
+    if (Np < 2048) parts = 1;
+    order_kernel<<<dim3(parts, S), Np / 8, lds, st>>>(kv, ws, G, KU, Np, force_bitonic, order_out);
     return hipGetLastError();
 }
 

@@ -86,7 +86,7 @@ def test_workspace_sizes(lib):
     (dict(num_q_heads=30), 1),            # not a multiple of the KV heads
     (dict(batch=-1), 1), (dict(num_kv_heads=0), 1), (dict(k_pool=None), 1), (dict(v_pool=None), 1),
     (dict(block_table=None), 1), (dict(ctx_lens=None), 1),
-    (dict(max_blocks_per_seq=8193), 2),
+    (dict(max_blocks_per_seq=8193), 2), (dict(max_blocks_per_seq=0), 1),
 ])
 def test_decode_rejects_bad_descriptors_on_the_host(lib, kw, want):
     assert _decode(lib, _desc(**kw)) == want
