@@ -60,6 +60,21 @@ class HipEvents:
         self.all = []
 
 
+def read_measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` on `workload` as measured with hardware counters (two
+    rocprofv3 --pmc runs, scaled by a plain copy of known size) and recorded in the text summary
+    profiles/hbm_traffic_<workload>.md as a line `traffic_bytes_per_launch <kernel> = <number>`;
+    None if there is no such record."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.md")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.replace("`", "").split()
+        if len(parts) >= 4 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel and parts[2] == "=":
+            return float(parts[3])
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,6 +156,13 @@ def main():
             psa.build_block_metadata(kvs[i], metas[i], page_fill=layers[i].page_fill, page_list=last_pages[i])
             psa.decode_attention(kvs[i], layers[i].q, metas[i], eps, m, workspace=ws, outputs=outs[i],
                                  tuning=tunings[i] if tunings else tun)
+
+    # one plain 1 GiB device copy: the known-size kernel that hardware-counter runs are scaled by
+    cal_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
 
     log(f"[bench] inputs ready in {time.time() - t0:.1f}s; warmup")
     for _ in range(args.warmup):
@@ -253,6 +275,8 @@ def main():
                "sample": f"config {cfg.index}, layers {sample}, requests {reqs}, all {Hq} query heads, "
                          f"scoring+ranking+progressive loop in fp64 ({t_cpu:.1f}s of CPU time)"}
 
+    traffic = read_measured_traffic(cfg.name, dom)
+
     result = {
         "metric": "psa_decode_query_heads_per_s", "value": value, "unit": "query-heads/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -262,7 +286,7 @@ def main():
                    "ctx": cfg.ctx, "kv_dtype": cfg.dtype, "threshold": eps, "check_granularity": m,
                    "chunk_blocks": args.chunk_blocks or 32, "parallelism": "1 GPU"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic,
                      "avg_launch_ms": kern_ms[dom], "algorithmic_bytes_per_launch": kern_bytes[dom]},
         "cpu_baseline": cpu,
         "whole_path": {"algorithmic_bytes_per_step": alg_bytes, "GBps": eff_gbs, "hbm_frac": eff_gbs / HBM_PEAK_GBS,
