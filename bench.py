@@ -83,6 +83,7 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = the 128K-context one)")
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
     ap.add_argument("--check-granularity", type=int, default=1)
+    ap.add_argument("--threshold", type=float, default=-1.0, help="override the workload's threshold (tuning)")
     ap.add_argument("--chunk-blocks", type=int, default=0)
     ap.add_argument("--workgroups", type=int, default=0)
     ap.add_argument("--window-chunks", type=int, default=0)
@@ -109,7 +110,7 @@ def main():
     if args.layers:
         cfg = cfg.scaled(layers=args.layers)
     L, B, Hq, H, G = cfg.layers, cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.group
-    eps, m = cfg.threshold, args.check_granularity
+    eps, m = (args.threshold if args.threshold >= 0 else cfg.threshold), args.check_granularity
     tuning_kw = dict(chunk_blocks=args.chunk_blocks, window_chunks=args.window_chunks, workgroups=args.workgroups)
 
     # ---- inputs, resident in HBM ---------------------------------------------------------------
