@@ -141,6 +141,19 @@ psa_status psa_decode_attention(const psa_kv_desc *desc, const void *q, const vo
                                 void *stream);
 
 /*
+ * Fixed-budget control: what block-level dynamic sparse attention does without PSA (Sec. 1, Sec. 2.2
+ * "KV Cache Selection": a fixed top-k, e.g. k = 64 or 128 blocks).  Same scoring and ranking as
+ * psa_decode_attention; every query head then attends exactly the first min(k_blocks, N) ranked
+ * blocks, and keys are read no further than that.  mass_est is P_acc of Algorithm 1 (lines 15-16)
+ * evaluated at that point.  All other arguments, the workspace size and the error behaviour are those
+ * of psa_decode_attention; k_blocks < 1 is PSA_ERR_INVALID_ARG.
+ */
+psa_status psa_topk_attention(const psa_kv_desc *desc, const void *q, const void *meta, int32_t k_blocks,
+                              float *out, int32_t *n_selected, float *mass_est, int32_t *blocks_read,
+                              int32_t *order_out, float *scores_out, int32_t *traffic_out,
+                              const psa_tuning *tuning, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Dense control: exact softmax attention over every block of the same paged layout
  * (Sec. 2.1: S = QK^T/sqrt(d), P = softmax(S), O = PV).
  *   out  [batch][num_q_heads][head_dim] float32

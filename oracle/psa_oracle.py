@@ -230,3 +230,26 @@ def psa_decode(pb: Problem, eps: float, m: int = 1, curves: bool = False,
     res = psa_decode_ordered(pb, order, eps, m, curves)
     res.cs = cs
     return res
+
+
+def topk_attention(pb: Problem, k: int, meta: np.ndarray | None = None) -> DecodeResult:
+    """Fixed-budget control (Sec. 1 and 2.2: what dynamic sparse attention does before PSA -- attend
+    exactly the k blocks with the best criticality scores): metadata -> scores -> ranking, then the
+    definition of attention over the first min(k, N) ranked blocks.  mass_est is Algorithm 1's P_acc
+    evaluated there (lines 15-16), read off the full curve of a run that never stops."""
+    if meta is None:
+        meta = block_metadata(pb, pb.page_fill())
+    _, cs = block_scores(pb, meta)
+    order = block_order(pb, cs)
+    B, Hq, H, D, T, P, MB = pb.dims
+    G = Hq // H
+    nb = pb.num_blocks()
+    n_take = np.repeat(np.minimum(k, nb)[:, None], Hq, 1).astype(np.int32)
+    out = attend_prefix(pb, order, n_take)
+    curves = psa_decode_ordered(pb, order, 1.0, 1, curves=True)
+    mass = np.zeros((B, Hq))
+    for r in range(B):
+        if nb[r]:
+            mass[r] = curves.p_acc[r, :, n_take[r, 0] - 1]
+    bread = n_take.reshape(B, H, G).max(-1).astype(np.int32)
+    return DecodeResult(out, n_take, mass, bread, order, cs)

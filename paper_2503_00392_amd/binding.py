@@ -82,6 +82,9 @@ def load_library() -> C.CDLL:
         lib.psa_decode_attention.restype = C.c_int
         lib.psa_decode_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, f32, i32, vp, vp, vp, vp, vp, vp,
                                              vp, C.POINTER(_Tuning), vp, sz, vp]
+        lib.psa_topk_attention.restype = C.c_int
+        lib.psa_topk_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, i32, vp, vp, vp, vp, vp, vp, vp,
+                                           C.POINTER(_Tuning), vp, sz, vp]
         lib.psa_dense_attention.restype = C.c_int
         lib.psa_dense_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, vp, sz, vp]
         lib.psa_read_device_error.restype = C.c_int
@@ -202,6 +205,37 @@ def decode_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, threshold
         _ptr(o.traffic), C.byref(t) if t else None, _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "psa_decode_attention")
     o._workspace = workspace   # keeps the buffer alive until the caller has synchronised
+    return o
+
+
+def topk_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, k_blocks: int, *,
+                   workspace: torch.Tensor | None = None, outputs: DecodeOutput | None = None,
+                   want_order: bool = False, want_scores: bool = False, want_traffic: bool = False,
+                   tuning: Tuning | None = None, stream=None) -> DecodeOutput:
+    """psa_topk_attention: the fixed-budget control.  Same buffers as decode_attention."""
+    d = kv.desc()
+    dev = q.device
+    B, Hq, H, MB = d.batch, d.num_q_heads, d.num_kv_heads, d.max_blocks_per_seq
+    t = tuning.c() if tuning else None
+    if workspace is None:
+        workspace = torch.empty(max(decode_workspace_bytes(kv, tuning), 256), dtype=torch.uint8, device=dev)
+    if outputs is None:
+        outputs = DecodeOutput(
+            torch.empty((B, Hq, 128), dtype=torch.float32, device=dev),
+            torch.empty((B, Hq), dtype=torch.int32, device=dev),
+            torch.empty((B, Hq), dtype=torch.float32, device=dev),
+            torch.empty((B, H), dtype=torch.int32, device=dev),
+            torch.empty((B, H, MB), dtype=torch.int32, device=dev) if want_order else None,
+            torch.empty((B, H, MB), dtype=torch.float32, device=dev) if want_scores else None,
+            torch.empty((B, H, 2), dtype=torch.int32, device=dev) if want_traffic else None)
+    o = outputs
+    assert q.is_contiguous() and meta.is_contiguous()
+    st = load_library().psa_topk_attention(
+        C.byref(d), _ptr(q), _ptr(meta), int(k_blocks), _ptr(o.out), _ptr(o.n_selected), _ptr(o.mass_est),
+        _ptr(o.blocks_read), _ptr(o.order), _ptr(o.scores), _ptr(o.traffic), C.byref(t) if t else None,
+        _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, "psa_topk_attention")
+    o._workspace = workspace
     return o
 
 

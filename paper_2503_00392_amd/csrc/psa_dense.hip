@@ -27,8 +27,10 @@ __global__ __launch_bounds__(256) void dense_split_kernel(KvView kv, const uint8
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, rg = lane >> 4, cl = lane & 15;
     const int ctx = ctx_clamped(kv, r, header);
     const int N = (ctx + kPage - 1) / kPage;
-    const int b0 = split * blocks_per_split;
-    const int b1 = min(N, b0 + blocks_per_split);
+    // every request is cut into the same number of splits, each over its own length: ragged batches stay balanced
+    const int bps = min(blocks_per_split, (N + nsplit - 1) / nsplit);
+    const int b0 = split * bps;
+    const int b1 = min(N, b0 + bps);
 
     const QueryRegs<G> qr = load_query<G>(q, r, h, kv.num_q_heads, cl);
     float m[G], l[G], acc[G][8];

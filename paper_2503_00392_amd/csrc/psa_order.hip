@@ -101,7 +101,7 @@ __device__ void bitonic_sort(unsigned long long (&e)[8], unsigned long long *lds
     }
 }
 
-__global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int G, int KU, int Np,
+__global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int G, int KU, int budget_blocks, int Np,
                                                       int force_bitonic,
                                                       int32_t *__restrict__ order_out) {
     extern __shared__ unsigned long long lds_raw[];
@@ -130,7 +130,9 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
     // ---- reset of the progressive kernel's per-stream state ------------------------------------
     if (tid == 0 && part == 0) {
         StreamCtl *c = &ws.ctl[s];
-        const unsigned nch = (unsigned)((N + KU - 1) / KU);
+        // key chunks that may ever be handed out: all of them, or those a fixed budget of blocks covers
+        const int nlim = budget_blocks > 0 ? min(N, budget_blocks) : N;
+        const unsigned nch = (unsigned)((nlim + KU - 1) / KU);
         c->k_next = 0; c->v_next = 0; c->k_blocks = 0; c->attached = 0;
         c->key_progress = (unsigned long long)nch << 32;                                  // frontier 0
         c->value_progress = (unsigned long long)(N == 0 ? 0u : (unsigned)kUnknownTotal) << 32;   // nothing released
@@ -306,7 +308,7 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
     PSA_ORDER_STAMP(6)
 }
 
-hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int KU, int force_bitonic,
+hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int KU, int budget_blocks, int force_bitonic,
                         int32_t *order_out, hipStream_t st) {
     const int S = kv.batch * kv.num_kv_heads;
     int Np = 512;
@@ -323,7 +325,7 @@ hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int KU, int
     int parts = 256 / (S > 0 ? S : 1);
     parts = parts < 1 ? 1 : (parts > 4 ? 4 : parts);
     if (Np < 2048) parts = 1;
-    order_kernel<<<dim3(parts, S), Np / 8, lds, st>>>(kv, ws, G, KU, Np, force_bitonic, order_out);
+    order_kernel<<<dim3(parts, S), Np / 8, lds, st>>>(kv, ws, G, KU, budget_blocks, Np, force_bitonic, order_out);
     return hipGetLastError();
 }
 

@@ -143,8 +143,10 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
     StreamCtl *ctl = &ws.ctl[s];
     const int ctx = stream_ctx(kv, s);
     const int N = (ctx + kPage - 1) / kPage;
-    const int nch = (N + KU - 1) / KU;
-    int fr = uniform((int)(ld_relaxed(&ctl->key_progress) & 0xffffffffull));
+    // chunks that will ever be published: all of them unless the ranking kernel set a budget
+    const unsigned long long kp0 = ld_relaxed(&ctl->key_progress);
+    const int nch = uniform((int)(kp0 >> 32));
+    int fr = uniform((int)(kp0 & 0xffffffffull));
     int fr_pub = fr;                           // frontier as the progress word shows it
     float Lacc = -INFINITY, Lmin = INFINITY;
     unsigned long long stop = 0ull;            // lanes >= G count as stopped

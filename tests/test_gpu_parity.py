@@ -157,3 +157,42 @@ def test_degenerate_scores_rank_by_block_index(psa):
         assert np.array_equal(order[r, :, :N[r]], np.tile(np.arange(N[r]), (cfg.num_kv_heads, 1)))
     rep = gc.check_decode_against_oracle(pb, gpu, 0.5, 1)
     assert rep.set_equal + rep.stop_flips == rep.heads
+
+
+@pytest.mark.parametrize("k", [1, 7, 32, 100, 10000])
+def test_topk_matches_oracle(psa, case, k):
+    """Fixed-budget control: same ranking, every head takes min(k, N) blocks, keys are read no
+    further than the budget (rounded up to whole chunks)."""
+    name, cfg, li, pb = case
+    kv = gc.to_kv(li)
+    meta = psa.build_block_metadata(kv, page_fill=li.page_fill)
+    gpu = psa.topk_attention(kv, li.q, meta, k, want_order=True, want_scores=True, want_traffic=True)
+    torch.cuda.synchronize()
+    assert psa.read_device_error(gpu._workspace) == 0
+    ora = po.topk_attention(pb, k)
+    N = pb.num_blocks()
+    want_n = np.repeat(np.minimum(k, N)[:, None], cfg.num_q_heads, 1)
+    g_n = gpu.n_selected.cpu().numpy()
+    assert np.array_equal(g_n, want_n) and np.array_equal(ora.n_selected, want_n)
+    assert np.array_equal(gpu.blocks_read.cpu().numpy(), np.repeat(np.minimum(k, N)[:, None], cfg.num_kv_heads, 1))
+    g_order = gpu.order.cpu().numpy()
+    g_out = gpu.out.cpu().numpy().astype(np.float64)
+    own = po.attend_prefix(pb, g_order, g_n)
+    assert gc.rel_l2(g_out, own).max() <= gc.OUT_RTOL
+    G = cfg.group
+    for r in range(cfg.batch):
+        n = int(want_n[r, 0])
+        for h in range(cfg.num_kv_heads):
+            sg, so = set(g_order[r, h, :n].tolist()), set(ora.order[r, h, :n].tolist())
+            if sg == so:
+                sl = slice(h * G, (h + 1) * G)
+                assert gc.rel_l2(g_out[r, sl], ora.out[r, sl]).max() <= gc.OUT_RTOL
+                np.testing.assert_allclose(gpu.mass_est[r, sl].cpu().numpy(), ora.mass_est[r, sl], atol=1e-4, rtol=0)
+            else:
+                edge = ora.cs[r, h, ora.order[r, h, n - 1]]
+                assert all(abs(ora.cs[r, h, b] - edge) <= gc.SCORE_ATOL for b in sg ^ so)
+    chunk = 32
+    tr = gpu.traffic.cpu().numpy()
+    lim = np.minimum(N, -(-np.minimum(k, N) // chunk) * chunk)
+    assert np.array_equal(tr[..., 0], np.repeat(lim[:, None], cfg.num_kv_heads, 1))       # keys: budget, whole chunks
+    assert np.array_equal(tr[..., 1], np.repeat(np.minimum(k, N)[:, None], cfg.num_kv_heads, 1))

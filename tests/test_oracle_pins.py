@@ -362,3 +362,44 @@ def test_worked_example_microbatches_behaviour():
     # with m = 4 a stop can only land on 4, 8 or 12 whatever the threshold
     for e_ in np.linspace(0.05, 0.999, 40):
         assert po.psa_decode(pb, float(e_), 4).n_selected[0, 0] in (4, 8, 12)
+
+
+# ---------------------------------------------------------------- fixed-budget control (Sec. 1, 2.2)
+@pytest.mark.parametrize("k", [1, 2, 5, 9, 100])
+def test_topk_is_attention_over_the_k_best_scored_blocks(k):
+    """Brute force: pick the k largest criticality scores per KV head (ties to the smaller block),
+    attend those blocks by the definition of softmax attention."""
+    pb = _problem(47)
+    res = po.topk_attention(pb, k)
+    _, cs = po.block_scores(pb, po.block_metadata(pb, pb.page_fill()))
+    nb = pb.num_blocks()
+    for r in range(3):
+        N = int(nb[r])
+        for hq in range(4):
+            sel = np.argsort(-cs[r, hq // 2, :N], kind="stable")[:k]
+            assert res.n_selected[r, hq] == min(k, N)
+            np.testing.assert_allclose(res.out[r, hq], ref.attend_blocks(pb, r, hq, sel), rtol=1e-11, atol=1e-12)
+            # the reported estimate is the P_acc curve read at min(k, N)
+            p = ref.p_acc_curve(ref.block_lse(pb, r, hq)[res.order[r, hq // 2, :N]])
+            assert abs(res.mass_est[r, hq] - p[min(k, N) - 1]) < 1e-10
+    assert np.array_equal(res.blocks_read, np.repeat(np.minimum(k, nb)[:, None], 2, 1))
+
+
+def test_topk_with_budget_covering_everything_is_dense_and_empty_request_is_zero():
+    pb = _problem(48, ctx=(37, 0, 5))
+    res = po.topk_attention(pb, 1000)
+    rout, _ = ref.dense(pb)
+    np.testing.assert_allclose(res.out, rout, rtol=1e-11, atol=1e-12)
+    assert np.all(res.mass_est[[0, 2]] == 1.0)
+    assert not res.out[1].any() and np.all(res.n_selected[1] == 0) and np.all(res.mass_est[1] == 0)
+
+
+@pytest.mark.parametrize("k", [1, 3, 8])
+def test_topk_equals_progressive_loop_with_threshold_zero_and_microbatch_k(k):
+    """Algorithm 1 tests the stop only every m blocks; with eps = 0 the first test passes, so the
+    loop with m = k is the fixed top-k baseline."""
+    pb = _problem(49)
+    a, b = po.topk_attention(pb, k), po.psa_decode(pb, 0.0, k)
+    assert np.array_equal(a.n_selected, b.n_selected)
+    np.testing.assert_allclose(a.out, b.out, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(a.mass_est, b.mass_est, rtol=1e-12)
