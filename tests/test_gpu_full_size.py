@@ -1,0 +1,137 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times
+(default tuning, m = 1 and the bench's m).  The oracle runs on the same seeded bytes; where a whole
+workload would take it minutes, it runs on a stated sample of requests (shortest, longest, a few in
+between) and the rest of the batch is checked through size-independent properties."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_common as gc
+from oracle import psa_oracle as po
+from workloads import generate_layer, get_config
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def psa():
+    import paper_2503_00392_amd as psa
+    psa.load_library()
+    assert torch.cuda.is_available()
+    return psa
+
+
+def _properties(psa, cfg, li, gpu, eps, m):
+    """What holds at any size without the oracle: ranking is a permutation in descending score order,
+    stops are admissible, the estimate exceeds eps unless everything was used, blocks_read is the
+    group's maximum, values are read exactly as far as the slowest head, keys at least that far."""
+    ctx = li.ctx_lens.cpu().numpy()
+    N = (ctx + 15) // 16
+    n = gpu.n_selected.cpu().numpy()
+    mass = gpu.mass_est.cpu().numpy()
+    G, H = cfg.group, cfg.num_kv_heads
+    Nh = np.repeat(N[:, None], cfg.num_q_heads, 1)
+    assert np.all((n >= np.minimum(1, Nh)) & (n <= Nh))
+    assert np.all((n % m == 0) | (n == Nh))
+    assert np.all((mass > eps) | (n == Nh))
+    assert np.all(mass[n == Nh] == 1.0) and np.all(mass <= 1.0)
+    read = gpu.blocks_read.cpu().numpy()
+    assert np.array_equal(read, n.reshape(cfg.batch, H, G).max(-1))
+    tr = gpu.traffic.cpu().numpy()
+    assert np.array_equal(tr[..., 1], read)
+    assert np.all(tr[..., 0] >= read) and np.all(tr[..., 0] <= np.repeat(N[:, None], H, 1))
+    order = gpu.order
+    scores = gpu.scores
+    for r in range(cfg.batch):
+        o = order[r, :, :N[r]].long()
+        assert torch.equal(torch.sort(o, dim=1).values, torch.arange(N[r], device=o.device).expand(H, -1))
+        ranked = torch.gather(scores[r, :, :N[r]], 1, o)
+        d = ranked[:, 1:] - ranked[:, :-1]
+        assert bool((d <= 0).all())
+        assert bool(((o[:, 1:] - o[:, :-1])[d == 0] > 0).all())
+        assert bool((order[r, :, N[r]:] == -1).all())
+    out = gpu.out
+    assert bool(torch.isfinite(out).all())
+
+
+def _run(psa, cfg, li, eps, m, requests):
+    gpu = gc.run_gpu_decode(li, eps, m)
+    _properties(psa, cfg, li, gpu, eps, m)
+    pb = gc.to_problem(li)
+    rep = gc.check_decode_against_oracle(pb, gpu, eps, m, requests=requests)
+    print(f"\n[config {cfg.index} eps={eps} m={m} requests={list(requests) if requests is not None else 'all'}] {rep}")
+    assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads
+    assert rep.stop_flips <= max(1, rep.heads // 50)
+    return gpu, pb
+
+
+def test_config2_full(psa):
+    cfg = get_config(2)
+    li = generate_layer(cfg, device="cuda")
+    for m in (1, 4):
+        _run(psa, cfg, li, cfg.threshold, m, None)
+
+
+@pytest.mark.parametrize("layer", [0, 7, 19])
+def test_config3_full_layers(psa, layer):
+    """128K context, 4 requests, random block table: layer 0 is one of the two near-dense layers, the
+    others draw their own critical fraction."""
+    cfg = get_config(3)
+    li = generate_layer(cfg, layer=layer, device="cuda")
+    gpu, pb = _run(psa, cfg, li, cfg.threshold, 1, None)
+    if layer == 7:
+        _run(psa, cfg, li, cfg.threshold, 4, [0, 3])
+        dense, lse = psa.dense_attention(gc.to_kv(li), li.q)
+        torch.cuda.synchronize()
+        want, wlse = po.dense_attention(pb)
+        assert gc.rel_l2(dense.cpu().numpy().astype(np.float64), want).max() <= gc.OUT_RTOL
+        np.testing.assert_allclose(lse.cpu().numpy(), wlse, rtol=0, atol=2e-3)
+
+
+def test_config4_full_ragged(psa):
+    """64 requests of 4K..128K tokens, groups of 8: the oracle takes the shortest, the longest and four
+    requests spread over the length range; all 64 go through the property checks."""
+    cfg = get_config(4)
+    li = generate_layer(cfg, device="cuda")
+    ctx = li.ctx_lens.cpu().numpy()
+    by_len = np.argsort(ctx, kind="stable")
+    sample = sorted({int(by_len[i]) for i in (0, 12, 25, 38, 51, len(by_len) - 1)})
+    gpu, pb = _run(psa, cfg, li, cfg.threshold, 1, sample)
+    # metadata over the whole pool, bit for bit
+    meta = psa.build_block_metadata(gc.to_kv(li), page_fill=li.page_fill)
+    torch.cuda.synchronize()
+    want = po.block_metadata(pb, li.page_fill.cpu().numpy())
+    assert np.array_equal(meta.view(torch.int16).cpu().numpy().view(np.uint16), want)
+    # dense control on the same sample
+    dense, _ = psa.dense_attention(gc.to_kv(li), li.q)
+    torch.cuda.synchronize()
+    sub = po.Problem(pb.q[sample], pb.k_pool, pb.v_pool, pb.block_table[sample], pb.ctx_lens[sample], pb.dtype)
+    want, _ = po.dense_attention(sub)
+    assert gc.rel_l2(dense.cpu().numpy().astype(np.float64)[sample], want).max() <= gc.OUT_RTOL
+
+
+@pytest.mark.parametrize("eps", [0.95, 0.99])
+def test_config5_full_uniform(psa, eps):
+    """Flat attention: nearly everything must be read; the sets may differ by tolerated blocks, which
+    is why outputs are always compared against attention over the GPU's own set."""
+    cfg = get_config(5)
+    li = generate_layer(cfg, device="cuda")
+    _run(psa, cfg, li, eps, 1, [0, 5, 15])
+
+
+def test_topk_full_size_config3(psa):
+    cfg = get_config(3)
+    li = generate_layer(cfg, layer=11, device="cuda")
+    pb = gc.to_problem(li)
+    kv = gc.to_kv(li)
+    meta = psa.build_block_metadata(kv, page_fill=li.page_fill)
+    for k in (64, 1000):
+        gpu = psa.topk_attention(kv, li.q, meta, k, want_order=True, want_traffic=True)
+        torch.cuda.synchronize()
+        assert psa.read_device_error(gpu._workspace) == 0
+        n = gpu.n_selected.cpu().numpy()
+        assert np.all(n == k)
+        own = po.attend_prefix(pb, gpu.order.cpu().numpy(), n)
+        assert gc.rel_l2(gpu.out.cpu().numpy().astype(np.float64), own).max() <= gc.OUT_RTOL
+        tr = gpu.traffic.cpu().numpy()
+        assert np.all(tr[..., 0] == -(-k // 32) * 32) and np.all(tr[..., 1] == k)
