@@ -89,6 +89,7 @@ def main():
     ap.add_argument("--window-chunks", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-topk-comparison", action="store_true")
     ap.add_argument("--cpu-layers", type=str, default="", help="layers the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -149,7 +150,8 @@ def main():
     outs = [psa.DecodeOutput(torch.empty((B, Hq, 128), dtype=torch.float32, device=dev),
                              torch.empty((B, Hq), dtype=torch.int32, device=dev),
                              torch.empty((B, Hq), dtype=torch.float32, device=dev),
-                             torch.empty((B, H), dtype=torch.int32, device=dev), None, None,
+                             torch.empty((B, H), dtype=torch.int32, device=dev),
+                             torch.empty((B, Hq), dtype=torch.float32, device=dev), None, None,
                              torch.empty((B, H, 2), dtype=torch.int32, device=dev)) for _ in range(L)]
 
     def step(tunings=None):
@@ -248,6 +250,59 @@ def main():
                  "hbm_frac": dense_bytes / (dense_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                  "psa_speedup": dense_ms / ms_per_step, "kv_reduction_implied": kv_reduction}
 
+    # ---- fixed-budget control: the smallest uniform k that gives every query head at least the true
+    # attention mass PSA's selection holds for it (the adaptive-budget claim of Sec. 1 / Sec. 5.2 on
+    # these inputs).  True mass of a selection = exp(lse of the selection - lse of dense attention).
+    topk = None
+    if not args.no_topk_comparison:
+        dws2 = torch.empty(max(psa.dense_workspace_bytes(kv) for kv in kvs), dtype=torch.uint8, device=dev)
+        dout2 = torch.empty((B, Hq, 128), dtype=torch.float32, device=dev)
+        tout = psa.DecodeOutput(torch.empty((B, Hq, 128), dtype=torch.float32, device=dev),
+                                torch.empty((B, Hq), dtype=torch.int32, device=dev),
+                                torch.empty((B, Hq), dtype=torch.float32, device=dev),
+                                torch.empty((B, H), dtype=torch.int32, device=dev),
+                                torch.empty((B, Hq), dtype=torch.float32, device=dev), None, None, None)
+        k_layer, mass_min, mass_mean = [], [], []
+        for i in range(L):
+            dlse_i = torch.empty((B, Hq), dtype=torch.float32, device=dev)
+            psa.dense_attention(kvs[i], layers[i].q, workspace=dws2, out=dout2, lse=dlse_i)
+            live = torch.isfinite(dlse_i)
+            target = torch.exp(outs[i].lse - dlse_i)
+            mass_min.append(float(target[live].min()) if bool(live.any()) else 1.0)
+            mass_mean.append(float(target[live].mean()) if bool(live.any()) else 1.0)
+            lo, hi = 1, max(int(nblk[i].max()), 1)
+            while lo < hi:
+                mid = (lo + hi) // 2
+                psa.topk_attention(kvs[i], layers[i].q, metas[i], mid, workspace=ws, outputs=tout, tuning=tun)
+                reached = torch.exp(tout.lse - dlse_i) >= target * (1.0 - 1e-5)
+                if bool((reached | ~live).all()):
+                    hi = mid
+                else:
+                    lo = mid + 1
+            k_layer.append(lo)
+        k_all = max(k_layer)
+        for rep in range(1 + args.steps):
+            if rep == 1:
+                e0.record()
+            for i in range(L):
+                psa.topk_attention(kvs[i], layers[i].q, metas[i], k_all, workspace=ws, outputs=tout, tuning=tun)
+        e1.record()
+        torch.cuda.synchronize()
+        assert psa.read_device_error(ws) == 0
+        topk_ms = e0.elapsed_time(e1) / args.steps
+        uni_all = np.minimum(N_total, k_all).sum()
+        uni_layer = sum(np.minimum(N_total[i], k_layer[i]).sum() for i in range(L))
+        topk = {"definition": "smallest k such that top-k attention gives every query head at least the true "
+                              "attention mass of PSA's selection for that head",
+                "uniform_k_all_layers": k_all, "uniform_k_per_layer": k_layer,
+                "psa_blocks_read_per_stream_mean": float(blocks_read.mean()),
+                "psa_true_mass_min": float(min(mass_min)), "psa_true_mass_mean": float(np.mean(mass_mean)),
+                "blocks_uniform_k_over_psa": float(uni_all / max(blocks_read.sum(), 1)),
+                "blocks_per_layer_k_over_psa": float(uni_layer / max(blocks_read.sum(), 1)),
+                "topk_ms_per_step_at_uniform_k": topk_ms, "psa_speedup_over_uniform_k": topk_ms / ms_per_step}
+        log(f"[bench] uniform top-k matching PSA's true mass on every head: k = {k_all} "
+            f"(per layer {k_layer}); PSA reads {blocks_read.mean():.0f} blocks per stream on average")
+
     # ---- the oracle on the host cores, bounded sample ----------------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -297,6 +352,7 @@ def main():
                        "phase_avg_ms_per_layer": phase_avg,
                        "kernel_GBps": kern_gbs},
         "dense_control": dense,
+        "topk_control": topk,
         "metadata_bulk_build": {"ms": meta_ms, "GBps": meta_bytes / (meta_ms * 1e-3) / 1e9},
     }
     for n in ("select", "attend"):

@@ -124,6 +124,10 @@ psa_status psa_build_block_metadata(const psa_kv_desc *desc, void *meta, const i
  *   n_selected   [batch][num_q_heads] blocks attended by that query head (a prefix of the ranking)
  *   mass_est     [batch][num_q_heads] float32, P_acc at the stop (1 if every block was used)
  *   blocks_read  [batch][num_kv_heads] max of n_selected over the group; may be NULL
+ *   lse_out      [batch][num_q_heads] float32, natural log of the sum of exp(scaled logit) over the
+ *                tokens of the attended blocks (-inf for an empty request): what a caller needs to merge
+ *                `out` with attention over other tokens, and, against psa_dense_attention's lse, the
+ *                true share of the attention mass the selection holds; may be NULL
  *   order_out    [batch][num_kv_heads][max_blocks_per_seq] the ranking (logical blocks, -1 beyond
  *                the request's block count); may be NULL
  *   scores_out   [batch][num_kv_heads][max_blocks_per_seq] float32 criticality scores by logical
@@ -136,7 +140,7 @@ psa_status psa_build_block_metadata(const psa_kv_desc *desc, void *meta, const i
 psa_status psa_decode_attention(const psa_kv_desc *desc, const void *q, const void *meta,
                                 float threshold, int32_t check_granularity, float *out,
                                 int32_t *n_selected, float *mass_est, int32_t *blocks_read,
-                                int32_t *order_out, float *scores_out, int32_t *traffic_out,
+                                float *lse_out, int32_t *order_out, float *scores_out, int32_t *traffic_out,
                                 const psa_tuning *tuning, void *workspace, size_t workspace_bytes,
                                 void *stream);
 
@@ -150,7 +154,7 @@ psa_status psa_decode_attention(const psa_kv_desc *desc, const void *q, const vo
  */
 psa_status psa_topk_attention(const psa_kv_desc *desc, const void *q, const void *meta, int32_t k_blocks,
                               float *out, int32_t *n_selected, float *mass_est, int32_t *blocks_read,
-                              int32_t *order_out, float *scores_out, int32_t *traffic_out,
+                              float *lse_out, int32_t *order_out, float *scores_out, int32_t *traffic_out,
                               const psa_tuning *tuning, void *workspace, size_t workspace_bytes, void *stream);
 
 /*

@@ -284,7 +284,7 @@ void oracle_dense_attention(const oracle_shape *sh, const uint16_t *q, const uin
 void oracle_attend_prefix(const oracle_shape *sh, const uint16_t *q, const uint16_t *k_pool,
                           const uint16_t *v_pool, const int32_t *block_table,
                           const int32_t *ctx_lens, const int32_t *order, const int32_t *n_take,
-                          double *out) {
+                          double *out, double *lse /* [batch][Hq] log of the softmax denominator, or NULL */) {
     const int Hq = sh->num_q_heads, H = sh->num_kv_heads, D = sh->head_dim, T = sh->page_size;
     const int G = Hq / H;
 #pragma omp parallel for collapse(2) schedule(dynamic)
@@ -296,6 +296,7 @@ void oracle_attend_prefix(const oracle_shape *sh, const uint16_t *q, const uint1
             const int32_t *ord = order + ((size_t)r * H + h) * sh->max_blocks;
             double *o = out + ((size_t)r * Hq + hq) * D;
             for (int c = 0; c < D; ++c) o[c] = 0.0;
+            if (lse) lse[(size_t)r * Hq + hq] = -INFINITY;
             if (n <= 0) continue;
             double *s = (double *)malloc((size_t)n * T * sizeof(double));
             double smax = -INFINITY, denom = 0.0;
@@ -310,6 +311,7 @@ void oracle_attend_prefix(const oracle_shape *sh, const uint16_t *q, const uint1
                 int valid = valid_tokens(ctx, T, ord[i]);
                 for (int t = 0; t < valid; ++t) denom += exp(s[(size_t)i * T + t] - smax);
             }
+            if (lse) lse[(size_t)r * Hq + hq] = smax + log(denom);
             for (int i = 0; i < n; ++i) {
                 int b = ord[i], page = block_table[(size_t)r * sh->max_blocks + b];
                 int valid = valid_tokens(ctx, T, b);

@@ -171,17 +171,20 @@ def dense_attention(pb: Problem):
     return out, lse
 
 
-def attend_prefix(pb: Problem, order: np.ndarray, n_take: np.ndarray) -> np.ndarray:
+def attend_prefix(pb: Problem, order: np.ndarray, n_take: np.ndarray, want_lse: bool = False):
+    """Softmax attention over the first n_take ranked blocks, by the definition; with want_lse also
+    the natural log of its denominator, sum over those tokens of exp(scaled logit)."""
     B, Hq, H, D, T, P, MB = pb.dims
     order, n_take = _i32(order), _i32(n_take)
     assert order.shape == (B, H, MB) and n_take.shape == (B, Hq)
     out = np.zeros((B, Hq, D))
+    lse = np.zeros((B, Hq)) if want_lse else None
     sh = pb.shape
     _load().oracle_attend_prefix(C.byref(sh), _p(pb.q, C.c_uint16), _p(pb.k_pool, C.c_uint16),
                                  _p(pb.v_pool, C.c_uint16), _p(pb.block_table, C.c_int32),
                                  _p(pb.ctx_lens, C.c_int32), _p(order, C.c_int32),
-                                 _p(n_take, C.c_int32), _p(out, C.c_double))
-    return out
+                                 _p(n_take, C.c_int32), _p(out, C.c_double), _p(lse, C.c_double))
+    return (out, lse) if want_lse else out
 
 
 @dataclass

@@ -81,10 +81,10 @@ def load_library() -> C.CDLL:
         lib.psa_build_block_metadata.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, i32, vp]
         lib.psa_decode_attention.restype = C.c_int
         lib.psa_decode_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, f32, i32, vp, vp, vp, vp, vp, vp,
-                                             vp, C.POINTER(_Tuning), vp, sz, vp]
+                                             vp, vp, C.POINTER(_Tuning), vp, sz, vp]
         lib.psa_topk_attention.restype = C.c_int
         lib.psa_topk_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, i32, vp, vp, vp, vp, vp, vp, vp,
-                                           C.POINTER(_Tuning), vp, sz, vp]
+                                           vp, C.POINTER(_Tuning), vp, sz, vp]
         lib.psa_dense_attention.restype = C.c_int
         lib.psa_dense_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, vp, sz, vp]
         lib.psa_read_device_error.restype = C.c_int
@@ -171,6 +171,7 @@ class DecodeOutput:
     n_selected: torch.Tensor   # int32 [B][Hq]
     mass_est: torch.Tensor     # float32 [B][Hq]
     blocks_read: torch.Tensor  # int32 [B][Hkv]
+    lse: torch.Tensor          # float32 [B][Hq], natural-log sum of exponentiated logits of the attended tokens
     order: torch.Tensor | None     # int32 [B][Hkv][max_blocks]
     scores: torch.Tensor | None    # float32 [B][Hkv][max_blocks]
     traffic: torch.Tensor | None   # int32 [B][Hkv][2]: K blocks, V blocks loaded
@@ -194,6 +195,7 @@ def decode_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, threshold
             torch.empty((B, Hq), dtype=torch.int32, device=dev),
             torch.empty((B, Hq), dtype=torch.float32, device=dev),
             torch.empty((B, H), dtype=torch.int32, device=dev),
+            torch.empty((B, Hq), dtype=torch.float32, device=dev),
             torch.empty((B, H, MB), dtype=torch.int32, device=dev) if want_order else None,
             torch.empty((B, H, MB), dtype=torch.float32, device=dev) if want_scores else None,
             torch.empty((B, H, 2), dtype=torch.int32, device=dev) if want_traffic else None)
@@ -201,8 +203,8 @@ def decode_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, threshold
     assert q.is_contiguous() and meta.is_contiguous()
     st = load_library().psa_decode_attention(
         C.byref(d), _ptr(q), _ptr(meta), float(threshold), int(check_granularity), _ptr(o.out),
-        _ptr(o.n_selected), _ptr(o.mass_est), _ptr(o.blocks_read), _ptr(o.order), _ptr(o.scores),
-        _ptr(o.traffic), C.byref(t) if t else None, _ptr(workspace), workspace.numel(), _stream(stream))
+        _ptr(o.n_selected), _ptr(o.mass_est), _ptr(o.blocks_read), _ptr(o.lse), _ptr(o.order),
+        _ptr(o.scores), _ptr(o.traffic), C.byref(t) if t else None, _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "psa_decode_attention")
     o._workspace = workspace   # keeps the buffer alive until the caller has synchronised
     return o
@@ -225,6 +227,7 @@ def topk_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, k_blocks: i
             torch.empty((B, Hq), dtype=torch.int32, device=dev),
             torch.empty((B, Hq), dtype=torch.float32, device=dev),
             torch.empty((B, H), dtype=torch.int32, device=dev),
+            torch.empty((B, Hq), dtype=torch.float32, device=dev),
             torch.empty((B, H, MB), dtype=torch.int32, device=dev) if want_order else None,
             torch.empty((B, H, MB), dtype=torch.float32, device=dev) if want_scores else None,
             torch.empty((B, H, 2), dtype=torch.int32, device=dev) if want_traffic else None)
@@ -232,7 +235,7 @@ def topk_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, k_blocks: i
     assert q.is_contiguous() and meta.is_contiguous()
     st = load_library().psa_topk_attention(
         C.byref(d), _ptr(q), _ptr(meta), int(k_blocks), _ptr(o.out), _ptr(o.n_selected), _ptr(o.mass_est),
-        _ptr(o.blocks_read), _ptr(o.order), _ptr(o.scores), _ptr(o.traffic), C.byref(t) if t else None,
+        _ptr(o.blocks_read), _ptr(o.lse), _ptr(o.order), _ptr(o.scores), _ptr(o.traffic), C.byref(t) if t else None,
         _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "psa_topk_attention")
     o._workspace = workspace

@@ -112,7 +112,7 @@ hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const Decode
     if (ev) (void)hipEventRecord(ev[3], st);
     if ((e = launch_attend(kv, d->dtype, G, ws, plan, st)) != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[4], st);
-    e = launch_finalize(kv, ws, G, plan.chunk_blocks, a.out, a.n_selected, a.mass_est, a.blocks_read,
+    e = launch_finalize(kv, ws, G, plan.chunk_blocks, a.out, a.n_selected, a.mass_est, a.blocks_read, a.lse_out,
                         a.traffic_out, st);
     if (ev) (void)hipEventRecord(ev[5], st);
     return e;

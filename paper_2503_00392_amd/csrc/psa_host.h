@@ -57,6 +57,7 @@ struct DecodeArgs {
     int32_t *n_selected;
     float *mass_est;
     int32_t *blocks_read, *order_out;
+    float *lse_out;
     float *scores_out;
     int32_t *traffic_out;
 };
@@ -73,7 +74,7 @@ hipError_t launch_select(const KvView &kv, int dtype, int G, const void *q, cons
 hipError_t launch_attend(const KvView &kv, int dtype, int G, const DecodeWs &ws, const DecodePlan &plan,
                          hipStream_t st);
 hipError_t launch_finalize(const KvView &kv, const DecodeWs &ws, int G, int VU, float *out,
-                           int32_t *n_selected, float *mass_est, int32_t *blocks_read,
+                           int32_t *n_selected, float *mass_est, int32_t *blocks_read, float *lse_out,
                            int32_t *traffic_out, hipStream_t st);
 
 }  // namespace psa

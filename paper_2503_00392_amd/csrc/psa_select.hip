@@ -189,7 +189,10 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
                     const float M2 = fminf(Lmin, __uint_as_float((uint32_t)(a >> 32)));
                     const int cidx = fr + i;
                     const int n_end = min((cidx + 1) * KU, N);
-                    if (p_acc(L2, M2, N - n_end) > eps) {
+                    // a stop inside this chunk needs a position where the rule is tested (line 17 is reached
+                    // every m blocks and at the last block) and, P_acc being non-decreasing, a pass at its end
+                    const bool tested = (n_end / m) * m > cidx * KU || n_end == N;
+                    if (tested && p_acc(L2, M2, N - n_end) > eps) {
                         // the stop may lie in this chunk: block by block, in rank order
                         const int b0 = cidx * KU;
                         const float *lb = ws.block_lse + ((size_t)s * kv.max_blocks + b0) * G + lane;

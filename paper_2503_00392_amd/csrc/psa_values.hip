@@ -185,6 +185,7 @@ __global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, i
                                                        int32_t *__restrict__ n_selected,
                                                        float *__restrict__ mass_est,
                                                        int32_t *__restrict__ blocks_read,
+                                                       float *__restrict__ lse_out,
                                                        int32_t *__restrict__ traffic_out) {
     __shared__ float red[512];
     __shared__ float wgt[kMaxBlocks / 4];        // per-unit rescale factor (value units are >= 4 blocks)
@@ -259,6 +260,7 @@ __global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, i
         if (tid == 0) {
             n_selected[qi] = n;
             mass_est[qi] = P;
+            if (lse_out) lse_out[qi] = den > 0.0f ? (M + log2_fast(den)) * kLn2 : -INFINITY;
             if (g == 0) {
                 int mx = 0;
                 for (int x = 0; x < G; ++x) {
@@ -290,10 +292,10 @@ hipError_t launch_attend(const KvView &kv, int dtype, int G, const DecodeWs &ws,
 }
 
 hipError_t launch_finalize(const KvView &kv, const DecodeWs &ws, int G, int VU, float *out,
-                           int32_t *n_selected, float *mass_est, int32_t *blocks_read,
+                           int32_t *n_selected, float *mass_est, int32_t *blocks_read, float *lse_out,
                            int32_t *traffic_out, hipStream_t st) {
     finalize_kernel<<<kv.batch * kv.num_kv_heads * G, 512, 0, st>>>(kv, ws, G, VU, out, n_selected, mass_est,
-                                                                    blocks_read, traffic_out);
+                                                                    blocks_read, lse_out, traffic_out);
     return hipGetLastError();
 }
 

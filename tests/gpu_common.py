@@ -12,6 +12,7 @@ from workloads import LayerInputs, as_bits
 
 OUT_RTOL = 2e-3        # relative L2 error of an output row, fp16/bf16 inputs, fp32 accumulation
 SCORE_ATOL = 1e-3      # score distance to the stopping boundary inside which a block may differ
+LSE_ATOL = 2e-3        # natural-log units, on values of order 10
 PACC_ATOL = 1e-5       # |P_acc - eps| inside which the stop index itself may flip
 
 
@@ -93,7 +94,11 @@ def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, request
     assert rep.worst_score <= SCORE_ATOL / 4, f"score error {rep.worst_score}"
 
     # -- output against attention over the GPU's OWN selected prefix (always) ----------------------
-    own = po.attend_prefix(sub, g_order, g_n)
+    own, own_lse = po.attend_prefix(sub, g_order, g_n, want_lse=True)
+    g_lse = gpu.lse.cpu().numpy().astype(np.float64)[requests]
+    fin = np.isfinite(own_lse)
+    assert np.array_equal(np.isneginf(g_lse), ~fin), "lse must be -inf exactly for empty requests"
+    assert np.abs(g_lse[fin] - own_lse[fin]).max(initial=0.0) <= LSE_ATOL, "lse of the attended prefix"
     err_own = rel_l2(g_out, own)
     rep.worst_out_vs_own_set = float(err_own.max()) if err_own.size else 0.0
     assert rep.worst_out_vs_own_set <= OUT_RTOL, f"output vs own set: {rep.worst_out_vs_own_set}"

@@ -30,7 +30,7 @@ def declared_functions():
 
 def test_header_declares_the_named_entry_points():
     names = declared_functions()
-    for want in ("psa_build_block_metadata", "psa_decode_attention", "psa_dense_attention",
+    for want in ("psa_build_block_metadata", "psa_decode_attention", "psa_dense_attention", "psa_topk_attention",
                  "psa_decode_workspace_bytes", "psa_dense_workspace_bytes", "psa_read_device_error",
                  "psa_status_string"):
         assert want in names
@@ -64,7 +64,7 @@ def _desc(**kw):
 def _decode(lib, d, threshold=0.9, m=1, q=0x10, meta=0x20, out=0x30, nsel=0x40, mass=0x50, ws=0x60,
             ws_bytes=1 << 40, tuning=None):
     return lib.psa_decode_attention(C.byref(d), q, meta, threshold, m, out, nsel, mass, None, None, None,
-                                    None, C.byref(tuning) if tuning else None, ws, ws_bytes, None)
+                                    None, None, C.byref(tuning) if tuning else None, ws, ws_bytes, None)
 
 
 def test_workspace_sizes(lib):
@@ -108,8 +108,12 @@ def test_decode_rejects_bad_scalars_and_null_buffers(lib):
     assert _decode(lib, d, tuning=T(0, -1, 0, 0, 0, None)) == 1
     assert _decode(lib, d, tuning=T(0, 0, 0, 2, 0, None)) == 1
     assert _decode(lib, d, tuning=T(0, 0, 0, 0, -3, None)) == 1
-    assert lib.psa_decode_attention(None, 1, 1, 0.5, 1, 1, 1, 1, None, None, None, None, None, 1, 1 << 30,
-                                    None) == 1
+    assert lib.psa_decode_attention(None, 1, 1, 0.5, 1, 1, 1, 1, None, None, None, None, None, None, 1,
+                                    1 << 30, None) == 1
+    assert lib.psa_topk_attention(C.byref(d), 0x10, 0x20, 0, 0x30, 0x40, 0x50, None, None, None, None, None,
+                                  None, 0x60, 1 << 40, None) == 1          # budget below one block
+    assert lib.psa_topk_attention(C.byref(d), 0x10, 0x20, 4, 0x30, 0x40, 0x50, None, None, None, None, None,
+                                  None, 0x60, 64, None) == 3
 
 
 def test_empty_batch_is_ok_and_enqueues_nothing(lib):

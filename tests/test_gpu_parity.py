@@ -177,8 +177,10 @@ def test_topk_matches_oracle(psa, case, k):
     assert np.array_equal(gpu.blocks_read.cpu().numpy(), np.repeat(np.minimum(k, N)[:, None], cfg.num_kv_heads, 1))
     g_order = gpu.order.cpu().numpy()
     g_out = gpu.out.cpu().numpy().astype(np.float64)
-    own = po.attend_prefix(pb, g_order, g_n)
+    own, own_lse = po.attend_prefix(pb, g_order, g_n, want_lse=True)
     assert gc.rel_l2(g_out, own).max() <= gc.OUT_RTOL
+    fin = np.isfinite(own_lse)
+    assert np.abs(gpu.lse.cpu().numpy()[fin] - own_lse[fin]).max(initial=0.0) <= gc.LSE_ATOL
     G = cfg.group
     for r in range(cfg.batch):
         n = int(want_n[r, 0])

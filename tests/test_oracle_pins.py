@@ -403,3 +403,24 @@ def test_topk_equals_progressive_loop_with_threshold_zero_and_microbatch_k(k):
     assert np.array_equal(a.n_selected, b.n_selected)
     np.testing.assert_allclose(a.out, b.out, rtol=1e-11, atol=1e-12)
     np.testing.assert_allclose(a.mass_est, b.mass_est, rtol=1e-12)
+
+
+def test_prefix_lse_is_logsumexp_of_the_attended_logits_and_true_mass_follows():
+    """The log-denominator of attention over a ranked prefix, against scipy's logsumexp over the same
+    tokens' logits; over all blocks it is the dense one; exp(prefix - dense) is the true-mass curve."""
+    from scipy.special import logsumexp
+    pb = _problem(50)
+    res = po.psa_decode(pb, 0.8, 1, curves=True)
+    _, lse = po.attend_prefix(pb, res.order, res.n_selected, want_lse=True)
+    _, dense_lse = ref.dense(pb)
+    nb = pb.num_blocks()
+    for r in range(3):
+        for hq in range(4):
+            n = res.n_selected[r, hq]
+            blocks = res.order[r, hq // 2, :n]
+            want = logsumexp(ref.block_lse(pb, r, hq)[blocks])
+            assert abs(lse[r, hq] - want) < 1e-10
+            assert abs(np.exp(lse[r, hq] - dense_lse[r, hq]) - res.true_mass[r, hq, n - 1]) < 1e-10
+    full = np.repeat(nb[:, None], 4, 1).astype(np.int32)
+    _, lse_all = po.attend_prefix(pb, res.order, full, want_lse=True)
+    np.testing.assert_allclose(lse_all, dense_lse, rtol=0, atol=1e-10)
