@@ -115,11 +115,10 @@ __device__ __forceinline__ float p_acc(float Lacc, float Lmin, int n_left) {
 }
 
 __device__ __forceinline__ void nap(int tries) {
-    // grows from about half a microsecond to about twelve
+    // about half a microsecond, then about two: long enough that the pollers of one stream stay well
+    // below what one cache line serves, short enough that an opening window is noticed at once
     __builtin_amdgcn_s_sleep(20);
     if (tries > 1) __builtin_amdgcn_s_sleep(60);
-    if (tries > 3) __builtin_amdgcn_s_sleep(127);
-    if (tries > 6) { __builtin_amdgcn_s_sleep(127); __builtin_amdgcn_s_sleep(127); }
 }
 
 template <int G>
