@@ -359,8 +359,9 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     unsigned long long w = pack2(aggL, aggMin);
     if (w >= kAggArmed) w = kAggArmed - 1;     // a NaN that happens to look like one of the marks
     unsigned long long *cw = &ws.agg[((size_t)s * ws.max_chunks + c) * G];
+    // The G words need no order among themselves: the fold takes a chunk only when it sees all of
+    // them, and a chunk it finds half published it simply looks at again.
     if (lane >= 1 && lane < G) st_relaxed(cw + lane, w);
-    stores_done();                              // words 1..G-1 are in place before word 0 is exchanged in
     unsigned long long old = 0;
     if (lane == 0) old = __hip_atomic_exchange(cw, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (uniform((int)(old == kAggArmed))) fold_stream<G>(kv, ws, s, eps, m, CB);
