@@ -35,27 +35,22 @@ struct KvView {
 // "Chunk" = `CB` consecutive ranked blocks: the unit in which keys are read and folded into the
 // stop rule, and in which values are read.
 //
-// Per-stream control block of the progressive kernel: four 128-byte lines, so that the two ticket
-// counters, the progress words that waiting waves poll, and the fold's own state never share a
-// cache line (accesses to one line are served one after the other).
-constexpr int32_t kUnknownTotal = 0x7fffffff;
+// Per-stream control block of the progressive kernel: four 128-byte lines, so that the ticket
+// counter, the progress word that idle workgroups poll, the bookkeeping counters and the fold's own
+// state never share a cache line (accesses to one line are served one after the other).
 struct alignas(128) StreamCtl {
     // line 0: key tickets
     int32_t k_next;     // next key chunk to hand out (fetch-and-add)
     int32_t pad0[31];
-    // line 1: progress, written by the folding wave only, each as ONE 64-bit store
+    // line 1: progress, written by the folding wave only, as ONE 64-bit store
     unsigned long long key_progress;    // low: frontier = key chunks folded into the stop rule so far;
-                                        // high: k_limit = key chunks worth reading (all of them until the
-                                        // fold has finished, then what it used)
-    unsigned long long value_progress;  // low: v_avail = value units released so far;
-                                        // high: v_total = value units of the stream, kUnknownTotal until
-                                        // every head has stopped or the blocks ran out
-    int32_t pad1[28];
-    // line 2: value tickets
-    int32_t v_next;     // next value unit to hand out (compare-and-swap, never beyond v_avail)
+                                        // high: k_limit = key chunks worth reading (all of them, or what a
+                                        // block budget covers, until the fold has finished; then what it used)
+    int32_t pad1[30];
+    // line 2: counters
     int32_t k_blocks;   // key slices loaded (traffic accounting)
-    int32_t attached;   // waves working on this stream beyond its first ones (joiners)
-    int32_t pad2[29];
+    int32_t attached;   // workgroups working on this stream beyond its first ones (joiners)
+    int32_t pad2[30];
     // line 3: fold state, owned by the folding wave
     float Lacc[8];               // per head: log2 of AS_acc over the folded chunks
     float Lmin[8];               // per head: log2 of AS_min over the folded chunks

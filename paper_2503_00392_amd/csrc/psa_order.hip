@@ -133,9 +133,8 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         // key chunks that may ever be handed out: all of them, or those a fixed budget of blocks covers
         const int nlim = budget_blocks > 0 ? min(N, budget_blocks) : N;
         const unsigned nch = (unsigned)((nlim + KU - 1) / KU);
-        c->k_next = 0; c->v_next = 0; c->k_blocks = 0; c->attached = 0;
+        c->k_next = 0; c->k_blocks = 0; c->attached = 0;
         c->key_progress = (unsigned long long)nch << 32;                                  // frontier 0
-        c->value_progress = (unsigned long long)(N == 0 ? 0u : (unsigned)kUnknownTotal) << 32;   // nothing released
         for (int g = 0; g < 8; ++g) { c->Lacc[g] = -INFINITY; c->Lmin[g] = INFINITY; c->stop[g] = ~0ull; }
     }
     if (part == 0) {

@@ -137,15 +137,15 @@ struct SelectShared {
 // Leaves either with the stream's key side closed, or with the mark on the first unpublished chunk.
 // =================================================================================================
 template <int G>
-__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU) {
+__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU, int fr) {
+    // fr: the chunk the mark was on, which is where the previous holder of the fold stopped
     const int lane = threadIdx.x & 63;
     StreamCtl *ctl = &ws.ctl[s];
     const int ctx = stream_ctx(kv, s);
     const int N = (ctx + kPage - 1) / kPage;
     // chunks that will ever be published: all of them unless the ranking kernel set a budget
+    // (all loads of this prologue are issued before the first of them is waited for)
     const unsigned long long kp0 = ld_relaxed(&ctl->key_progress);
-    const int nch = uniform((int)(kp0 >> 32));
-    int fr = uniform((int)(kp0 & 0xffffffffull));
     int fr_pub = fr;                           // frontier as the progress word shows it
     float Lacc = -INFINITY, Lmin = INFINITY;
     unsigned long long stop = 0ull;            // lanes >= G count as stopped
@@ -159,6 +159,8 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
     const int hg = lane < G ? lane : 0;
     bool finished = false;
     int walked = fr;
+    int nch = ws.max_chunks;                   // until the limit has arrived; words beyond it hold the sentinel
+    bool first = true;
     while (!finished) {
         unsigned long long v[4];
         int k = 0;
@@ -168,6 +170,7 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
             const int ci = fr + u * CPR + lane / G;
             v[u] = (ci < nch) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
         }
+        if (first) { nch = uniform((int)(kp0 >> 32)); first = false; }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const unsigned long long pub = __ballot(v[u] < kAggArmed);
@@ -221,23 +224,24 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
         fr = walked;
         if (fr >= nch) finished = true;
         if (finished) break;
-        // leave the state and the progress words behind: waiting key workers and value workers move on
+        const bool moved = walked != fr_pub;
+        fr_pub = walked;
+        if (!gap) {
+            // all 4 rounds were published: open the window further and load the next ones
+            if (lane == 0 && moved)
+                st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)nch << 32) | (unsigned)walked);
+            continue;
+        }
+        // chunk fr is not published: leave the state and the frontier behind and mark the chunk; if it
+        // was published meanwhile the mark fails and the fold simply carries on
         if (lane < G) {
             st_relaxed(&ctl->Lacc[lane], Lacc);
             st_relaxed(&ctl->Lmin[lane], Lmin);
             st_relaxed(&ctl->stop[lane], stop);
         }
-        stores_done();
-        if (lane == 0 && walked != fr_pub) {
+        if (lane == 0 && moved)
             st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)nch << 32) | (unsigned)walked);
-            st_relaxed(&ctl->value_progress,
-                       ((unsigned long long)(unsigned)kUnknownTotal << 32) | (unsigned)(walked));
-        }
-        fr_pub = walked;
-        if (!gap) continue;            // all 4 rounds were published: load the next ones
-        // chunk fr is not published: mark it; if it was published meanwhile the mark fails and the
-        // fold simply carries on
-        stores_done();
+        stores_done();                 // whoever finds the mark finds the state, and stores its own frontier later
         unsigned long long seen = 0;
         if (lane == 0) {
             unsigned long long expected = kAggSentinel;
@@ -248,17 +252,10 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
         }
         if (uniform((int)(seen == kAggSentinel))) return;     // marked: the chunk's publisher carries on
     }
-    // every head has stopped, or the blocks ran out: close the key side, release the last value units
+    // every head has stopped, or the blocks ran out: close the key side (limit = frontier)
     if (lane < G) st_relaxed(&ctl->stop[lane], stop);
-    int nmax = (lane < G) ? ((stop == ~0ull) ? N : (int)(stop >> 32)) : 0;
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) nmax = max(nmax, __shfl_xor(nmax, d));
-    const int vt = (nmax + KU - 1) / KU;
-    stores_done();
-    if (lane == 0) {
+    if (lane == 0)
         st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)walked << 32) | (unsigned)walked);
-        st_relaxed(&ctl->value_progress, ((unsigned long long)(unsigned)vt << 32) | (unsigned)vt);
-    }
 }
 
 // =================================================================================================
@@ -364,7 +361,7 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     if (lane >= 1 && lane < G) st_relaxed(cw + lane, w);
     unsigned long long old = 0;
     if (lane == 0) old = __hip_atomic_exchange(cw, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (uniform((int)(old == kAggArmed))) fold_stream<G>(kv, ws, s, eps, m, CB);
+    if (uniform((int)(old == kAggArmed))) fold_stream<G>(kv, ws, s, eps, m, CB, c);
 }
 
 // =================================================================================================
