@@ -88,7 +88,18 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
         ++trace_n;                                                                             \
     }
 #define PSA_NOW() wall_clock64()
+#define PSA_STAMP(K) if (threadIdx.x == 0) sh.stamp[K] = wall_clock64();
+#define PSA_TRACE_SPAN(KIND, S, IDX, T0, T1)                                                   \
+    if (threadIdx.x == 0 && trace_n < kTracePerWave) {                                         \
+        unsigned long long *rec_ = ws.trace + 8 + ((size_t)blockIdx.x * kTracePerWave + trace_n) * 4; \
+        rec_[0] = ((unsigned long long)(KIND) << 56) | ((unsigned long long)(S) << 32) | (unsigned)(IDX); \
+        rec_[1] = (unsigned long long)blockIdx.x;                                              \
+        rec_[2] = (T0); rec_[3] = (T1);                                                        \
+        ++trace_n;                                                                             \
+    }
 #else
+#define PSA_STAMP(K)
+#define PSA_TRACE_SPAN(KIND, S, IDX, T0, T1)
 #define PSA_TRACE(KIND, S, IDX, T0)
 #define PSA_NOW() 0ull
 #endif
@@ -129,6 +140,9 @@ struct SelectShared {
     int what;                              // 0: chunk `item`; 2: nothing right now; 3: all handed out; 4: give up
     int item;
     int next;                              // stream to join, -1 = leave
+#ifdef PSA_ENABLE_TRACE
+    unsigned long long stamp[8];
+#endif
 };
 
 // =================================================================================================
@@ -290,6 +304,7 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     }
     float *lg_out = ws.logits + row0 * (kPage * G);
     lds_barrier();
+    PSA_STAMP(0)
 
     // ---- keys: wave w takes blocks [32*it + 4*w, +4).  A operand: row n = token n of the block,
     //      same channel assignment as the queries; 64 contiguous bytes per token and step. ------------
@@ -337,12 +352,15 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
             }
         }
     }
+    PSA_STAMP(1)
     lds_barrier();
+    PSA_STAMP(2)
     // the blocks' L_b, for the fold's block-by-block pass; complete before the chunk is published
     for (int idx = tid; idx < nblk * G; idx += kSelectThreads)
         st_relaxed(&ws.block_lse[row0 * G + idx], sh.Lb[idx / G][idx % G]);
     stores_done();
     lds_barrier();
+    PSA_STAMP(3)
     if (wave != 0) return;
 
     // ---- publish: the chunk's fold over its own blocks in rank order, one lane per head ------------------
@@ -361,7 +379,9 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     if (lane >= 1 && lane < G) st_relaxed(cw + lane, w);
     unsigned long long old = 0;
     if (lane == 0) old = __hip_atomic_exchange(cw, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    PSA_STAMP(4)
     if (uniform((int)(old == kAggArmed))) fold_stream<G>(kv, ws, s, eps, m, CB, c);
+    PSA_STAMP(5)
 }
 
 // =================================================================================================
@@ -384,6 +404,7 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
         const int N = (stream_ctx(kv, home) + kPage - 1) / kPage;
         int tries = 0, k_loaded = 0;
         while (true) {
+            [[maybe_unused]] const unsigned long long td = PSA_NOW();
             if (tid == 0) {
                 int what = 3, item = -1;
                 const unsigned long long kp = ld_relaxed(&ctl->key_progress);
@@ -402,10 +423,17 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
             }
             lds_barrier();
             const int what = sh.what, item = sh.item;
+            PSA_TRACE(9, home, what, td);
             if (what == 0) {
                 [[maybe_unused]] const unsigned long long t0 = PSA_NOW();
                 process_chunk<DT, G>(sh, kv, q, ws, eps, m, CB, home, item);
                 PSA_TRACE(1, home, item, t0);
+                PSA_TRACE_SPAN(10, home, item, t0, sh.stamp[0]);             // ticket known -> pages staged
+                PSA_TRACE_SPAN(11, home, item, sh.stamp[0], sh.stamp[1]);    // keys loaded, logits computed (wave 0)
+                PSA_TRACE_SPAN(12, home, item, sh.stamp[1], sh.stamp[2]);    // the other waves
+                PSA_TRACE_SPAN(13, home, item, sh.stamp[2], sh.stamp[3]);    // stores complete
+                PSA_TRACE_SPAN(14, home, item, sh.stamp[3], sh.stamp[4]);    // published
+                PSA_TRACE_SPAN(15, home, item, sh.stamp[4], sh.stamp[5]);    // fold, if it was this chunk's turn
                 k_loaded += min(CB, N - item * CB);
                 tries = 0;
             } else if (what == 2) {
