@@ -90,6 +90,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-topk-comparison", action="store_true")
+    ap.add_argument("--no-scorer-comparison", action="store_true")
     ap.add_argument("--cpu-layers", type=str, default="", help="layers the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -303,6 +304,49 @@ def main():
         log(f"[bench] uniform top-k matching PSA's true mass on every head: k = {k_all} "
             f"(per layer {k_layer}); PSA reads {blocks_read.mean():.0f} blocks per stream on average")
 
+    # ---- ranking quality of the two scorers over the same metadata: how many blocks PSA reads with each,
+    # what share of the true attention mass the selection then holds, how far the rule's own estimate
+    # P_acc overshoots it (the estimate is only a bound under an ideal ranking, Sec. 3.2) -------------------
+    scorers = None
+    if not args.no_scorer_comparison:
+        dws3 = torch.empty(max(psa.dense_workspace_bytes(kv) for kv in kvs), dtype=torch.uint8, device=dev)
+        dout3 = torch.empty((B, Hq, 128), dtype=torch.float32, device=dev)
+        dlses = []
+        for i in range(L):
+            dl = torch.empty((B, Hq), dtype=torch.float32, device=dev)
+            psa.dense_attention(kvs[i], layers[i].q, workspace=dws3, out=dout3, lse=dl)
+            dlses.append(dl)
+        so = psa.DecodeOutput(torch.empty((B, Hq, 128), dtype=torch.float32, device=dev),
+                              torch.empty((B, Hq), dtype=torch.int32, device=dev),
+                              torch.empty((B, Hq), dtype=torch.float32, device=dev),
+                              torch.empty((B, H), dtype=torch.int32, device=dev),
+                              torch.empty((B, Hq), dtype=torch.float32, device=dev), None, None, None)
+        scorers = {}
+        for name, code in (("upper_bound", psa.SCORE_UPPER_BOUND), ("cuboid_center", psa.SCORE_CUBOID_CENTER)):
+            read, true_mass, gap, short = [], [], [], []
+            for rep in range(2):
+                if rep == 1:
+                    e0.record()
+                for i in range(L):
+                    psa.decode_attention(kvs[i], layers[i].q, metas[i], eps, m, workspace=ws, outputs=so,
+                                         tuning=tun, scorer=code)
+                    if rep == 0:
+                        live = torch.isfinite(dlses[i])
+                        tm = torch.exp(so.lse - dlses[i])[live]
+                        read.append(so.blocks_read.double().mean().item())
+                        true_mass.append(tm.double().mean().item())
+                        gap.append((so.mass_est[live] - tm).double().mean().item())
+                        short.append((tm < eps).double().mean().item())
+            e1.record()
+            torch.cuda.synchronize()
+            scorers[name] = {"blocks_read_per_stream_mean": float(np.mean(read)),
+                             "true_mass_mean": float(np.mean(true_mass)),
+                             "estimate_minus_true_mass_mean": float(np.mean(gap)),
+                             "heads_with_true_mass_below_threshold": float(np.mean(short)),
+                             "ms_per_step": e0.elapsed_time(e1)}
+            log(f"[bench] scorer {name}: {scorers[name]}")
+        assert psa.read_device_error(ws) == 0
+
     # ---- the oracle on the host cores, bounded sample ----------------------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -353,6 +397,7 @@ def main():
                        "kernel_GBps": kern_gbs},
         "dense_control": dense,
         "topk_control": topk,
+        "scorer_comparison": scorers,
         "metadata_bulk_build": {"ms": meta_ms, "GBps": meta_bytes / (meta_ms * 1e-3) / 1e9},
     }
     for n in ("select", "attend"):

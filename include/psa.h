@@ -54,6 +54,15 @@ enum {
 };
 
 /* Shapes and layout of ONE layer's paged KV cache (PagedAttention layout, Sec. 2.1 "KV Cache"). */
+/* How a block's criticality score is computed from its metadata (Algorithm 1, line 5: CS = q . B_meta).
+ * Both read the same per-channel min/max metadata and take the maximum over the query heads that
+ * share the KV head.
+ *   PSA_SCORE_UPPER_BOUND    sum_c max(q_c kmin_c, q_c kmax_c) / sqrt(d): the largest scaled logit any
+ *                            key inside the block's bounding cuboid can give (default)
+ *   PSA_SCORE_CUBOID_CENTER  q . (kmin + kmax)/2 / sqrt(d): the scaled logit of the cuboid's centre, a
+ *                            reading of the "cuboid-mean" metadata Sec. 3.1 names as its default      */
+typedef enum { PSA_SCORE_UPPER_BOUND = 0, PSA_SCORE_CUBOID_CENTER = 1 } psa_scorer;
+
 typedef struct {
     int32_t batch;              /* decode requests, one query token each                          */
     int32_t num_q_heads;        /* Hq                                                             */
@@ -138,7 +147,7 @@ psa_status psa_build_block_metadata(const psa_kv_desc *desc, void *meta, const i
  * A request with ctx_len 0 gets out = 0, n_selected = 0, mass_est = 0.
  */
 psa_status psa_decode_attention(const psa_kv_desc *desc, const void *q, const void *meta,
-                                float threshold, int32_t check_granularity, float *out,
+                                float threshold, int32_t check_granularity, int32_t scorer, float *out,
                                 int32_t *n_selected, float *mass_est, int32_t *blocks_read,
                                 float *lse_out, int32_t *order_out, float *scores_out, int32_t *traffic_out,
                                 const psa_tuning *tuning, void *workspace, size_t workspace_bytes,
@@ -153,7 +162,7 @@ psa_status psa_decode_attention(const psa_kv_desc *desc, const void *q, const vo
  * of psa_decode_attention; k_blocks < 1 is PSA_ERR_INVALID_ARG.
  */
 psa_status psa_topk_attention(const psa_kv_desc *desc, const void *q, const void *meta, int32_t k_blocks,
-                              float *out, int32_t *n_selected, float *mass_est, int32_t *blocks_read,
+                              int32_t scorer, float *out, int32_t *n_selected, float *mass_est, int32_t *blocks_read,
                               float *lse_out, int32_t *order_out, float *scores_out, int32_t *traffic_out,
                               const psa_tuning *tuning, void *workspace, size_t workspace_bytes, void *stream);
 

@@ -152,14 +152,20 @@ void oracle_block_metadata(const oracle_shape *sh, const uint16_t *k_pool, const
 
 /* ---------- criticality scores (Algorithm 1, line 5) -------------------------------------- */
 /*
- * UB[g][b] = (1/sqrt d) * sum_c max(q[g][c]*kmin[b][c], q[g][c]*kmax[b][c]): no key inside the
- * cuboid [kmin, kmax] can give a larger scaled logit.  CS[b] = max over the heads g of the group
- * (reading: one ranking per KV head must serve all its query heads; max keeps the bound valid for
- * each of them).  ub: [batch][num_q_heads][max_blocks], cs: [batch][num_kv_heads][max_blocks];
+ * scorer 0 (the default reading of q . B_meta for cuboid metadata):
+ *   UB[g][b] = (1/sqrt d) * sum_c max(q[g][c]*kmin[b][c], q[g][c]*kmax[b][c]): no key inside the
+ *   cuboid [kmin, kmax] can give a larger scaled logit.
+ * scorer 1 (a reading of the "cuboid-mean" metadata that Sec. 3.1 names as the default without
+ *   defining it): the scaled logit of the cuboid's centre, q . (kmin + kmax)/2 / sqrt d, which is
+ *   also the mean of the largest and the smallest logit the cuboid allows.  Parity unpinned.
+ * CS[b] = max over the heads g of the group (reading: one ranking per KV head must serve all its
+ * query heads; for scorer 0 max keeps the bound valid for each of them).
+ * ub: [batch][num_q_heads][max_blocks] per-head scores, cs: [batch][num_kv_heads][max_blocks];
  * entries at b >= N_r are left untouched.
  */
 void oracle_block_scores(const oracle_shape *sh, const uint16_t *q, const uint16_t *meta,
-                         const int32_t *block_table, const int32_t *ctx_lens, double *ub, double *cs) {
+                         const int32_t *block_table, const int32_t *ctx_lens, int32_t scorer,
+                         double *ub, double *cs) {
     const int Hq = sh->num_q_heads, H = sh->num_kv_heads, D = sh->head_dim, G = Hq / H;
     const double inv_sqrt_d = 1.0 / sqrt((double)D);
     for (int r = 0; r < sh->batch; ++r) {
@@ -177,7 +183,7 @@ void oracle_block_scores(const oracle_shape *sh, const uint16_t *q, const uint16
                         double qc = decode(qg[c], sh->dtype);
                         double a = qc * decode(mn[c], sh->dtype);
                         double z = qc * decode(mx[c], sh->dtype);
-                        acc += a > z ? a : z;
+                        acc += scorer == 1 ? 0.5 * (a + z) : (a > z ? a : z);
                     }
                     acc *= inv_sqrt_d;
                     if (ub) ub[((size_t)r * Hq + h * G + g) * sh->max_blocks + b] = acc;

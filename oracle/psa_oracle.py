@@ -137,15 +137,19 @@ def block_metadata(pb: Problem, page_fill=None) -> np.ndarray:
     return meta
 
 
-def block_scores(pb: Problem, meta: np.ndarray):
-    """Returns (UB [B][Hq][max_blocks], CS [B][Hkv][max_blocks]); -inf beyond each request's N."""
+UPPER_BOUND, CUBOID_CENTER = 0, 1      # scorers (Algorithm 1, line 5; see psa_oracle.c)
+
+
+def block_scores(pb: Problem, meta: np.ndarray, scorer: int = UPPER_BOUND):
+    """Returns (per-head scores [B][Hq][max_blocks], CS [B][Hkv][max_blocks]); -inf beyond each
+    request's N."""
     B, Hq, H, D, T, P, MB = pb.dims
     ub = np.full((B, Hq, MB), -np.inf)
     cs = np.full((B, H, MB), -np.inf)
     sh = pb.shape
     _load().oracle_block_scores(C.byref(sh), _p(pb.q, C.c_uint16), _p(_u16(meta), C.c_uint16),
                                 _p(pb.block_table, C.c_int32), _p(pb.ctx_lens, C.c_int32),
-                                _p(ub, C.c_double), _p(cs, C.c_double))
+                                C.c_int32(scorer), _p(ub, C.c_double), _p(cs, C.c_double))
     return ub, cs
 
 
@@ -224,25 +228,26 @@ def psa_decode_ordered(pb: Problem, order: np.ndarray, eps: float, m: int = 1,
 
 
 def psa_decode(pb: Problem, eps: float, m: int = 1, curves: bool = False,
-               meta: np.ndarray | None = None) -> DecodeResult:
+               meta: np.ndarray | None = None, scorer: int = UPPER_BOUND) -> DecodeResult:
     """The whole path: metadata -> scores -> ranking -> progressive loop (Algorithm 1)."""
     if meta is None:
         meta = block_metadata(pb, pb.page_fill())
-    _, cs = block_scores(pb, meta)
+    _, cs = block_scores(pb, meta, scorer)
     order = block_order(pb, cs)
     res = psa_decode_ordered(pb, order, eps, m, curves)
     res.cs = cs
     return res
 
 
-def topk_attention(pb: Problem, k: int, meta: np.ndarray | None = None) -> DecodeResult:
+def topk_attention(pb: Problem, k: int, meta: np.ndarray | None = None,
+                   scorer: int = UPPER_BOUND) -> DecodeResult:
     """Fixed-budget control (Sec. 1 and 2.2: what dynamic sparse attention does before PSA -- attend
     exactly the k blocks with the best criticality scores): metadata -> scores -> ranking, then the
     definition of attention over the first min(k, N) ranked blocks.  mass_est is Algorithm 1's P_acc
     evaluated there (lines 15-16), read off the full curve of a run that never stops."""
     if meta is None:
         meta = block_metadata(pb, pb.page_fill())
-    _, cs = block_scores(pb, meta)
+    _, cs = block_scores(pb, meta, scorer)
     order = block_order(pb, cs)
     B, Hq, H, D, T, P, MB = pb.dims
     G = Hq // H

@@ -80,11 +80,11 @@ def load_library() -> C.CDLL:
         lib.psa_build_block_metadata.restype = C.c_int
         lib.psa_build_block_metadata.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, i32, vp]
         lib.psa_decode_attention.restype = C.c_int
-        lib.psa_decode_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, f32, i32, vp, vp, vp, vp, vp, vp,
-                                             vp, vp, C.POINTER(_Tuning), vp, sz, vp]
+        lib.psa_decode_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, f32, i32, i32, vp, vp, vp, vp, vp,
+                                             vp, vp, vp, C.POINTER(_Tuning), vp, sz, vp]
         lib.psa_topk_attention.restype = C.c_int
-        lib.psa_topk_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, i32, vp, vp, vp, vp, vp, vp, vp,
-                                           vp, C.POINTER(_Tuning), vp, sz, vp]
+        lib.psa_topk_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, i32, i32, vp, vp, vp, vp, vp, vp,
+                                           vp, vp, C.POINTER(_Tuning), vp, sz, vp]
         lib.psa_dense_attention.restype = C.c_int
         lib.psa_dense_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, vp, sz, vp]
         lib.psa_read_device_error.restype = C.c_int
@@ -165,6 +165,9 @@ def build_block_metadata(kv: KvCache, meta: torch.Tensor | None = None, page_fil
     return meta
 
 
+SCORE_UPPER_BOUND, SCORE_CUBOID_CENTER = 0, 1      # psa_scorer
+
+
 @dataclass
 class DecodeOutput:
     out: torch.Tensor          # float32 [B][Hq][128]
@@ -181,7 +184,7 @@ def decode_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, threshold
                      check_granularity: int = 1, *, workspace: torch.Tensor | None = None,
                      outputs: DecodeOutput | None = None, want_order: bool = False,
                      want_scores: bool = False, want_traffic: bool = False,
-                     tuning: Tuning | None = None, stream=None) -> DecodeOutput:
+                     tuning: Tuning | None = None, stream=None, scorer: int = SCORE_UPPER_BOUND) -> DecodeOutput:
     """psa_decode_attention.  Pass `workspace` and `outputs` to make the call allocation-free."""
     d = kv.desc()
     dev = q.device
@@ -202,7 +205,7 @@ def decode_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, threshold
     o = outputs
     assert q.is_contiguous() and meta.is_contiguous()
     st = load_library().psa_decode_attention(
-        C.byref(d), _ptr(q), _ptr(meta), float(threshold), int(check_granularity), _ptr(o.out),
+        C.byref(d), _ptr(q), _ptr(meta), float(threshold), int(check_granularity), int(scorer), _ptr(o.out),
         _ptr(o.n_selected), _ptr(o.mass_est), _ptr(o.blocks_read), _ptr(o.lse), _ptr(o.order),
         _ptr(o.scores), _ptr(o.traffic), C.byref(t) if t else None, _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "psa_decode_attention")
@@ -213,7 +216,7 @@ def decode_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, threshold
 def topk_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, k_blocks: int, *,
                    workspace: torch.Tensor | None = None, outputs: DecodeOutput | None = None,
                    want_order: bool = False, want_scores: bool = False, want_traffic: bool = False,
-                   tuning: Tuning | None = None, stream=None) -> DecodeOutput:
+                   tuning: Tuning | None = None, stream=None, scorer: int = SCORE_UPPER_BOUND) -> DecodeOutput:
     """psa_topk_attention: the fixed-budget control.  Same buffers as decode_attention."""
     d = kv.desc()
     dev = q.device
@@ -234,7 +237,7 @@ def topk_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, k_blocks: i
     o = outputs
     assert q.is_contiguous() and meta.is_contiguous()
     st = load_library().psa_topk_attention(
-        C.byref(d), _ptr(q), _ptr(meta), int(k_blocks), _ptr(o.out), _ptr(o.n_selected), _ptr(o.mass_est),
+        C.byref(d), _ptr(q), _ptr(meta), int(k_blocks), int(scorer), _ptr(o.out), _ptr(o.n_selected), _ptr(o.mass_est),
         _ptr(o.blocks_read), _ptr(o.lse), _ptr(o.order), _ptr(o.scores), _ptr(o.traffic), C.byref(t) if t else None,
         _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "psa_topk_attention")

@@ -67,7 +67,7 @@ psa_status psa_build_block_metadata(const psa_kv_desc *d, void *meta, const int3
 }
 
 static psa_status decode_common(const psa_kv_desc *d, const void *q, const void *meta, float threshold,
-                                int32_t check_granularity, int32_t budget_blocks, float *out, int32_t *n_selected,
+                                int32_t check_granularity, int32_t budget_blocks, int32_t scorer, float *out, int32_t *n_selected,
                                 float *mass_est, int32_t *blocks_read, float *lse_out, int32_t *order_out,
                                 float *scores_out, int32_t *traffic_out, const psa_tuning *tuning,
                                 void *workspace, size_t workspace_bytes, void *stream) {
@@ -75,6 +75,7 @@ static psa_status decode_common(const psa_kv_desc *d, const void *q, const void 
     if (st != PSA_OK) return st;
     if (!(threshold >= 0.0f && threshold <= 1.0f)) return PSA_ERR_INVALID_ARG;   // also rejects NaN
     if (check_granularity < 1) return PSA_ERR_INVALID_ARG;
+    if (scorer != PSA_SCORE_UPPER_BOUND && scorer != PSA_SCORE_CUBOID_CENTER) return PSA_ERR_INVALID_ARG;
     if (d->max_blocks_per_seq > psa::kMaxBlocks) return PSA_ERR_UNSUPPORTED;
     if (tuning) {
         const int cb = tuning->chunk_blocks;
@@ -92,28 +93,28 @@ static psa_status decode_common(const psa_kv_desc *d, const void *q, const void 
     a.q = q; a.meta = meta; a.threshold = threshold; a.check_granularity = check_granularity;
     a.out = out; a.n_selected = n_selected; a.mass_est = mass_est; a.blocks_read = blocks_read; a.lse_out = lse_out;
     a.order_out = order_out; a.scores_out = scores_out; a.traffic_out = traffic_out;
-    a.budget_blocks = budget_blocks;
+    a.budget_blocks = budget_blocks; a.scorer = scorer;
     hipError_t e = psa::launch_decode(d, a, plan, workspace, (hipStream_t)stream);
     return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
 }
 
 psa_status psa_decode_attention(const psa_kv_desc *d, const void *q, const void *meta, float threshold,
-                                int32_t check_granularity, float *out, int32_t *n_selected,
+                                int32_t check_granularity, int32_t scorer, float *out, int32_t *n_selected,
                                 float *mass_est, int32_t *blocks_read, float *lse_out, int32_t *order_out,
                                 float *scores_out, int32_t *traffic_out, const psa_tuning *tuning,
                                 void *workspace, size_t workspace_bytes, void *stream) {
-    return decode_common(d, q, meta, threshold, check_granularity, 0, out, n_selected, mass_est, blocks_read,
+    return decode_common(d, q, meta, threshold, check_granularity, 0, scorer, out, n_selected, mass_est, blocks_read,
                          lse_out, order_out, scores_out, traffic_out, tuning, workspace, workspace_bytes, stream);
 }
 
 // A fixed budget of k blocks is Algorithm 1 with threshold 0 tested once every k blocks: P_acc > 0
 // holds at the first test, so every head stops at min(k, N); the key read-ahead ends there too.
 psa_status psa_topk_attention(const psa_kv_desc *d, const void *q, const void *meta, int32_t k_blocks,
-                              float *out, int32_t *n_selected, float *mass_est, int32_t *blocks_read,
+                              int32_t scorer, float *out, int32_t *n_selected, float *mass_est, int32_t *blocks_read,
                               float *lse_out, int32_t *order_out, float *scores_out, int32_t *traffic_out,
                               const psa_tuning *tuning, void *workspace, size_t workspace_bytes, void *stream) {
     if (k_blocks < 1) return PSA_ERR_INVALID_ARG;
-    return decode_common(d, q, meta, 0.0f, k_blocks, k_blocks, out, n_selected, mass_est, blocks_read,
+    return decode_common(d, q, meta, 0.0f, k_blocks, k_blocks, scorer, out, n_selected, mass_est, blocks_read,
                          lse_out, order_out, scores_out, traffic_out, tuning, workspace, workspace_bytes, stream);
 }
 

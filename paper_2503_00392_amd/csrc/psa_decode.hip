@@ -103,7 +103,7 @@ hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const Decode
     hipEvent_t *ev = plan.events;
     hipError_t e;
     if (ev) (void)hipEventRecord(ev[0], st);
-    if ((e = launch_score(kv, d->dtype, G, a.q, a.meta, ws, a.scores_out, st)) != hipSuccess) return e;
+    if ((e = launch_score(kv, d->dtype, G, a.scorer, a.q, a.meta, ws, a.scores_out, st)) != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);
     if ((e = launch_order(kv, ws, G, plan.chunk_blocks, a.budget_blocks, plan.force_bitonic, a.order_out, st)) != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[2], st);

@@ -52,6 +52,7 @@ struct DecodeArgs {
     const void *q, *meta;
     float threshold;
     int check_granularity;
+    int scorer;           // psa_scorer
     int budget_blocks;    // > 0: keys are handed out no further than this many ranked blocks
     float *out;
     int32_t *n_selected;
@@ -65,7 +66,7 @@ hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const Decode
                          hipStream_t st);
 
 // psa_score.hip, psa_order.hip, psa_select.hip, psa_values.hip: the kernels of one decode call
-hipError_t launch_score(const KvView &kv, int dtype, int G, const void *q, const void *meta,
+hipError_t launch_score(const KvView &kv, int dtype, int G, int scorer, const void *q, const void *meta,
                         const DecodeWs &ws, float *scores_out, hipStream_t st);
 hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int KU, int budget_blocks, int force_bitonic,
                         int32_t *order_out, hipStream_t st);

@@ -5,12 +5,15 @@
 namespace psa {
 
 // =================================================================================================
-// Scoring.  UB[g][b] = (1/sqrt d) sum_c max(q_c kmin_c, q_c kmax_c) = (1/sqrt d) (q+ . kmax + q- . kmin)
-// with q+ = max(q,0), q- = min(q,0); CS[b] = max_g UB[g][b].
+// Scoring.  Upper bound (CENTER = 0):
+//   UB[g][b] = (1/sqrt d) sum_c max(q_c kmin_c, q_c kmax_c) = (1/sqrt d) (q+ . kmax + q- . kmin)
+//   with q+ = max(q,0), q- = min(q,0).
+// Cuboid centre (CENTER = 1): (1/sqrt d) q . (kmin + kmax)/2 = (1/(2 sqrt d)) (q . kmax + q . kmin).
+// Either way CS[b] = max over the heads g of the group.
 // grid (ceil(max_blocks/64), S), 256 threads.  A 16-lane row handles one block: lanes 0-7 take
-// 32 bytes each of the min row against q-, lanes 8-15 of the max row against q+.
+// 32 bytes each of the min row (against q-, or q), lanes 8-15 of the max row (against q+, or q).
 // =================================================================================================
-template <int DT, int G>
+template <int DT, int G, int CENTER>
 __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__restrict__ q,
                                                     const uint8_t *__restrict__ meta,
                                                     float *__restrict__ scores,
@@ -36,7 +39,7 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const uint32_t neg = ((w[j] >> 15) & 0x00010001u) * 0xFFFFu;
-            qs[g][j] = w[j] & (is_max ? ~neg : neg);
+            qs[g][j] = CENTER ? w[j] : (w[j] & (is_max ? ~neg : neg));
         }
     }
 
@@ -66,7 +69,7 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
 #pragma unroll
             for (int j = 0; j < 8; ++j) p = dot2<DT>(w[j], qs[g][j], p);
             p = row_sum16(p);
-            cs = fmaxf(cs, p * kScale);
+            cs = fmaxf(cs, p * (CENTER ? 0.5f * kScale : kScale));
         }
         if (cl == 0 && b < N) {
             scores[(size_t)s * kv.max_blocks + b] = cs;
@@ -76,18 +79,23 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
 }
 
 template <int DT, int G>
-static hipError_t launch_score_t(const KvView &kv, const void *q, const void *meta, const DecodeWs &ws,
+static hipError_t launch_score_t(const KvView &kv, int scorer, const void *q, const void *meta, const DecodeWs &ws,
                                  float *scores_out, hipStream_t st) {
     const int S = kv.batch * kv.num_kv_heads;
-    score_kernel<DT, G><<<dim3((kv.max_blocks + 63) / 64, S), 256, 0, st>>>(
-        kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores, scores_out, ws.header);
+    const dim3 grid((kv.max_blocks + 63) / 64, S);
+    if (scorer == 1)
+        score_kernel<DT, G, 1><<<grid, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
+                                                     scores_out, ws.header);
+    else
+        score_kernel<DT, G, 0><<<grid, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
+                                                     scores_out, ws.header);
     return hipGetLastError();
 }
 
-hipError_t launch_score(const KvView &kv, int dtype, int G, const void *q, const void *meta,
+hipError_t launch_score(const KvView &kv, int dtype, int G, int scorer, const void *q, const void *meta,
                         const DecodeWs &ws, float *scores_out, hipStream_t st) {
 #define PSA_CASE(DT, GG) \
-    if (dtype == DT && G == GG) return launch_score_t<DT, GG>(kv, q, meta, ws, scores_out, st);
+    if (dtype == DT && G == GG) return launch_score_t<DT, GG>(kv, scorer, q, meta, ws, scores_out, st);
     PSA_CASE(0, 1) PSA_CASE(0, 2) PSA_CASE(0, 4) PSA_CASE(0, 8)
     PSA_CASE(1, 1) PSA_CASE(1, 2) PSA_CASE(1, 4) PSA_CASE(1, 8)
 #undef PSA_CASE

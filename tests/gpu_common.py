@@ -51,7 +51,8 @@ class ParityReport:
                 f"worst_score_err={self.worst_score:.2e} worst_mass_err={self.worst_mass:.2e}")
 
 
-def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, requests=None) -> ParityReport:
+def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, requests=None,
+                                scorer: int = 0) -> ParityReport:
     """gpu: DecodeOutput with order and scores.  `requests`: subset of request indices the oracle
     computes (all by default)."""
     B, Hq, H, D, T, P, MB = pb.dims
@@ -70,7 +71,7 @@ def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, request
     g_order = gpu.order.cpu().numpy()[requests]
     g_scores = gpu.scores.cpu().numpy().astype(np.float64)[requests]
 
-    ora = po.psa_decode(sub, eps, m)
+    ora = po.psa_decode(sub, eps, m, scorer=scorer)
     nb = sub.num_blocks()
     rep = ParityReport()
 
@@ -118,7 +119,7 @@ def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, request
             assert g_mass[i, hq] > eps or n_g == N, "estimate must exceed eps unless all blocks were used"
             if n_g != n_o:
                 if curves is None:
-                    curves = po.psa_decode(sub, eps, m, curves=True)
+                    curves = po.psa_decode(sub, eps, m, curves=True, scorer=scorer)
                 p_at = curves.p_acc[i, hq, min(n_g, n_o) - 1]
                 assert abs(p_at - eps) <= PACC_ATOL, \
                     f"stop index {n_g} vs oracle {n_o} with P_acc {p_at} not at the boundary {eps}"
@@ -144,13 +145,13 @@ def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, request
     return rep
 
 
-def run_gpu_decode(li: LayerInputs, eps: float, m: int = 1, tuning=None, meta=None):
+def run_gpu_decode(li: LayerInputs, eps: float, m: int = 1, tuning=None, meta=None, scorer: int = 0):
     import paper_2503_00392_amd as psa
     kv = to_kv(li)
     if meta is None:
         meta = psa.build_block_metadata(kv, page_fill=li.page_fill)
     out = psa.decode_attention(kv, li.q, meta, eps, m, want_order=True, want_scores=True,
-                               want_traffic=True, tuning=tuning)
+                               want_traffic=True, tuning=tuning, scorer=scorer)
     torch.cuda.synchronize()
     flags = psa.read_device_error(out._workspace)
     assert flags == 0, f"device error flags {flags}"

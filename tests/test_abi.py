@@ -62,9 +62,9 @@ def _desc(**kw):
 
 
 def _decode(lib, d, threshold=0.9, m=1, q=0x10, meta=0x20, out=0x30, nsel=0x40, mass=0x50, ws=0x60,
-            ws_bytes=1 << 40, tuning=None):
-    return lib.psa_decode_attention(C.byref(d), q, meta, threshold, m, out, nsel, mass, None, None, None,
-                                    None, None, C.byref(tuning) if tuning else None, ws, ws_bytes, None)
+            ws_bytes=1 << 40, tuning=None, scorer=0):
+    return lib.psa_decode_attention(C.byref(d), q, meta, threshold, m, scorer, out, nsel, mass, None, None,
+                                    None, None, None, C.byref(tuning) if tuning else None, ws, ws_bytes, None)
 
 
 def test_workspace_sizes(lib):
@@ -98,6 +98,7 @@ def test_decode_rejects_bad_scalars_and_null_buffers(lib):
     assert _decode(lib, d, threshold=-0.01) == 1
     assert _decode(lib, d, threshold=1.01) == 1
     assert _decode(lib, d, m=0) == 1
+    assert _decode(lib, d, scorer=2) == 1 and _decode(lib, d, scorer=-1) == 1
     for name in ("q", "meta", "out", "nsel", "mass", "ws"):
         assert _decode(lib, d, **{name: None}) == 1, name
     assert _decode(lib, d, ws_bytes=1024) == 3
@@ -108,11 +109,11 @@ def test_decode_rejects_bad_scalars_and_null_buffers(lib):
     assert _decode(lib, d, tuning=T(0, -1, 0, 0, 0, None)) == 1
     assert _decode(lib, d, tuning=T(0, 0, 0, 2, 0, None)) == 1
     assert _decode(lib, d, tuning=T(0, 0, 0, 0, -3, None)) == 1
-    assert lib.psa_decode_attention(None, 1, 1, 0.5, 1, 1, 1, 1, None, None, None, None, None, None, 1,
+    assert lib.psa_decode_attention(None, 1, 1, 0.5, 1, 0, 1, 1, 1, None, None, None, None, None, None, 1,
                                     1 << 30, None) == 1
-    assert lib.psa_topk_attention(C.byref(d), 0x10, 0x20, 0, 0x30, 0x40, 0x50, None, None, None, None, None,
+    assert lib.psa_topk_attention(C.byref(d), 0x10, 0x20, 0, 0, 0x30, 0x40, 0x50, None, None, None, None, None,
                                   None, 0x60, 1 << 40, None) == 1          # budget below one block
-    assert lib.psa_topk_attention(C.byref(d), 0x10, 0x20, 4, 0x30, 0x40, 0x50, None, None, None, None, None,
+    assert lib.psa_topk_attention(C.byref(d), 0x10, 0x20, 4, 0, 0x30, 0x40, 0x50, None, None, None, None, None,
                                   None, 0x60, 64, None) == 3
 
 

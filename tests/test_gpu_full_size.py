@@ -135,3 +135,13 @@ def test_topk_full_size_config3(psa):
         assert gc.rel_l2(gpu.out.cpu().numpy().astype(np.float64), own).max() <= gc.OUT_RTOL
         tr = gpu.traffic.cpu().numpy()
         assert np.all(tr[..., 0] == -(-k // 32) * 32) and np.all(tr[..., 1] == k)
+
+
+def test_center_scorer_full_size_config3(psa):
+    cfg = get_config(3)
+    li = generate_layer(cfg, layer=23, device="cuda")
+    gpu = gc.run_gpu_decode(li, cfg.threshold, 1, scorer=psa.SCORE_CUBOID_CENTER)
+    _properties(psa, cfg, li, gpu, cfg.threshold, 1)
+    rep = gc.check_decode_against_oracle(gc.to_problem(li), gpu, cfg.threshold, 1, requests=[1, 2], scorer=po.CUBOID_CENTER)
+    print(f"\n[config 3 layer 23 centre scorer] {rep}")
+    assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads

@@ -198,3 +198,23 @@ def test_topk_matches_oracle(psa, case, k):
     lim = np.minimum(N, -(-np.minimum(k, N) // chunk) * chunk)
     assert np.array_equal(tr[..., 0], np.repeat(lim[:, None], cfg.num_kv_heads, 1))       # keys: budget, whole chunks
     assert np.array_equal(tr[..., 1], np.repeat(np.minimum(k, N)[:, None], cfg.num_kv_heads, 1))
+
+
+def test_cuboid_center_scorer_matches_oracle(psa, case):
+    """The second scorer: same metadata, the centre of the bounding cuboid instead of its best corner."""
+    name, cfg, li, pb = case
+    for m in (1, 4):
+        gpu = gc.run_gpu_decode(li, cfg.threshold, m, scorer=psa.SCORE_CUBOID_CENTER)
+        rep = gc.check_decode_against_oracle(pb, gpu, cfg.threshold, m, scorer=po.CUBOID_CENTER)
+        print(f"\n[{name} centre scorer m={m}] {rep}")
+        assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads - \
+            int((pb.num_blocks() == 0).sum()) * pb.q.shape[1]
+        assert rep.stop_flips <= max(1, rep.heads // 50)
+    k = 9
+    kv = gc.to_kv(li)
+    meta = psa.build_block_metadata(kv, page_fill=li.page_fill)
+    top = psa.topk_attention(kv, li.q, meta, k, want_order=True, scorer=psa.SCORE_CUBOID_CENTER)
+    torch.cuda.synchronize()
+    assert torch.equal(top.order, gpu.order)
+    own = po.attend_prefix(pb, top.order.cpu().numpy(), top.n_selected.cpu().numpy())
+    assert gc.rel_l2(top.out.cpu().numpy().astype(np.float64), own).max() <= gc.OUT_RTOL

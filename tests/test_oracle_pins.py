@@ -170,6 +170,51 @@ def test_order_is_descending_permutation_with_ties_to_smaller_index():
             assert np.array_equal(o, np.argsort(-keys[r, h, :n], kind="stable"))
 
 
+@pytest.mark.parametrize("dtype", [po.F16, po.BF16])
+def test_center_score_is_the_mean_of_the_extreme_logits_of_the_cuboid(dtype):
+    """Cuboid-centre scorer: q.(kmin+kmax)/2/sqrt(d).  Brute force over the cuboid's corners gives the
+    largest and the smallest logit it allows (LP over a box); the centre's logit is their mean, it lies
+    between the block's smallest and largest possible logit, and it is the exact logit when the block
+    holds one token.  The group reduce stays a max."""
+    rng = np.random.default_rng(23)
+    pb = ref.random_problem(rng, B=2, Hq=6, Hkv=2, d=16, T=4, ctx=(13, 29), dtype=dtype)
+    meta = po.block_metadata(pb, pb.page_fill())
+    ce, cs = po.block_scores(pb, meta, po.CUBOID_CENTER)
+    ub, _ = po.block_scores(pb, meta, po.UPPER_BOUND)
+    G, T = 3, 4
+    for r in range(2):
+        n = int(pb.num_blocks()[r])
+        for hq in range(6):
+            q = po.decode(pb.q[r, hq], pb.dtype)
+            s = ref.logits(pb, r, hq)
+            for b in range(n):
+                page = pb.block_table[r, b]
+                lo, hi = po.decode(meta[page, hq // G, 0], pb.dtype), po.decode(meta[page, hq // G, 1], pb.dtype)
+                top = q @ np.where(q > 0, hi, lo) / math.sqrt(16)
+                bottom = q @ np.where(q > 0, lo, hi) / math.sqrt(16)
+                assert abs(top - ub[r, hq, b]) < 1e-12
+                assert abs(ce[r, hq, b] - 0.5 * (top + bottom)) < 1e-12
+                assert abs(ce[r, hq, b] - q @ (0.5 * (lo + hi)) / math.sqrt(16)) < 1e-12
+                blk = s[b * T:(b + 1) * T]
+                assert bottom - 1e-12 <= blk.min() and blk.max() <= top + 1e-12
+                if len(blk) == 1:
+                    assert abs(ce[r, hq, b] - blk[0]) < 1e-12
+        for h in range(2):
+            np.testing.assert_array_equal(cs[r, h, :n], ce[r, h * G:(h + 1) * G, :n].max(0))
+
+
+def test_scorer_changes_the_ranking_not_the_rule():
+    """With either scorer the progressive loop is the same function of the ranking it is given."""
+    pb = _problem(51)
+    for scorer in (po.UPPER_BOUND, po.CUBOID_CENTER):
+        res = po.psa_decode(pb, 0.9, 2, scorer=scorer)
+        meta = po.block_metadata(pb, pb.page_fill())
+        _, cs = po.block_scores(pb, meta, scorer)
+        again = po.psa_decode_ordered(pb, po.block_order(pb, cs), 0.9, 2)
+        assert np.array_equal(res.n_selected, again.n_selected) and np.array_equal(res.out, again.out)
+        np.testing.assert_allclose(po.attend_prefix(pb, res.order, res.n_selected), res.out, rtol=1e-11, atol=1e-12)
+
+
 # ---------------------------------------------------------------- progressive loop, Alg. 1 lines 7-19
 def _problem(seed, dtype=po.F16, **kw):
     rng = np.random.default_rng(seed)
