@@ -117,6 +117,25 @@ psa_status psa_build_block_metadata(const psa_kv_desc *desc, void *meta, const i
                                     const int32_t *page_list, int32_t num_listed, void *stream);
 
 /*
+ * Incremental decode: appends one token per request to the paged cache and keeps the block metadata
+ * current (Sec. 3.1: metadata is created on the GPU as a block fills).  For request r with length
+ * c = ctx_lens[r] the token goes to slot c % 16 of page block_table[r][c / 16]; that page's metadata
+ * becomes the min/max over its c % 16 + 1 valid tokens (bit for bit what psa_build_block_metadata
+ * gives on the new cache); ctx_lens[r] becomes c + 1.
+ *   desc     the call WRITES desc->k_pool, desc->v_pool and desc->ctx_lens (declared const in the
+ *            struct because every other call only reads them); the block table must already hold a
+ *            page for position c
+ *   k_new    [batch][num_kv_heads][head_dim], desc->dtype: the new token's keys; v_new likewise
+ *   meta     [num_pages][num_kv_heads][2][head_dim], updated in place
+ *   status   [batch] int32 or NULL: 0 = appended; PSA_DEVERR_CTX_RANGE = the request's row of the
+ *            block table is full (or its length is negative); PSA_DEVERR_PAGE_RANGE = the table entry
+ *            is outside the pool.  In both cases nothing of that request is touched.
+ * Not to be overlapped with another call that uses the same cache.
+ */
+psa_status psa_append_kv(const psa_kv_desc *desc, const void *k_new, const void *v_new, void *meta,
+                         int32_t *status, void *stream);
+
+/*
  * One decode step of Progressive Sparse Attention for one layer (Algorithm 1; Sec. 3.2 for the
  * microbatch size and for the batched form in which every query stops on its own).
  * Per (request, KV head): score every block from its metadata (line 5: the largest scaled logit

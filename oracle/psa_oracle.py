@@ -261,3 +261,29 @@ def topk_attention(pb: Problem, k: int, meta: np.ndarray | None = None,
             mass[r] = curves.p_acc[r, :, n_take[r, 0] - 1]
     bread = n_take.reshape(B, H, G).max(-1).astype(np.int32)
     return DecodeResult(out, n_take, mass, bread, order, cs)
+
+
+def append_kv(pb: Problem, k_new: np.ndarray, v_new: np.ndarray):
+    """Incremental decode (Sec. 3.1: each step adds the new token's K/V to the cache; block metadata
+    lives with the block): the cache after one more token per request.  k_new, v_new: uint16 bit
+    patterns [B][Hkv][d].  Returns (the new Problem, status [B]) where status is 0, or 2 when the
+    request's table row is full or its length is negative, or 1 when the table entry is outside the
+    pool -- such a request is left as it was.  Metadata of the new cache is obtained the plain way,
+    block_metadata(new, new.page_fill()): nothing incremental here."""
+    B, Hq, H, D, T, P, MB = pb.dims
+    k_pool, v_pool = pb.k_pool.copy(), pb.v_pool.copy()
+    ctx = pb.ctx_lens.copy()
+    status = np.zeros(B, dtype=np.int32)
+    for r in range(B):
+        c = int(ctx[r])
+        if c < 0 or c >= MB * T:
+            status[r] = 2
+            continue
+        page = int(pb.block_table[r, c // T])
+        if page < 0 or page >= P:
+            status[r] = 1
+            continue
+        k_pool[page, :, c % T, :] = k_new[r]
+        v_pool[page, :, c % T, :] = v_new[r]
+        ctx[r] = c + 1
+    return Problem(pb.q, k_pool, v_pool, pb.block_table, ctx, pb.dtype), status

@@ -82,6 +82,8 @@ def load_library() -> C.CDLL:
         lib.psa_decode_attention.restype = C.c_int
         lib.psa_decode_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, f32, i32, i32, vp, vp, vp, vp, vp,
                                              vp, vp, vp, C.POINTER(_Tuning), vp, sz, vp]
+        lib.psa_append_kv.restype = C.c_int
+        lib.psa_append_kv.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, vp, vp]
         lib.psa_topk_attention.restype = C.c_int
         lib.psa_topk_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, i32, i32, vp, vp, vp, vp, vp, vp,
                                            vp, vp, C.POINTER(_Tuning), vp, sz, vp]
@@ -163,6 +165,18 @@ def build_block_metadata(kv: KvCache, meta: torch.Tensor | None = None, page_fil
                                                  n_listed, _stream(stream))
     _check(st, "psa_build_block_metadata")
     return meta
+
+
+def append_kv(kv: KvCache, k_new: torch.Tensor, v_new: torch.Tensor, meta: torch.Tensor,
+              status: torch.Tensor | None = None, stream=None) -> None:
+    """psa_append_kv: writes into kv.k_pool, kv.v_pool, kv.ctx_lens and meta in place."""
+    assert k_new.is_contiguous() and v_new.is_contiguous() and meta.is_contiguous()
+    assert k_new.dtype == kv.k_pool.dtype and v_new.dtype == kv.k_pool.dtype
+    d = kv.desc()
+    assert tuple(k_new.shape) == (d.batch, d.num_kv_heads, 128) and tuple(v_new.shape) == tuple(k_new.shape)
+    st = load_library().psa_append_kv(C.byref(d), _ptr(k_new), _ptr(v_new), _ptr(meta), _ptr(status),
+                                      _stream(stream))
+    _check(st, "psa_append_kv")
 
 
 SCORE_UPPER_BOUND, SCORE_CUBOID_CENTER = 0, 1      # psa_scorer

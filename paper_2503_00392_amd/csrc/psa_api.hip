@@ -66,6 +66,16 @@ psa_status psa_build_block_metadata(const psa_kv_desc *d, void *meta, const int3
     return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
 }
 
+psa_status psa_append_kv(const psa_kv_desc *d, const void *k_new, const void *v_new, void *meta,
+                         int32_t *status, void *stream) {
+    psa_status st = check_desc(d, true, true);
+    if (st != PSA_OK) return st;
+    if (d->batch == 0) return PSA_OK;
+    if (!k_new || !v_new || !meta) return PSA_ERR_INVALID_ARG;
+    hipError_t e = psa::launch_append(d, k_new, v_new, meta, status, (hipStream_t)stream);
+    return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
+}
+
 static psa_status decode_common(const psa_kv_desc *d, const void *q, const void *meta, float threshold,
                                 int32_t check_granularity, int32_t budget_blocks, int32_t scorer, float *out, int32_t *n_selected,
                                 float *mass_est, int32_t *blocks_read, float *lse_out, int32_t *order_out,

@@ -206,4 +206,25 @@ __device__ __forceinline__ int clamp_page_quiet(int page, int num_pages) {
     return (unsigned)page >= (unsigned)num_pages ? 0 : page;
 }
 
+// ---- packed 16-bit min/max on order-preserving keys (block metadata) --------------------------
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+
+// Two packed 16-bit floats -> keys whose unsigned order is the numeric order.
+__device__ __forceinline__ uint32_t to_ordered(uint32_t w) {
+    const uint32_t neg = ((w >> 15) & 0x00010001u) * 0xFFFFu;   // 0xFFFF in each negative half
+    return w ^ (neg | 0x80008000u);
+}
+__device__ __forceinline__ uint32_t from_ordered(uint32_t k) {
+    const uint32_t was_neg = (((~k) >> 15) & 0x00010001u) * 0xFFFFu;
+    return k ^ (was_neg | 0x80008000u);
+}
+__device__ __forceinline__ uint32_t pk_min(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(ushort2_t, a),
+                                                                  __builtin_bit_cast(ushort2_t, b)));
+}
+__device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, a),
+                                                                  __builtin_bit_cast(ushort2_t, b)));
+}
+
 }  // namespace psa

@@ -7,7 +7,7 @@ import torch
 
 import gpu_common as gc
 from oracle import psa_oracle as po
-from workloads import generate_layer, get_config
+from workloads import add_headroom, as_bits, generate_layer, get_config, step_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -218,3 +218,68 @@ def test_cuboid_center_scorer_matches_oracle(psa, case):
     assert torch.equal(top.order, gpu.order)
     own = po.attend_prefix(pb, top.order.cpu().numpy(), top.n_selected.cpu().numpy())
     assert gc.rel_l2(top.out.cpu().numpy().astype(np.float64), own).max() <= gc.OUT_RTOL
+
+
+@pytest.mark.parametrize("which", ["c1_ragged", "c3_small_bf16"])
+def test_incremental_decode_loop(psa, which):
+    """Several decode steps in a row: append the step's token (K, V, metadata, length -- all on the GPU),
+    then PSA with the step's query.  After every step the cache and the metadata equal, bit for bit,
+    what the oracle gets by appending to its own copy and rebuilding the metadata from scratch, and the
+    decode result matches the oracle's on that cache.  Lengths are chosen so that pages fill, new
+    pages start and a request starts from nothing."""
+    if which == "c1_ragged":
+        cfg = _small(1, batch=4, ctx=700)             # every request generated at 700 tokens, then cut back
+        start = [16 * 9 - 2, 16 * 20, 333, 0]
+    else:
+        cfg = _small(3, batch=2, ctx=4096, layers=1)
+        start = [4096 - 3, 2000]
+    steps = 6
+    li = add_headroom(generate_layer(cfg, device="cuda", poison_tail=True), steps)
+    li.ctx_lens.copy_(torch.tensor(start, dtype=torch.int32))
+    kv = gc.to_kv(li)
+    fill0 = torch.from_numpy(gc.to_problem(li).page_fill()).cuda()
+    meta = psa.build_block_metadata(kv, page_fill=fill0)
+    pb = gc.to_problem(li)
+    status = torch.full((cfg.batch,), -1, dtype=torch.int32, device="cuda")
+    for t in range(1, steps + 1):
+        q, k_new, v_new = step_inputs(li, t)
+        psa.append_kv(kv, k_new, v_new, meta, status)
+        torch.cuda.synchronize()
+        pb, want_status = po.append_kv(po.Problem(as_bits(q), pb.k_pool, pb.v_pool, pb.block_table, pb.ctx_lens, pb.dtype),
+                                       as_bits(k_new), as_bits(v_new))
+        assert np.array_equal(status.cpu().numpy(), want_status) and not want_status.any()
+        assert np.array_equal(li.ctx_lens.cpu().numpy(), pb.ctx_lens)
+        fill = pb.page_fill()
+        want_meta = po.block_metadata(pb, fill)
+        got_meta = as_bits(meta)
+        used = fill > 0
+        assert np.array_equal(got_meta[used], want_meta[used]), f"metadata differs after step {t}"
+        # valid tokens of the pools are identical (rows beyond a page's fill may hold the poison)
+        gk, gv = as_bits(li.k_pool), as_bits(li.v_pool)
+        for page in np.nonzero(used)[0]:
+            assert np.array_equal(gk[page, :, :fill[page]], pb.k_pool[page, :, :fill[page]])
+            assert np.array_equal(gv[page, :, :fill[page]], pb.v_pool[page, :, :fill[page]])
+        out = psa.decode_attention(kv, q, meta, cfg.threshold, 1, want_order=True, want_scores=True, want_traffic=True)
+        torch.cuda.synchronize()
+        assert psa.read_device_error(out._workspace) == 0
+        rep = gc.check_decode_against_oracle(pb, out, cfg.threshold, 1)
+        assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads
+    assert np.array_equal(pb.ctx_lens, np.array(start) + steps)
+
+
+def test_append_reports_a_full_table_row_and_leaves_the_request_alone(psa):
+    cfg = _small(1, batch=2, ctx=64)
+    li = generate_layer(cfg, device="cuda")          # rows of exactly 4 blocks, both requests full
+    li.ctx_lens.copy_(torch.tensor([64, 63], dtype=torch.int32))
+    kv = gc.to_kv(li)
+    meta = psa.build_block_metadata(kv, page_fill=li.page_fill)
+    before_k, before_meta = li.k_pool.clone(), meta.clone()
+    q, k_new, v_new = step_inputs(li, 1)
+    status = torch.zeros(2, dtype=torch.int32, device="cuda")
+    psa.append_kv(kv, k_new, v_new, meta, status)
+    torch.cuda.synchronize()
+    assert status.tolist() == [2, 0] and li.ctx_lens.tolist() == [64, 64]
+    page0 = li.block_table[0].long()
+    assert torch.equal(li.k_pool[page0], before_k[page0]) and torch.equal(meta[page0].view(torch.int16), before_meta[page0].view(torch.int16))
+    last = int(li.block_table[1, 3])
+    assert torch.equal(li.k_pool[last, :, 15].view(torch.int16), k_new[1].view(torch.int16))

@@ -469,3 +469,47 @@ def test_prefix_lse_is_logsumexp_of_the_attended_logits_and_true_mass_follows():
     full = np.repeat(nb[:, None], 4, 1).astype(np.int32)
     _, lse_all = po.attend_prefix(pb, res.order, full, want_lse=True)
     np.testing.assert_allclose(lse_all, dense_lse, rtol=0, atol=1e-10)
+
+
+# ---------------------------------------------------------------- incremental decode (Sec. 3.1)
+def test_append_puts_the_token_at_the_end_of_the_request_and_metadata_follows():
+    """After an append, the request's key/value sequence is the old one plus the new token; the
+    metadata of the new cache (built the plain way) is numpy's min/max over each block's valid tokens;
+    attention over the new cache therefore sees exactly one more token."""
+    rng = np.random.default_rng(60)
+    full = ref.random_problem(rng, B=3, Hq=4, Hkv=2, d=16, T=4, ctx=(12, 12, 4))     # pages for three blocks each
+    pb = po.Problem(full.q, full.k_pool, full.v_pool, full.block_table, np.array([7, 8, 0], dtype=np.int32), full.dtype)
+    k_new = rng.integers(0, 0x3c00, size=(3, 2, 16), dtype=np.uint16)       # positive finite halves
+    v_new = rng.integers(0, 0x3c00, size=(3, 2, 16), dtype=np.uint16)
+    new, status = po.append_kv(pb, k_new, v_new)
+    assert np.array_equal(status, [0, 0, 0]) and np.array_equal(new.ctx_lens, [8, 9, 1])
+    for r in range(3):
+        for h in range(2):
+            k1, v1 = ref.stream_kv(new, r, h)
+            assert len(k1) == pb.ctx_lens[r] + 1
+            if pb.ctx_lens[r] > 0:
+                k0, v0 = ref.stream_kv(pb, r, h)
+                assert np.array_equal(k1[:-1], k0) and np.array_equal(v1[:-1], v0)
+            assert np.array_equal(k1[-1], po.decode(k_new[r, h], pb.dtype))
+            assert np.array_equal(v1[-1], po.decode(v_new[r, h], pb.dtype))
+    meta = po.block_metadata(new, new.page_fill())
+    T = 4
+    for r in range(3):
+        for b in range(int(new.num_blocks()[r])):
+            page = new.block_table[r, b]
+            valid = min(T, int(new.ctx_lens[r]) - b * T)
+            kk = po.decode(new.k_pool[page, :, :valid, :], new.dtype)
+            assert np.array_equal(po.decode(meta[page, :, 0], new.dtype), kk.min(1))
+            assert np.array_equal(po.decode(meta[page, :, 1], new.dtype), kk.max(1))
+    # untouched: the old problem object
+    assert np.array_equal(pb.ctx_lens, [7, 8, 0])
+
+
+def test_append_refuses_a_full_row_and_a_page_outside_the_pool():
+    rng = np.random.default_rng(61)
+    pb = ref.random_problem(rng, B=2, Hq=2, Hkv=1, d=16, T=4, ctx=(8, 3))           # rows of two blocks
+    pb.block_table[1, 0] = 999
+    tok = np.zeros((2, 1, 16), dtype=np.uint16)
+    new, status = po.append_kv(pb, tok, tok)
+    assert np.array_equal(status, [2, 1]) and np.array_equal(new.ctx_lens, [8, 3])
+    assert np.array_equal(new.k_pool, pb.k_pool)

@@ -1,6 +1,6 @@
 """Seeded synthetic inputs for the PSA decode path (no arithmetic of the method lives here)."""
-from .generator import (CONFIGS, LayerInputs, WorkloadConfig, as_bits, base_seed, generate_layer,
-                        get_config)
+from .generator import (CONFIGS, LayerInputs, WorkloadConfig, add_headroom, as_bits, base_seed,
+                        generate_layer, get_config, step_inputs)
 
-__all__ = ["CONFIGS", "LayerInputs", "WorkloadConfig", "as_bits", "base_seed", "generate_layer",
-           "get_config"]
+__all__ = ["CONFIGS", "LayerInputs", "WorkloadConfig", "add_headroom", "as_bits", "base_seed",
+           "generate_layer", "get_config", "step_inputs"]

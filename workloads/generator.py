@@ -253,3 +253,52 @@ def generate_layer(cfg: WorkloadConfig, layer: int = 0, seed: int | None = None,
                        torch.from_numpy(table).to(device),
                        torch.from_numpy(ctx.astype(np.int32)).to(device),
                        torch.from_numpy(fill).to(device), fracs)
+
+
+def add_headroom(li: LayerInputs, extra_tokens: int) -> LayerInputs:
+    """The same cache with room to append `extra_tokens` tokens per request: every row of the block
+    table is extended with fresh pages, which sit at the end of the pools (zero-filled, fill 0)."""
+    B = li.ctx_lens.numel()
+    ctx = li.ctx_lens.cpu().numpy().astype(np.int64)
+    have = (ctx + PAGE - 1) // PAGE
+    need = (ctx + extra_tokens + PAGE - 1) // PAGE
+    extra = int((need - have).sum())
+    P0 = li.k_pool.shape[0]
+    pad = torch.zeros((extra,) + tuple(li.k_pool.shape[1:]), dtype=li.k_pool.dtype, device=li.k_pool.device)
+    table = np.zeros((B, max(int(need.max()), 1)), dtype=np.int32)
+    old = li.block_table.cpu().numpy()
+    nxt = P0
+    for r in range(B):
+        table[r, :have[r]] = old[r, :have[r]]
+        for b in range(int(have[r]), int(need[r])):
+            table[r, b] = nxt
+            nxt += 1
+    dev = li.k_pool.device
+    return LayerInputs(cfg=li.cfg, layer=li.layer, q=li.q.clone(),
+                       k_pool=torch.cat([li.k_pool, pad]).contiguous(), v_pool=torch.cat([li.v_pool, pad]).contiguous(),
+                       block_table=torch.from_numpy(table).to(dev), ctx_lens=li.ctx_lens.clone(),
+                       page_fill=torch.cat([li.page_fill, torch.zeros(extra, dtype=torch.int32, device=dev)]).contiguous(),
+                       frac=li.frac)
+
+
+def step_inputs(li: LayerInputs, step: int, seed: int | None = None):
+    """Inputs of decode step `step` = 1, 2, ... after the cache `li` was built: (q, k_new, v_new).
+    Queries drift slowly (each step adds a small seeded perturbation to the previous step's query:
+    consecutive decode queries are similar), the new token's keys and values are drawn like
+    background tokens.  Rounded to the cache's 16-bit type; the rounded bits are the input."""
+    if seed is None:
+        seed = base_seed(li.cfg.index)
+    dev = li.q.device
+    dt = li.q.dtype
+    B, Hq, d = li.q.shape
+    H = li.k_pool.shape[1]
+    q = li.q.float()
+    for t in range(1, step + 1):
+        g = torch.Generator(device="cpu")
+        g.manual_seed(_sub_seed(seed, 707, li.layer, t))
+        q = q + 0.15 * torch.randn((B, Hq, d), generator=g).to(dev)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(_sub_seed(seed, 709, li.layer, step))
+    k_new = torch.randn((B, H, d), generator=g).to(dev).to(dt)
+    v_new = torch.randn((B, H, d), generator=g).to(dev).to(dt)
+    return q.to(dt).contiguous(), k_new.contiguous(), v_new.contiguous()
