@@ -84,6 +84,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
     ap.add_argument("--check-granularity", type=int, default=1)
     ap.add_argument("--threshold", type=float, default=-1.0, help="override the workload's threshold (tuning)")
+    ap.add_argument("--scorer", type=int, default=0, help="0 = upper bound (default), 1 = cuboid centre")
     ap.add_argument("--chunk-blocks", type=int, default=0)
     ap.add_argument("--workgroups", type=int, default=0)
     ap.add_argument("--window-chunks", type=int, default=0)
@@ -159,7 +160,7 @@ def main():
         for i in range(L):
             psa.build_block_metadata(kvs[i], metas[i], page_fill=layers[i].page_fill, page_list=last_pages[i])
             psa.decode_attention(kvs[i], layers[i].q, metas[i], eps, m, workspace=ws, outputs=outs[i],
-                                 tuning=tunings[i] if tunings else tun)
+                                 tuning=tunings[i] if tunings else tun, scorer=args.scorer)
 
     # one plain 1 GiB device copy: the known-size kernel that hardware-counter runs are scaled by
     cal_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
@@ -384,6 +385,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "layers": L, "batch": B, "num_q_heads": Hq, "num_kv_heads": H,
                    "ctx": cfg.ctx, "kv_dtype": cfg.dtype, "threshold": eps, "check_granularity": m,
+                   "scorer": ["upper_bound", "cuboid_center"][args.scorer],
                    "chunk_blocks": args.chunk_blocks or 32, "parallelism": "1 GPU"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic,

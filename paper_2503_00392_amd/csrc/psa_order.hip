@@ -4,8 +4,8 @@
 // Main path: a monotone bucket map + exact in-bucket ranking.
 //   1. every thread holds 8 keys (order-preserving 32-bit images of the scores, inverted so that a
 //      smaller key is a larger score) and the workgroup reduces their minimum and maximum;
-//   2. bucket(key) = floor((key - min) * scale) is monotone in the key, so bucket order is key
-//      order; an LDS counter per bucket and a workgroup scan give each bucket its output range;
+//   2. bucket = floor((largest score - score) * scale) is monotone in the score, so bucket order is
+//      rank order; an LDS counter per bucket and a workgroup scan give each bucket its output range;
 //   3. an element's final rank is its bucket's base plus the number of elements of the same bucket
 //      that precede it under (key, index) -- counted exactly, so the result does not depend on the
 //      order in which the LDS atomics arrived.
@@ -49,6 +49,12 @@ __device__ __forceinline__ uint32_t descending_key(float score) {
     if (u == 0x80000000u) u = 0u;
     const uint32_t asc = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
     return ~asc;
+}
+
+// The score a key stands for (with -0 read as +0).
+__device__ __forceinline__ float score_of_key(uint32_t key) {
+    const uint32_t asc = ~key;
+    return __uint_as_float((asc & 0x80000000u) ? (asc & 0x7FFFFFFFu) : ~asc);
 }
 
 __device__ void bitonic_sort(unsigned long long (&e)[8], unsigned long long *lds_keys, int Np, int tid,
@@ -173,7 +179,13 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
     lds_barrier();
     kmin = 0xFFFFFFFFu; kmax = 0u;
     for (int w = 0; w < nwaves; ++w) { kmin = min(kmin, scratch[w]); kmax = max(kmax, scratch[16 + w]); }
-    const float scale = (float)NB / ((float)(kmax - kmin) + 1.0f);
+    // Buckets are equal steps of the SCORE between the largest and the smallest one (not of its bit
+    // pattern, which would crowd scores of small magnitude or mixed sign into a few buckets).  Every
+    // operation below is monotone in the score, so a block that ranks before another never lands in a
+    // later bucket; the exact order inside a bucket is settled by counting.
+    const float smax = score_of_key(kmin), span = smax - score_of_key(kmax);
+    const bool span_ok = span > 0.0f && span < INFINITY;       // false also for NaN: the fallback ranks then
+    const float scale = span_ok ? (float)NB / span : 0.0f;
     PSA_ORDER_STAMP(1)
 
     int bkt[8], arrival[8];
@@ -181,8 +193,9 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
     for (int j = 0; j < 8; ++j) {
         bkt[j] = 0; arrival[j] = 0;
         if (tid * 8 + j < N) {
-            int b = (int)((float)(key[j] - kmin) * scale);
-            b = b < 0 ? 0 : (b > NB - 1 ? NB - 1 : b);
+            const float fb = (smax - score_of_key(key[j])) * scale;
+            int b = fb >= (float)(NB - 1) ? NB - 1 : (int)fb;     // (a NaN compares false and converts to 0)
+            b = b < 0 ? 0 : b;
             bkt[j] = b;
             arrival[j] = (int)atomicAdd(&cnt[b], 1u);
         }
