@@ -42,7 +42,7 @@ DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t) {
 }
 
 struct WsLayout {
-    size_t header, ctl, scores, order, ranked_page, agg, block_lse, logits, partial, total;
+    size_t header, ctl, scores, order, ranked_page, agg, block_lse, logits, partial, value_items, total;
 #ifdef PSA_ENABLE_TRACE
     size_t trace;
 #endif
@@ -63,6 +63,7 @@ static WsLayout layout(const psa_kv_desc *d, const DecodePlan &p) {
     L.block_lse = at;   at = align_up(at + S * MB * G * 4, 256);
     L.logits = at;      at = align_up(at + S * MB * kPage * G * 4, 256);
     L.partial = at;     at = align_up(at + S * p.max_chunks * G * kPartialStride * 4, 256);
+    L.value_items = at; at = align_up(at + S * p.max_chunks * 4, 256);
 #ifdef PSA_ENABLE_TRACE
     L.trace = at;       at = align_up(at + (size_t)(2 + kTraceRecords) * 32, 256);
 #endif
@@ -92,6 +93,7 @@ hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const Decode
     ws.block_lse = reinterpret_cast<float *>(base + L.block_lse);
     ws.logits = reinterpret_cast<float *>(base + L.logits);
     ws.partial = reinterpret_cast<float *>(base + L.partial);
+    ws.value_items = reinterpret_cast<int32_t *>(base + L.value_items);
     ws.max_chunks = plan.max_chunks;
     ws.max_units = plan.max_chunks;
 #ifdef PSA_ENABLE_TRACE

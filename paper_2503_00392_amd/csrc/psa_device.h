@@ -58,7 +58,8 @@ struct alignas(128) StreamCtl {
 };
 
 struct DecodeWs {
-    int32_t *header;        // [1] sticky error bits
+    int32_t *header;        // [64]: word 1 = sticky error bits; word kValueCount (a cache line of its own) =
+                            // number of entries of value_items
     StreamCtl *ctl;         // [S]
     float *scores;          // [S][max_blocks]
     int32_t *order;         // [S][max_blocks]  ranked logical blocks
@@ -67,6 +68,8 @@ struct DecodeWs {
     float *block_lse;       // [S][max_blocks][G]  log2 of each ranked block's AS (Algorithm 1 line 10)
     float *logits;          // [S][max_blocks][G][16]  scaled logits (log2 units) by ranked block
     float *partial;         // [S][max_chunks][G][kPartialStride]
+    int32_t *value_items;   // [S * max_chunks] value units to attend: stream * max_chunks + chunk, appended by
+                            // each stream's fold when it closes the stream
     int32_t max_chunks;     // chunks per stream at most
     int32_t max_units;      // = max_chunks (stride of `partial`)
 #ifdef PSA_ENABLE_TRACE
@@ -78,6 +81,7 @@ constexpr int kTracePerWave = 256;
 constexpr int kTraceRecords = 4096 * kTracePerWave;   // up to 4096 waves
 #endif
 constexpr int kPartialStride = 132;  // M, l, pad, pad, acc[128]
+constexpr int kValueCount = 32;      // index of the value-item counter in the workspace header
 // A chunk word holds (L_chunk, Lmin_chunk) as two floats once the chunk is published.  Before that
 // it holds one of two NaN patterns no computation produces: "not published", or -- word 0 only --
 // "not published, and the fold stopped here": whoever publishes over that one carries on folding.

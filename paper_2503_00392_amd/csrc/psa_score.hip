@@ -24,6 +24,7 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
     // first kernel of a decode call: it clears the sticky error word and clamps silently; the
     // ranking kernel, which sees the same table entries and contexts, reports them
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 2) header[threadIdx.x] = 0;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 2) header[kValueCount] = 0;   // value work list
     const int ctx = ctx_clamped_quiet(kv, r);
     const int N = (ctx + kPage - 1) / kPage;
     const int base = blockIdx.x * 64 + wave * 16;

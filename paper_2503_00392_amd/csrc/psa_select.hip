@@ -270,6 +270,16 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
     if (lane < G) st_relaxed(&ctl->stop[lane], stop);
     if (lane == 0)
         st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)walked << 32) | (unsigned)walked);
+    // the stream's value units (the chunks up to its slowest head's stop) go onto the work list of the
+    // value pass, which therefore starts no workgroup for a chunk nobody selected
+    int nmax = (lane < G) ? ((stop == ~0ull) ? N : (int)(stop >> 32)) : 0;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) nmax = max(nmax, __shfl_xor(nmax, d));
+    const int units = (nmax + KU - 1) / KU;
+    int base = 0;
+    if (lane == 0) base = atomicAdd(&ws.header[kValueCount], units);
+    base = uniform(base);
+    for (int i = lane; i < units; i += 64) ws.value_items[base + i] = s * ws.max_chunks + i;
 }
 
 // =================================================================================================

@@ -5,8 +5,9 @@
 // attention over each head's own prefix: softmax numerators from the stored logits, times the value
 // slices of the selected blocks -- every workgroup independent, no waiting, and only blocks
 // actually selected are read.
-//   attend_kernel    one workgroup per (chunk, stream): p = exp(logit - chunk max), partial
-//                    numerator sum_t p_t v_t per head, exp-sum and reference maximum
+//   attend_kernel    per value unit (chunk, stream) on the work list the selection kernel wrote:
+//                    p = exp(logit - chunk max), partial numerator sum_t p_t v_t per head, exp-sum and
+//                    reference maximum
 //   finalize_kernel  merges a head's chunks (the online-softmax merge of line 11, all at once):
 //                    out_g = sum over the chunks of the head's own prefix of the partial numerators,
 //                    over the sum of the partial exp-sums, both rescaled to one reference maximum
@@ -35,11 +36,9 @@ __device__ __forceinline__ int head_stop(const StreamCtl *ctl, int g, int N) {
     return (st != ~0ull && (int)(st >> 32) <= N) ? (int)(st >> 32) : N;
 }
 
-// grid (max_chunks, S), 256 threads.
+// One value unit: chunk c of stream s.  Called by all 256 threads of a workgroup.
 template <int DT, int G>
-__global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int CB) {
-    __shared__ AttendShared<G> sh;
-    const int c = blockIdx.x, s = blockIdx.y;
+__device__ void attend_unit(AttendShared<G> &sh, const KvView &kv, const DecodeWs &ws, int CB, int s, int c) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, rg = lane >> 4, cl = lane & 15;
     const int h = s % kv.num_kv_heads;
     int ctx = kv.ctx_lens[s / kv.num_kv_heads];
@@ -175,6 +174,16 @@ __global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int
     }
 }
 
+// One workgroup per entry of the work list the selection kernel left; the grid is sized for the most
+// there can be, and a workgroup beyond the list's end returns after one load.
+template <int DT, int G>
+__global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int CB) {
+    __shared__ AttendShared<G> sh;
+    if ((int)blockIdx.x >= ws.header[kValueCount]) return;
+    const int item = ws.value_items[blockIdx.x];
+    attend_unit<DT, G>(sh, kv, ws, CB, item / ws.max_chunks, item % ws.max_chunks);
+}
+
 constexpr int kUnitLanes = 16;   // value units merged side by side by one workgroup
 
 // =================================================================================================
@@ -277,7 +286,8 @@ __global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, i
 
 template <int DT, int G>
 static hipError_t launch_attend_t(const KvView &kv, const DecodeWs &ws, const DecodePlan &plan, hipStream_t st) {
-    attend_kernel<DT, G><<<dim3(plan.max_chunks, kv.batch * kv.num_kv_heads), 256, 0, st>>>(kv, ws, plan.chunk_blocks);
+    const unsigned grid = (unsigned)(kv.batch * kv.num_kv_heads) * (unsigned)plan.max_chunks;
+    attend_kernel<DT, G><<<grid, 256, 0, st>>>(kv, ws, plan.chunk_blocks);
     return hipGetLastError();
 }
 
