@@ -37,6 +37,10 @@ DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t) {
     p.max_chunks = (d->max_blocks_per_seq + p.chunk_blocks - 1) / p.chunk_blocks;
     if (p.max_chunks < 1) p.max_chunks = 1;
     p.force_bitonic = t ? t->force_bitonic : 0;
+    {
+        const long long items = (long long)d->batch * d->num_kv_heads * p.max_chunks;
+        p.select_grid = (int)(items < p.persistent_wgs ? items : p.persistent_wgs);
+    }
     p.events = t ? static_cast<hipEvent_t *>(t->phase_events) : nullptr;
     return p;
 }
@@ -107,9 +111,9 @@ hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const Decode
     if (ev) (void)hipEventRecord(ev[0], st);
     if ((e = launch_score(kv, d->dtype, G, a.scorer, a.q, a.meta, ws, a.scores_out, st)) != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);
-    if ((e = launch_order(kv, ws, G, plan.chunk_blocks, a.budget_blocks, plan.force_bitonic, a.order_out, st)) != hipSuccess) return e;
+    if ((e = launch_order(kv, ws, G, plan, a.budget_blocks, a.order_out, st)) != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[2], st);
-    if ((e = launch_select(kv, d->dtype, G, a.q, ws, a.threshold, a.check_granularity, plan, st)) != hipSuccess)
+    if ((e = launch_select(kv, d->dtype, G, a.q, ws, a.threshold, a.check_granularity, a.budget_blocks, plan, st)) != hipSuccess)
         return e;
     if (ev) (void)hipEventRecord(ev[3], st);
     if ((e = launch_attend(kv, d->dtype, G, ws, plan, st)) != hipSuccess) return e;

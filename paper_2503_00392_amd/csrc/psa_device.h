@@ -81,6 +81,7 @@ constexpr int kTracePerWave = 256;
 constexpr int kTraceRecords = 4096 * kTracePerWave;   // up to 4096 waves
 #endif
 constexpr int kPartialStride = 132;  // M, l, pad, pad, acc[128]
+constexpr int kMaxWindowChunks = 256; // chunks handed out beyond the fold's frontier, at most
 constexpr int kValueCount = 32;      // index of the value-item counter in the workspace header
 // A chunk word holds (L_chunk, Lmin_chunk) as two floats once the chunk is published.  Before that
 // it holds one of two NaN patterns no computation produces: "not published", or -- word 0 only --

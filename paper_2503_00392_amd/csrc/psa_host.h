@@ -46,7 +46,8 @@ struct DecodePlan {
     int window_chunks;
     int spin_limit;
     int max_chunks;
-    int persistent_wgs;   // workgroups of the progressive kernel's persistent grid
+    int persistent_wgs;   // workgroups of the progressive kernel's persistent grid, at most
+    int select_grid;      // ... and how many are launched (no more than there are chunks)
     int force_bitonic;
     hipEvent_t *events;   // NULL or 6 events recorded between the kernels
 };
@@ -72,10 +73,10 @@ hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const Decode
 // psa_score.hip, psa_order.hip, psa_select.hip, psa_values.hip: the kernels of one decode call
 hipError_t launch_score(const KvView &kv, int dtype, int G, int scorer, const void *q, const void *meta,
                         const DecodeWs &ws, float *scores_out, hipStream_t st);
-hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int KU, int budget_blocks, int force_bitonic,
+hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, const DecodePlan &plan, int budget_blocks,
                         int32_t *order_out, hipStream_t st);
 hipError_t launch_select(const KvView &kv, int dtype, int G, const void *q, const DecodeWs &ws, float eps,
-                         int m, const DecodePlan &plan, hipStream_t st);
+                         int m, int budget_blocks, const DecodePlan &plan, hipStream_t st);
 hipError_t launch_attend(const KvView &kv, int dtype, int G, const DecodeWs &ws, const DecodePlan &plan,
                          hipStream_t st);
 hipError_t launch_finalize(const KvView &kv, const DecodeWs &ws, int G, int VU, float *out,

@@ -107,7 +107,8 @@ __device__ void bitonic_sort(unsigned long long (&e)[8], unsigned long long *lds
     }
 }
 
-__global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int G, int KU, int budget_blocks, int Np,
+__global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int G, int KU, int budget_blocks,
+                                                     int select_grid, int window, int Np,
                                                       int force_bitonic,
                                                       int32_t *__restrict__ order_out) {
     extern __shared__ unsigned long long lds_raw[];
@@ -139,7 +140,12 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         // key chunks that may ever be handed out: all of them, or those a fixed budget of blocks covers
         const int nlim = budget_blocks > 0 ? min(N, budget_blocks) : N;
         const unsigned nch = (unsigned)((nlim + KU - 1) / KU);
-        c->k_next = 0; c->k_blocks = 0; c->attached = 0;
+        // the selection kernel's workgroup b starts on stream b mod S with chunk b / S, without asking:
+        // those first chunks count as handed out
+        const int S = gridDim.y;
+        const int starters = s < select_grid ? (select_grid - s + S - 1) / S : 0;
+        c->k_next = min(min(starters, window), (int)nch);
+        c->k_blocks = 0; c->attached = 0;
         c->key_progress = (unsigned long long)nch << 32;                                  // frontier 0
         for (int g = 0; g < 8; ++g) { c->Lacc[g] = -INFINITY; c->Lmin[g] = INFINITY; c->stop[g] = ~0ull; }
     }
@@ -320,7 +326,7 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
     PSA_ORDER_STAMP(6)
 }
 
-hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int KU, int budget_blocks, int force_bitonic,
+hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, const DecodePlan &plan, int budget_blocks,
                         int32_t *order_out, hipStream_t st) {
     const int S = kv.batch * kv.num_kv_heads;
     int Np = 512;
@@ -337,7 +343,9 @@ hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, int KU, int
     int parts = 256 / (S > 0 ? S : 1);
     parts = parts < 1 ? 1 : (parts > 4 ? 4 : parts);
     if (Np < 2048) parts = 1;
-    order_kernel<<<dim3(parts, S), Np / 8, lds, st>>>(kv, ws, G, KU, budget_blocks, Np, force_bitonic, order_out);
+    order_kernel<<<dim3(parts, S), Np / 8, lds, st>>>(kv, ws, G, plan.chunk_blocks, budget_blocks, plan.select_grid,
+                                                      plan.window_chunks < kMaxWindowChunks ? plan.window_chunks : kMaxWindowChunks,
+                                                      Np, plan.force_bitonic, order_out);
     return hipGetLastError();
 }
 

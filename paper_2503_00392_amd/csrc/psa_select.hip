@@ -106,7 +106,6 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
 
 constexpr int kBatch = 4;            // key slices a wave keeps in flight
 constexpr int kSelectThreads = 512;  // 8 waves: a 32-block chunk is one batch per wave
-constexpr int kMaxWindow = 256;      // chunks handed out beyond the frontier, at most
 constexpr int kMaxJoiners = 32;      // workgroups that may join a stream beyond its first ones
 
 // Tokens of stream s's request, clamped like everywhere else.
@@ -117,7 +116,7 @@ __device__ __forceinline__ int stream_ctx(const KvView &kv, int s) {
 
 __device__ __forceinline__ int window_of(int window, int frontier) {
     const int w = max(window, frontier >> 1);
-    return w > kMaxWindow ? kMaxWindow : w;
+    return w > kMaxWindowChunks ? kMaxWindowChunks : w;
 }
 
 // P_acc of Algorithm 1 lines 15-16 in the log2 domain: AS_acc / (AS_acc + AS_min * N_left).
@@ -373,14 +372,24 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     PSA_STAMP(3)
     if (wave != 0) return;
 
-    // ---- publish: the chunk's fold over its own blocks in rank order, one lane per head ------------------
+    // ---- publish: the chunk's (log-sum-exp, minimum) of its blocks' L_b per head.  Lane = (slot, head):
+    //      64/G slots each fold every (64/G)-th block, then a butterfly over the slots -- a fixed tree, so
+    //      the word is reproducible; lse2 is symmetric, so every lane of a head ends with the same bits. -------
     float aggL = -INFINITY, aggMin = INFINITY;
-    if (lane < G)
-        for (int i = 0; i < nblk; ++i) {
-            const float Lb = sh.Lb[i][lane];
+    {
+        constexpr int kSlots = 64 / G;
+        const int g = lane % G;
+        for (int i = lane / G; i < nblk; i += kSlots) {
+            const float Lb = sh.Lb[i][g];
             aggL = lse2(aggL, Lb);
             aggMin = fminf(aggMin, Lb);
         }
+#pragma unroll
+        for (int d = G; d < 64; d <<= 1) {
+            aggL = lse2(aggL, __shfl_xor(aggL, d));
+            aggMin = fminf(aggMin, __shfl_xor(aggMin, d));
+        }
+    }
     unsigned long long w = pack2(aggL, aggMin);
     if (w >= kAggArmed) w = kAggArmed - 1;     // a NaN that happens to look like one of the marks
     unsigned long long *cw = &ws.agg[((size_t)s * ws.max_chunks + c) * G];
@@ -401,12 +410,12 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
 template <int DT, int G>
 __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, const uint8_t *__restrict__ q,
                                                                 DecodeWs ws, float eps, int m, int CB,
-                                                                int window, int spin_limit) {
+                                                                int window, int spin_limit, int budget_blocks) {
     __shared__ SelectShared<G> sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = kv.batch * kv.num_kv_heads;
     int home = blockIdx.x % S;
-    bool joined = false;
+    bool joined = false, starting = true;
     [[maybe_unused]] int trace_n = 0;
     PSA_TRACE(5, home, 0, PSA_NOW());
     while (true) {
@@ -417,21 +426,31 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
             [[maybe_unused]] const unsigned long long td = PSA_NOW();
             if (tid == 0) {
                 int what = 3, item = -1;
-                const unsigned long long kp = ld_relaxed(&ctl->key_progress);
-                const int fr = (int)(kp & 0xffffffffull), lim = (int)(kp >> 32);
-                const int nx = ld_relaxed(&ctl->k_next);
-                if (nx < lim) {
-                    what = 2;
-                    if (nx < fr + window_of(window, fr)) {
-                        item = atomicAdd(&ctl->k_next, 1);
-                        if (item < lim) what = 0;   // (lim can only have shrunk: a stale pass reads a chunk nobody needs)
+                if (starting) {
+                    // the first chunk needs no ticket: workgroup b takes chunk b / S of stream b mod S (the
+                    // ranking kernel has counted these as handed out)
+                    const int first = blockIdx.x / S;
+                    const int nlim = budget_blocks > 0 ? min(N, budget_blocks) : N;
+                    if (first < window_of(window, 0) && first * CB < nlim) { what = 0; item = first; }
+                }
+                if (what != 0) {
+                    const unsigned long long kp = ld_relaxed(&ctl->key_progress);
+                    const int fr = (int)(kp & 0xffffffffull), lim = (int)(kp >> 32);
+                    const int nx = ld_relaxed(&ctl->k_next);
+                    if (nx < lim) {
+                        what = 2;
+                        if (nx < fr + window_of(window, fr)) {
+                            item = atomicAdd(&ctl->k_next, 1);
+                            if (item < lim) what = 0;   // (lim can only have shrunk: a stale pass reads a chunk nobody needs)
+                        }
+                        if (what == 2 && ++tries > spin_limit) what = 4;
                     }
-                    if (what == 2 && ++tries > spin_limit) what = 4;
                 }
                 sh.what = what;
                 sh.item = item;
             }
             lds_barrier();
+            starting = false;
             const int what = sh.what, item = sh.item;
             PSA_TRACE(9, home, what, td);
             if (what == 0) {
@@ -501,18 +520,17 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
 
 template <int DT, int G>
 static hipError_t launch_select_t(const KvView &kv, const void *q, const DecodeWs &ws, float eps, int m,
-                                  const DecodePlan &plan, hipStream_t st) {
-    const unsigned items = (unsigned)(kv.batch * kv.num_kv_heads) * (unsigned)plan.max_chunks;
-    const unsigned grid = items < (unsigned)plan.persistent_wgs ? items : (unsigned)plan.persistent_wgs;
+                                  int budget_blocks, const DecodePlan &plan, hipStream_t st) {
+    const unsigned grid = (unsigned)plan.select_grid;
     select_kernel<DT, G><<<grid, kSelectThreads, 0, st>>>(kv, (const uint8_t *)q, ws, eps, m, plan.chunk_blocks,
-                                               plan.window_chunks, plan.spin_limit);
+                                               plan.window_chunks, plan.spin_limit, budget_blocks);
     return hipGetLastError();
 }
 
 hipError_t launch_select(const KvView &kv, int dtype, int G, const void *q, const DecodeWs &ws, float eps,
-                         int m, const DecodePlan &plan, hipStream_t st) {
+                         int m, int budget_blocks, const DecodePlan &plan, hipStream_t st) {
 #define PSA_CASE(DT, GG) \
-    if (dtype == DT && G == GG) return launch_select_t<DT, GG>(kv, q, ws, eps, m, plan, st);
+    if (dtype == DT && G == GG) return launch_select_t<DT, GG>(kv, q, ws, eps, m, budget_blocks, plan, st);
     PSA_CASE(0, 1) PSA_CASE(0, 2) PSA_CASE(0, 4) PSA_CASE(0, 8)
     PSA_CASE(1, 1) PSA_CASE(1, 2) PSA_CASE(1, 4) PSA_CASE(1, 8)
 #undef PSA_CASE
