@@ -126,30 +126,62 @@ __global__ __launch_bounds__(256) void dense_split_kernel(KvView kv, const uint8
     }
 }
 
-// grid (S*G); 128 threads: one per channel.
-__global__ __launch_bounds__(128) void dense_combine_kernel(const float *__restrict__ partial, int nsplit,
+// grid (S*G); 512 threads = 4 split lanes x 128 channels.  Split lane j takes splits j, j+4, ... in
+// ascending order (loads issued four deep, no branches); the 4 lanes are then added in a fixed order.
+__global__ __launch_bounds__(512) void dense_combine_kernel(const float *__restrict__ partial, int nsplit,
                                                             int G, int num_kv_heads, int num_q_heads,
                                                             float *__restrict__ out,
                                                             float *__restrict__ lse) {
-    const int s = blockIdx.x / G, g = blockIdx.x % G, ch = threadIdx.x;
+    __shared__ float red[512];
+    __shared__ float wgt[1024];                 // rescale factor of every split (nsplit <= 1024)
+    __shared__ float num_part[4][kHeadDim];
+    __shared__ float den_part[4];
+    const int s = blockIdx.x / G, g = blockIdx.x % G, tid = threadIdx.x;
+    const int ch = tid & 127, sl = tid >> 7;
     const int r = s / num_kv_heads, h = s % num_kv_heads;
     const float *src = partial + ((size_t)s * nsplit * G + g) * kDenseStride;
     const size_t stride = (size_t)G * kDenseStride;
     float M = -INFINITY;
-    for (int i = 0; i < nsplit; ++i) M = fmaxf(M, src[i * stride]);
+    for (int i = tid; i < nsplit; i += 512) { const float mi = src[i * stride]; wgt[i] = mi; M = fmaxf(M, mi); }
+    red[tid] = M;
+    __syncthreads();
+    for (int d = 256; d >= 1; d >>= 1) {
+        if (tid < d) red[tid] = fmaxf(red[tid], red[tid + d]);
+        __syncthreads();
+    }
+    M = red[0];
+    __syncthreads();
+    for (int i = tid; i < nsplit; i += 512) {
+        const float mi = wgt[i];
+        wgt[i] = (mi == -INFINITY || M == -INFINITY) ? 0.0f : exp2_fast(mi - M);
+    }
+    __syncthreads();
     float num = 0.0f, den = 0.0f;
-    if (M != -INFINITY) {
-        for (int i = 0; i < nsplit; ++i) {
-            const float mi = src[i * stride];
-            if (mi == -INFINITY) continue;
-            const float w = exp2_fast(mi - M);
-            den += src[i * stride + 1] * w;
-            num += src[i * stride + 4 + ch] * w;
+    for (int i0 = sl; i0 < nsplit; i0 += 16) {
+        float a[4], l[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int i = min(i0 + 4 * k, nsplit - 1);          // clamped: the loads need no branch
+            a[k] = src[i * stride + 4 + ch];
+            l[k] = src[i * stride + 1];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const float w = (i0 + 4 * k < nsplit) ? wgt[i0 + 4 * k] : 0.0f;
+            num = fmaf(a[k], w, num);
+            den = fmaf(l[k], w, den);
         }
     }
-    const size_t qi = (size_t)r * num_q_heads + h * G + g;
-    out[qi * kHeadDim + ch] = den > 0.0f ? num / den : 0.0f;
-    if (lse && ch == 0) lse[qi] = den > 0.0f ? (M + log2_fast(den)) * kLn2 : -INFINITY;
+    num_part[sl][ch] = num;
+    if (ch == 0) den_part[sl] = den;
+    __syncthreads();
+    if (tid < kHeadDim) {
+        const float n = (num_part[0][tid] + num_part[1][tid]) + (num_part[2][tid] + num_part[3][tid]);
+        const float dsum = (den_part[0] + den_part[1]) + (den_part[2] + den_part[3]);
+        const size_t qi = (size_t)r * num_q_heads + h * G + g;
+        out[qi * kHeadDim + tid] = dsum > 0.0f ? n / dsum : 0.0f;
+        if (lse && tid == 0) lse[qi] = dsum > 0.0f ? (M + log2_fast(dsum)) * kLn2 : -INFINITY;
+    }
 }
 
 // ---- host side ----------------------------------------------------------------------------------
@@ -177,7 +209,7 @@ static hipError_t launch_dense_t(const KvView &kv, const void *q, float *out, fl
     const int bps = (kv.max_blocks + nsplit - 1) / nsplit;
     clear_words_kernel<<<1, 64, 0, st>>>(header, 64);
     dense_split_kernel<DT, G><<<dim3(nsplit, S), 256, 0, st>>>(kv, (const uint8_t *)q, partial, bps, header);
-    dense_combine_kernel<<<S * G, 128, 0, st>>>(partial, nsplit, G, kv.num_kv_heads, kv.num_q_heads, out, lse);
+    dense_combine_kernel<<<S * G, 512, 0, st>>>(partial, nsplit, G, kv.num_kv_heads, kv.num_q_heads, out, lse);
     return hipGetLastError();
 }
 
