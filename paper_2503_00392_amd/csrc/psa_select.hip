@@ -89,6 +89,9 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
     }
 #define PSA_NOW() wall_clock64()
 #define PSA_STAMP(K) if (threadIdx.x == 0) sh.stamp[K] = wall_clock64();
+#define PSA_FOLD_STAMP() if (threadIdx.x == 0 && *fold_n < 16) fold_t[(*fold_n)++] = wall_clock64();
+#define PSA_FOLD_ARGS , unsigned long long *fold_t, int *fold_n
+#define PSA_FOLD_PASS , sh.fold_stamp, &sh.fold_stamps
 #define PSA_TRACE_SPAN(KIND, S, IDX, T0, T1)                                                   \
     if (threadIdx.x == 0 && trace_n < kTracePerWave) {                                         \
         unsigned long long *rec_ = ws.trace + 8 + ((size_t)blockIdx.x * kTracePerWave + trace_n) * 4; \
@@ -99,6 +102,9 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
     }
 #else
 #define PSA_STAMP(K)
+#define PSA_FOLD_STAMP()
+#define PSA_FOLD_ARGS
+#define PSA_FOLD_PASS
 #define PSA_TRACE_SPAN(KIND, S, IDX, T0, T1)
 #define PSA_TRACE(KIND, S, IDX, T0)
 #define PSA_NOW() 0ull
@@ -136,11 +142,14 @@ struct SelectShared {
     float Lb[kMaxChunkBlocks][G];          // per-block log2-sum-exp2
     int page[kMaxChunkBlocks];
     int valid[kMaxChunkBlocks];
-    int what;                              // 0: chunk `item`; 2: nothing right now; 3: all handed out; 4: give up
+    int what;                              // 0: chunk `item`; 3: all handed out; 4: give up
     int item;
+    int go;                                // after the wait for the window: 1 = read the chunk, 0 = dropped, 2 = gave up
     int next;                              // stream to join, -1 = leave
 #ifdef PSA_ENABLE_TRACE
     unsigned long long stamp[8];
+    unsigned long long fold_stamp[16];
+    int fold_stamps;
 #endif
 };
 
@@ -150,16 +159,19 @@ struct SelectShared {
 // Leaves either with the stream's key side closed, or with the mark on the first unpublished chunk.
 // =================================================================================================
 template <int G>
-__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU, int fr) {
+__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU, int fr PSA_FOLD_ARGS) {
     // fr: the chunk the mark was on, which is where the previous holder of the fold stopped
     const int lane = threadIdx.x & 63;
     StreamCtl *ctl = &ws.ctl[s];
     const int ctx = stream_ctx(kv, s);
     const int N = (ctx + kPage - 1) / kPage;
-    // chunks that will ever be published: all of them unless the ranking kernel set a budget
-    // (all loads of this prologue are issued before the first of them is waited for)
+    constexpr int CPR = 64 / G;                // chunks per load round: lane = (chunk j, head)
+    const unsigned long long *agg = ws.agg + (size_t)s * ws.max_chunks * G;
+    const int hg = lane < G ? lane : 0;
+    // One round trip for everything the fold starts from: the chunk limit (all chunks unless the ranking
+    // kernel set a budget), the state the previous holder left, and the words of the next 4*CPR chunks
+    // (words of chunks that will never be published hold the "not published" pattern).
     const unsigned long long kp0 = ld_relaxed(&ctl->key_progress);
-    int fr_pub = fr;                           // frontier as the progress word shows it
     float Lacc = -INFINITY, Lmin = INFINITY;
     unsigned long long stop = 0ull;            // lanes >= G count as stopped
     if (lane < G) {
@@ -167,94 +179,102 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
         Lmin = ld_relaxed(&ctl->Lmin[lane]);
         stop = ld_relaxed(&ctl->stop[lane]);
     }
-    constexpr int CPR = 64 / G;                // chunks per load round: lane = (chunk j, head)
-    const unsigned long long *agg = ws.agg + (size_t)s * ws.max_chunks * G;
-    const int hg = lane < G ? lane : 0;
-    bool finished = false;
+    // (The fold runs rarely and on one wave, so its instructions are usually not in the instruction
+    // cache: the loops below are deliberately not unrolled -- compact code beats straight-line code here.)
+    unsigned long long v;
+    {
+        const int ci = fr + lane / G;
+        v = (ci < ws.max_chunks) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
+    }
+    const int nch = uniform((int)(kp0 >> 32));
+    PSA_FOLD_STAMP()
+    int fr_pub = fr;                           // frontier as the progress word shows it
     int walked = fr;
-    int nch = ws.max_chunks;                   // until the limit has arrived; words beyond it hold the sentinel
-    bool first = true;
-    while (!finished) {
-        unsigned long long v[4];
-        int k = 0;
-        bool gap = false;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int ci = fr + u * CPR + lane / G;
-            v[u] = (ci < nch) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
-        }
-        if (first) { nch = uniform((int)(kp0 >> 32)); first = false; }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const unsigned long long pub = __ballot(v[u] < kAggArmed);
-            const int ones = (pub == ~0ull) ? 64 : (__ffsll((long long)~pub) - 1);
-            const int ku = ones / G;           // leading chunks of this round with all G words published
-            if (!gap) k += ku;
-            if (ku < CPR) gap = true;
-        }
-        if (k > 0) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            for (int j = 0; j < CPR; ++j) {
-                const int i = u * CPR + j;
-                if (i >= k || finished) break;
-                const unsigned long long a = shfl_u64(v[u], j * G + hg);
-                if (stop == ~0ull) {
-                    const float L2 = lse2(Lacc, __uint_as_float((uint32_t)(a & 0xffffffffull)));
-                    const float M2 = fminf(Lmin, __uint_as_float((uint32_t)(a >> 32)));
-                    const int cidx = fr + i;
-                    const int n_end = min((cidx + 1) * KU, N);
-                    // a stop inside this chunk needs a position where the rule is tested (line 17 is reached
-                    // every m blocks and at the last block) and, P_acc being non-decreasing, a pass at its end
-                    const bool tested = (n_end / m) * m > cidx * KU || n_end == N;
-                    if (tested && p_acc(L2, M2, N - n_end) > eps) {
-                        // the stop may lie in this chunk: block by block, in rank order
-                        const int b0 = cidx * KU;
-                        const float *lb = ws.block_lse + ((size_t)s * kv.max_blocks + b0) * G + lane;
-                        float fl = Lacc, fm = Lmin;
-                        for (int t = 0; t < n_end - b0; ++t) {
-                            const float Lb = ld_relaxed(&lb[(size_t)t * G]);
-                            fl = lse2(fl, Lb);
-                            fm = fminf(fm, Lb);
-                            const int nn = b0 + t + 1;
-                            if (nn % m == 0 || nn == N) {
-                                const float P = p_acc(fl, fm, N - nn);
-                                if (P > eps) {
-                                    stop = ((unsigned long long)nn << 32) | __float_as_uint(P);
-                                    break;
-                                }
-                            }
-                        }
+    bool finished = false;
+    while (true) {
+        // v: the words of chunks fr .. fr+CPR-1; k = how many leading ones are completely published
+        const unsigned long long pub = __ballot(v < kAggArmed);
+        const int k = ((pub == ~0ull) ? 64 : (__ffsll((long long)~pub) - 1)) / G;
+        const bool gap = k < CPR;
+#pragma nounroll
+        for (int j = 0; j < k && !finished; ++j) {
+            const unsigned long long a = shfl_u64(v, j * G + hg);
+            const float L2 = lse2(Lacc, __uint_as_float((uint32_t)(a & 0xffffffffull)));
+            const float M2 = fminf(Lmin, __uint_as_float((uint32_t)(a >> 32)));
+            const int cidx = fr + j;
+            const int b0 = cidx * KU, n_end = min(b0 + KU, N);
+            // a stop inside this chunk needs a position where the rule is tested (line 17 is reached
+            // every m blocks and at the last block) and, P_acc being non-decreasing, a pass at its end
+            const bool tested = (n_end / m) * m > b0 || n_end == N;
+            const bool scan = stop == ~0ull && tested && p_acc(L2, M2, N - n_end) > eps;
+            if (__ballot(scan) != 0ull) {
+                // Some head may stop in this chunk.  Its blocks' L_b are fetched 64 at a time, lane = (block,
+                // head); a prefix scan over the blocks of each head (steps of G lanes) gives AS_acc and AS_min
+                // after every block, hence P_acc at every position; the first position that passes is the stop.
+                // (A fixed scan shape: reproducible.  It is not the left fold bit for bit, which only matters
+                // where P_acc is within rounding of the threshold.)
+                const float *lb = ws.block_lse + ((size_t)s * kv.max_blocks + b0) * G;
+                const int cnt = (n_end - b0) * G;
+                const unsigned long long head_lanes = (~0ull / ((1ull << G) - 1ull)) << hg;   // lanes of my head
+                float cl = __shfl(Lacc, lane % G), cm = __shfl(Lmin, lane % G);              // carried in
+                bool found = false;
+#pragma nounroll
+                for (int x0 = 0; x0 < cnt; x0 += 64) {
+                    const bool valid = x0 + lane < cnt;
+                    float pl = ld_relaxed(&lb[min(x0 + lane, cnt - 1)]);
+                    float pm = pl;
+#pragma nounroll
+                    for (int d = G; d < 64; d <<= 1) {
+                        const float ol = __shfl_up(pl, d), om = __shfl_up(pm, d);
+                        if (lane >= d) { pl = lse2(ol, pl); pm = fminf(om, pm); }
                     }
-                    Lacc = L2;
-                    Lmin = M2;
+                    const float fl = lse2(cl, pl), fm = fminf(cm, pm);
+                    const int nn = b0 + (x0 + lane) / G + 1;
+                    const float P = p_acc(fl, fm, N - nn);
+                    const unsigned long long hits = __ballot(valid && (nn % m == 0 || nn == N) && P > eps) & head_lanes;
+                    const int src = hits ? (__ffsll((long long)hits) - 1) : 0;
+                    const float Pf = __shfl(P, src);
+                    if (scan && !found && hits) {
+                        stop = ((unsigned long long)(b0 + (x0 + src) / G + 1) << 32) | __float_as_uint(Pf);
+                        found = true;
+                    }
+                    const int last = (min(64, cnt - x0) / G - 1) * G + lane % G;   // my head's last block of this group
+                    cl = __shfl(fl, last);
+                    cm = __shfl(fm, last);
                 }
-                walked = fr + i + 1;
-                if (__ballot(stop == ~0ull) == 0ull) finished = true;
             }
+            if (stop == ~0ull || scan) { Lacc = L2; Lmin = M2; }
+            walked = cidx + 1;
+            if (__ballot(stop == ~0ull) == 0ull) finished = true;
         }
-        }
+        PSA_FOLD_STAMP()
         fr = walked;
         if (fr >= nch) finished = true;
         if (finished) break;
         const bool moved = walked != fr_pub;
         fr_pub = walked;
-        if (!gap) {
-            // all 4 rounds were published: open the window further and load the next ones
-            if (lane == 0 && moved)
-                st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)nch << 32) | (unsigned)walked);
-            continue;
-        }
-        // chunk fr is not published: leave the state and the frontier behind and mark the chunk; if it
-        // was published meanwhile the mark fails and the fold simply carries on
-        if (lane < G) {
+        // the frontier (it opens the window for waiting workgroups), the state if the fold may have to be
+        // handed over, and the next chunk words -- one round trip for all of it
+        if (lane == 0 && moved)
+            st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)nch << 32) | (unsigned)walked);
+        if (gap && lane < G) {
             st_relaxed(&ctl->Lacc[lane], Lacc);
             st_relaxed(&ctl->Lmin[lane], Lmin);
             st_relaxed(&ctl->stop[lane], stop);
         }
-        if (lane == 0 && moved)
-            st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)nch << 32) | (unsigned)walked);
-        stores_done();                 // whoever finds the mark finds the state, and stores its own frontier later
+        {
+            const int ci = fr + lane / G;
+            v = (ci < nch) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
+        }
+        stores_done();
+        PSA_FOLD_STAMP()
+        if (!gap) continue;
+        {
+            const unsigned long long pub2 = __ballot(v < kAggArmed);
+            const int ones2 = (pub2 == ~0ull) ? 64 : (__ffsll((long long)~pub2) - 1);
+            if (ones2 >= G) continue;          // chunk fr was published meanwhile: carry on folding
+        }
+        // chunk fr is not published: mark it (the state is in place); whoever publishes it carries on
         unsigned long long seen = 0;
         if (lane == 0) {
             unsigned long long expected = kAggSentinel;
@@ -263,7 +283,13 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
                                                  __HIP_MEMORY_SCOPE_AGENT);
             seen = expected;
         }
-        if (uniform((int)(seen == kAggSentinel))) return;     // marked: the chunk's publisher carries on
+        PSA_FOLD_STAMP()
+        if (uniform((int)(seen == kAggSentinel))) return;
+        // published between the look and the mark: fetch the words again and carry on
+        {
+            const int ci = fr + lane / G;
+            v = (ci < nch) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
+        }
     }
     // every head has stopped, or the blocks ran out: close the key side (limit = frontier)
     if (lane < G) st_relaxed(&ctl->stop[lane], stop);
@@ -285,6 +311,22 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
 // Key work of one workgroup: chunk c of stream s.  Ends with the chunk published; wave 0 carries
 // the fold on if it was waiting for this chunk.
 // =================================================================================================
+// Physical page and valid-token count of each ranked block of chunk c of stream s -> LDS.  Issued as soon
+// as the workgroup holds the chunk's ticket, so that the loads overlap its wait for the window.
+template <int G>
+__device__ __forceinline__ void stage_pages(SelectShared<G> &sh, const KvView &kv, const DecodeWs &ws, int CB,
+                                            int s, int c) {
+    const int tid = threadIdx.x;
+    const int ctx = stream_ctx(kv, s);
+    const int N = (ctx + kPage - 1) / kPage;
+    const int nblk = min(CB, N - c * CB);
+    const size_t row0 = (size_t)s * kv.max_blocks + c * CB;
+    if (tid < nblk) {
+        sh.page[tid] = ws.ranked_page[row0 + tid];
+        sh.valid[tid] = min(kPage, ctx - ws.order[row0 + tid] * kPage);
+    }
+}
+
 template <int DT, int G>
 __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8_t *__restrict__ q,
                               const DecodeWs &ws, float eps, int m, int CB, int s, int c) {
@@ -295,12 +337,7 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     const int start = c * CB;
     const int nblk = min(CB, N - start);
     const size_t row0 = (size_t)s * kv.max_blocks + start;
-
-    // physical page and valid-token count of each ranked block of the chunk -> LDS
-    if (tid < nblk) {
-        sh.page[tid] = ws.ranked_page[row0 + tid];
-        sh.valid[tid] = min(kPage, ctx - ws.order[row0 + tid] * kPage);
-    }
+    // (the chunk's pages and valid-token counts are in LDS already: stage_pages)
     // B operand of the QK^T product: column n = lane%16 is query head n (zero beyond the group),
     // k block kq = lane/16; for step kk the lane holds channels 8*(4*kk + kq) .. +7.
     const int n = lane & 15, kq = lane >> 4;
@@ -399,7 +436,10 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     unsigned long long old = 0;
     if (lane == 0) old = __hip_atomic_exchange(cw, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     PSA_STAMP(4)
-    if (uniform((int)(old == kAggArmed))) fold_stream<G>(kv, ws, s, eps, m, CB, c);
+#ifdef PSA_ENABLE_TRACE
+    if (threadIdx.x == 0) sh.fold_stamps = 0;
+#endif
+    if (uniform((int)(old == kAggArmed))) fold_stream<G>(kv, ws, s, eps, m, CB, c PSA_FOLD_PASS);
     PSA_STAMP(5)
 }
 
@@ -421,7 +461,7 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
     while (true) {
         StreamCtl *ctl = &ws.ctl[home];
         const int N = (stream_ctx(kv, home) + kPage - 1) / kPage;
-        int tries = 0, k_loaded = 0;
+        int k_loaded = 0;
         while (true) {
             [[maybe_unused]] const unsigned long long td = PSA_NOW();
             if (tid == 0) {
@@ -434,42 +474,62 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
                     if (first < window_of(window, 0) && first * CB < nlim) { what = 0; item = first; }
                 }
                 if (what != 0) {
-                    const unsigned long long kp = ld_relaxed(&ctl->key_progress);
-                    const int fr = (int)(kp & 0xffffffffull), lim = (int)(kp >> 32);
-                    const int nx = ld_relaxed(&ctl->k_next);
-                    if (nx < lim) {
-                        what = 2;
-                        if (nx < fr + window_of(window, fr)) {
-                            item = atomicAdd(&ctl->k_next, 1);
-                            if (item < lim) what = 0;   // (lim can only have shrunk: a stale pass reads a chunk nobody needs)
-                        }
-                        if (what == 2 && ++tries > spin_limit) what = 4;
+                    // a ticket, taken whether or not the read-ahead window reaches it yet: the wait for the
+                    // window comes afterwards, with the chunk's page numbers already on their way
+                    const int lim = (int)(ld_relaxed(&ctl->key_progress) >> 32);
+                    if (ld_relaxed(&ctl->k_next) < lim) {
+                        item = atomicAdd(&ctl->k_next, 1);
+                        if (item < lim) what = 0;
                     }
                 }
                 sh.what = what;
                 sh.item = item;
             }
             lds_barrier();
+            const bool started = starting;
             starting = false;
             const int what = sh.what, item = sh.item;
             PSA_TRACE(9, home, what, td);
-            if (what == 0) {
+            if (what != 0) break;                      // the stream has no chunk left to hand out
+            stage_pages<G>(sh, kv, ws, CB, home, item);
+            if (tid == 0) {
+                // chunks handed out beyond the fold's frontier are at most the window: wait until this one is
+                // inside it, or the stream closes before it (then the ticket is dropped)
+                int go = 1;
+                if (!started) {
+                    [[maybe_unused]] const unsigned long long t0 = PSA_NOW();
+                    for (int tries = 0;; ++tries) {
+                        const unsigned long long kp = ld_relaxed(&ctl->key_progress);
+                        const int fr = (int)(kp & 0xffffffffull), lim = (int)(kp >> 32);
+                        if (item >= lim) { go = 0; break; }
+                        if (item < fr + window_of(window, fr)) break;
+                        if (tries >= spin_limit) { go = 2; break; }
+                        nap(tries);
+                    }
+                    PSA_TRACE(4, home, item, t0);
+                }
+                sh.go = go;
+            }
+            lds_barrier();
+            const int go = sh.go;
+            if (go == 1) {
                 [[maybe_unused]] const unsigned long long t0 = PSA_NOW();
                 process_chunk<DT, G>(sh, kv, q, ws, eps, m, CB, home, item);
                 PSA_TRACE(1, home, item, t0);
-                PSA_TRACE_SPAN(10, home, item, t0, sh.stamp[0]);             // ticket known -> pages staged
+                PSA_TRACE_SPAN(10, home, item, t0, sh.stamp[0]);             // queries loaded
                 PSA_TRACE_SPAN(11, home, item, sh.stamp[0], sh.stamp[1]);    // keys loaded, logits computed (wave 0)
                 PSA_TRACE_SPAN(12, home, item, sh.stamp[1], sh.stamp[2]);    // the other waves
                 PSA_TRACE_SPAN(13, home, item, sh.stamp[2], sh.stamp[3]);    // stores complete
                 PSA_TRACE_SPAN(14, home, item, sh.stamp[3], sh.stamp[4]);    // published
                 PSA_TRACE_SPAN(15, home, item, sh.stamp[4], sh.stamp[5]);    // fold, if it was this chunk's turn
+#ifdef PSA_ENABLE_TRACE
+                if (tid == 0)
+                    for (int fj = 0; fj < sh.fold_stamps; ++fj) { PSA_TRACE_SPAN(20 + fj, home, item, sh.stamp[4], sh.fold_stamp[fj]); }
+#endif
                 k_loaded += min(CB, N - item * CB);
-                tries = 0;
-            } else if (what == 2) {
-                [[maybe_unused]] const unsigned long long t0 = PSA_NOW();
-                nap(tries);
-                PSA_TRACE(4, home, tries, t0);
-            } else {
+            } else if (go == 2) {
+                if (tid == 0) sh.what = 4;
+                lds_barrier();
                 break;
             }
             lds_barrier();      // everyone has read sh.what before thread 0 decides again
