@@ -29,8 +29,9 @@ DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t) {
     if (t && t->window_chunks > 0) {
         p.window_chunks = t->window_chunks;
     } else {
-        // about 48 MiB of key slices in flight over all streams, 2 to 32 chunks per stream
-        const long long per_stream = (48ll << 20) / ((long long)(S > 0 ? S : 1) * p.chunk_blocks * kSliceBytes);
+        // about 64 MiB of key slices in flight over all streams (with 2 workgroups per CU: one chunk per
+        // workgroup), 2 to 32 chunks per stream
+        const long long per_stream = (64ll << 20) / ((long long)(S > 0 ? S : 1) * p.chunk_blocks * kSliceBytes);
         p.window_chunks = per_stream < 2 ? 2 : (per_stream > 32 ? 32 : (int)per_stream);
     }
     p.spin_limit = (t && t->spin_limit > 0) ? t->spin_limit : (1 << 17);
