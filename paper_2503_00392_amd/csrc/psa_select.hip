@@ -131,10 +131,10 @@ __device__ __forceinline__ float p_acc(float Lacc, float Lmin, int n_left) {
 }
 
 __device__ __forceinline__ void nap(int tries) {
-    // about half a microsecond, then about two: long enough that the pollers of one stream stay well
-    // below what one cache line serves, short enough that an opening window is noticed at once
+    // about half a microsecond, then about one: long enough that the pollers of one stream stay below
+    // what one cache line serves, short enough that an opening window is noticed at once
     __builtin_amdgcn_s_sleep(20);
-    if (tries > 1) __builtin_amdgcn_s_sleep(60);
+    if (tries > 1) __builtin_amdgcn_s_sleep(20);
 }
 
 template <int G>
