@@ -6,9 +6,10 @@
 // consecutive ranked blocks, the unit of work of a workgroup.
 //
 // A persistent grid of workgroups (8 waves each).  A workgroup attached to a stream repeats:
-//   1. take the stream's next chunk ticket (fetch-and-add), but only while the read-ahead window
-//      is open -- chunks handed out beyond the fold's frontier are at most max(window, frontier/2),
-//      256 at most, which bounds the keys read beyond the stop;
+//   1. take the stream's next chunk ticket (fetch-and-add), fetch the chunk's page numbers, then wait
+//      until the chunk is inside the read-ahead window -- chunks read beyond the fold's frontier are at
+//      most max(window, frontier/2), 256 at most, which bounds the keys read beyond the stop -- or
+//      drop the ticket if the stream closes first;
 //   2. read the chunk's key slices (each wave keeps 4 slices = 16 KiB in flight), compute the
 //      scaled logits of all G heads as a 16-token x 16-head x 128-channel product on the matrix
 //      cores (heads beyond G are zero columns), store them for the value pass, and reduce each
@@ -16,8 +17,8 @@
 //   3. publish the chunk's (log-sum-exp, minimum) of L_b per head as one 64-bit word per head.
 // THE FOLD applies lines 12-17 strictly in rank order: AS_acc, AS_min, N_left and P_acc at the end
 // of each published chunk after the frontier and, in the first chunk where P_acc exceeds the
-// threshold, block by block to find the head's exact stop.  It is a token: exactly one wave at a
-// time folds.  When it reaches a chunk that is not yet published it marks that chunk's word "the
+// threshold, with a prefix scan over the chunk's blocks to find the head's exact stop.  It is a
+// token: exactly one wave at a time folds.  When it reaches a chunk that is not yet published it marks that chunk's word "the
 // fold waits here" and its workgroup goes back to key work; the workgroup that later publishes over
 // the mark (an atomic exchange tells it) picks the fold up from the state left in the control
 // block.  So no workgroup ever waits for another one, nobody polls for the fold, nothing is locked.
