@@ -140,6 +140,7 @@ __device__ __forceinline__ void nap(int tries) {
 
 template <int G>
 struct SelectShared {
+    uint4 qb[4][64];                       // B operand of the QK^T product for the attached stream, by lane
     float Lb[kMaxChunkBlocks][G];          // per-block log2-sum-exp2
     int page[kMaxChunkBlocks];
     int valid[kMaxChunkBlocks];
@@ -328,27 +329,38 @@ __device__ __forceinline__ void stage_pages(SelectShared<G> &sh, const KvView &k
     }
 }
 
+// B operand of the QK^T product of stream s -> LDS, once per stream a workgroup attaches to: column
+// n = lane%16 is query head n (zero beyond the group), k block kq = lane/16; for step kk the lane holds
+// channels 8*(4*kk + kq) .. +7.  (The caller's next barrier makes it visible.)
+template <int G>
+__device__ __forceinline__ void load_queries(SelectShared<G> &sh, const KvView &kv, const uint8_t *__restrict__ q,
+                                             int s) {
+    const int tid = threadIdx.x;
+    if (tid < 256) {
+        const int kk = tid >> 6, ln = tid & 63, n = ln & 15, kq = ln >> 4;
+        const int r = s / kv.num_kv_heads, h = s % kv.num_kv_heads;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (n < G) v = ld16(q + ((size_t)(r * kv.num_q_heads + h * G + n) * kHeadDim + (4 * kk + kq) * 8) * 2);
+        sh.qb[kk][ln] = v;
+    }
+}
+
 template <int DT, int G>
 __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8_t *__restrict__ q,
                               const DecodeWs &ws, float eps, int m, int CB, int s, int c) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = s / kv.num_kv_heads, h = s % kv.num_kv_heads;
+    const int h = s % kv.num_kv_heads;
     const int ctx = stream_ctx(kv, s);
     const int N = (ctx + kPage - 1) / kPage;
     const int start = c * CB;
     const int nblk = min(CB, N - start);
     const size_t row0 = (size_t)s * kv.max_blocks + start;
     // (the chunk's pages and valid-token counts are in LDS already: stage_pages)
-    // B operand of the QK^T product: column n = lane%16 is query head n (zero beyond the group),
-    // k block kq = lane/16; for step kk the lane holds channels 8*(4*kk + kq) .. +7.
+    // B operand of the QK^T product (see load_queries): the same for every chunk of the stream
     const int n = lane & 15, kq = lane >> 4;
     uint4 qb[4];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        qb[kk] = make_uint4(0, 0, 0, 0);
-        if (n < G)
-            qb[kk] = ld16(q + ((size_t)(r * kv.num_q_heads + h * G + n) * kHeadDim + (4 * kk + kq) * 8) * 2);
-    }
+    for (int kk = 0; kk < 4; ++kk) qb[kk] = sh.qb[kk][lane];
     float *lg_out = ws.logits + row0 * (kPage * G);
     lds_barrier();
     PSA_STAMP(0)
@@ -463,6 +475,7 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
         StreamCtl *ctl = &ws.ctl[home];
         const int N = (stream_ctx(kv, home) + kPage - 1) / kPage;
         int k_loaded = 0;
+        load_queries<G>(sh, kv, q, home);
         while (true) {
             [[maybe_unused]] const unsigned long long td = PSA_NOW();
             if (tid == 0) {
@@ -477,11 +490,11 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
                 if (what != 0) {
                     // a ticket, taken whether or not the read-ahead window reaches it yet: the wait for the
                     // window comes afterwards, with the chunk's page numbers already on their way
-                    const int lim = (int)(ld_relaxed(&ctl->key_progress) >> 32);
-                    if (ld_relaxed(&ctl->k_next) < lim) {
-                        item = atomicAdd(&ctl->k_next, 1);
-                        if (item < lim) what = 0;
-                    }
+                    // (a ticket beyond the limit means the stream has none left; the counter then simply
+                    // runs ahead of the limit, which reads as "nothing to hand out" everywhere)
+                    const unsigned long long kp = ld_relaxed(&ctl->key_progress);
+                    item = atomicAdd(&ctl->k_next, 1);
+                    if (item < (int)(kp >> 32)) what = 0;
                 }
                 sh.what = what;
                 sh.item = item;
