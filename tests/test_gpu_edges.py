@@ -1,0 +1,117 @@
+"""GPU edge cases through the C ABI: empty and one-token requests inside a batch, lengths around a
+page boundary, and inputs only the device can see are wrong (a table entry outside the pool, a length
+beyond the table row, a negative length) -- the kernels clamp, say so in the sticky error word, and
+leave the other requests' results untouched."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_common as gc
+from oracle import psa_oracle as po
+from workloads import generate_layer, get_config
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def psa():
+    import paper_2503_00392_amd as psa
+    psa.load_library()
+    assert torch.cuda.is_available()
+    return psa
+
+
+def _layer(batch, ctx):
+    return generate_layer(get_config(1).scaled(batch=batch, ctx=ctx), device="cuda", poison_tail=True)
+
+
+LENGTHS = [0, 1, 15, 16, 17, 0, 300, 33]
+
+
+def _cut(li, lengths):
+    li.ctx_lens.copy_(torch.tensor(lengths, dtype=torch.int32))
+    pb = gc.to_problem(li)
+    return pb, torch.from_numpy(pb.page_fill()).cuda()
+
+
+@pytest.mark.parametrize("eps,m", [(0.9, 1), (0.5, 3), (1.0, 1), (0.0, 2)])
+def test_empty_tiny_and_page_boundary_requests(psa, eps, m):
+    li = _layer(len(LENGTHS), 320)
+    pb, fill = _cut(li, LENGTHS)
+    kv = gc.to_kv(li)
+    meta = psa.build_block_metadata(kv, page_fill=fill)
+    gpu = psa.decode_attention(kv, li.q, meta, eps, m, want_order=True, want_scores=True, want_traffic=True)
+    torch.cuda.synchronize()
+    assert psa.read_device_error(gpu._workspace) == 0
+    rep = gc.check_decode_against_oracle(pb, gpu, eps, m)
+    empty = [i for i, n in enumerate(LENGTHS) if n == 0]
+    assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads - len(empty) * pb.q.shape[1]
+    for r in empty:
+        assert not gpu.out[r].any() and not gpu.n_selected[r].any() and not gpu.mass_est[r].any()
+        assert torch.isneginf(gpu.lse[r]).all() and not gpu.blocks_read[r].any()
+        assert (gpu.order[r] == -1).all()
+    one = LENGTHS.index(1)                       # a single token: attention returns its value, estimate 1
+    assert (gpu.n_selected[one] == 1).all() and (gpu.mass_est[one] == 1.0).all()
+    page = int(li.block_table[one, 0])
+    G = li.cfg.group
+    for hq in range(li.cfg.num_q_heads):
+        assert torch.equal(gpu.out[one, hq], li.v_pool[page, hq // G, 0].float())
+
+
+def test_dense_and_topk_on_the_same_batch(psa):
+    li = _layer(len(LENGTHS), 320)
+    pb, fill = _cut(li, LENGTHS)
+    kv = gc.to_kv(li)
+    out, lse = psa.dense_attention(kv, li.q)
+    torch.cuda.synchronize()
+    want, wlse = po.dense_attention(pb)
+    live = np.array(LENGTHS) > 0
+    assert gc.rel_l2(out.cpu().numpy().astype(np.float64), want).max() <= gc.OUT_RTOL
+    np.testing.assert_allclose(lse.cpu().numpy()[live], wlse[live], rtol=0, atol=2e-3)
+    assert torch.isneginf(lse[~torch.from_numpy(live).cuda()]).all() and not out[~torch.from_numpy(live).cuda()].any()
+    meta = psa.build_block_metadata(kv, page_fill=fill)
+    top = psa.topk_attention(kv, li.q, meta, 2, want_order=True)
+    torch.cuda.synchronize()
+    nb = pb.num_blocks()
+    assert np.array_equal(top.n_selected.cpu().numpy(), np.repeat(np.minimum(2, nb)[:, None], li.cfg.num_q_heads, 1))
+    own = po.attend_prefix(pb, top.order.cpu().numpy(), top.n_selected.cpu().numpy())
+    assert gc.rel_l2(top.out.cpu().numpy().astype(np.float64), own).max() <= gc.OUT_RTOL
+
+
+def test_inputs_only_the_device_can_see_are_wrong(psa):
+    """Request 1 gets a table entry outside the pool, request 2 a length beyond its table row, request
+    3 a negative length.  Nothing faults; the error word names both kinds; requests 0 and 4 come out
+    exactly as in the clean run."""
+    li = _layer(5, 640)
+    kv = gc.to_kv(li)
+    meta = psa.build_block_metadata(kv, page_fill=li.page_fill)
+    clean = psa.decode_attention(kv, li.q, meta, 0.9, 1, want_order=True)
+    dclean, _ = psa.dense_attention(kv, li.q)
+    torch.cuda.synchronize()
+    assert psa.read_device_error(clean._workspace) == 0
+    li.block_table[1, 7] = li.k_pool.shape[0] + 12345
+    li.ctx_lens[2] = li.block_table.shape[1] * 16 + 999
+    li.ctx_lens[3] = -5
+    bad = psa.decode_attention(kv, li.q, meta, 0.9, 1, want_order=True)
+    torch.cuda.synchronize()
+    flags = psa.read_device_error(bad._workspace)
+    assert flags & 1 and flags & 2 and not flags & 4, flags
+    assert torch.isfinite(bad.out).all()
+    for r in (0, 4):
+        assert torch.equal(bad.out[r], clean.out[r]) and torch.equal(bad.n_selected[r], clean.n_selected[r])
+        assert torch.equal(bad.order[r], clean.order[r])
+    assert not bad.out[3].any() and not bad.n_selected[3].any()          # negative length reads as empty
+    assert (bad.n_selected[2] <= li.block_table.shape[1]).all()          # clamped to the row
+    dbad, _ = psa.dense_attention(kv, li.q)
+    torch.cuda.synchronize()
+    dflags = psa.read_device_error(dbad._workspace)
+    assert dflags & 1 and dflags & 2
+    for r in (0, 4):
+        assert torch.equal(dbad[r], dclean[r])
+    # the next clean call starts from a clean error word
+    li.block_table[1, 7] = 0
+    li.ctx_lens[2] = 640
+    li.ctx_lens[3] = 640
+    again = psa.decode_attention(kv, li.q, meta, 0.9, 1, workspace=bad._workspace)
+    torch.cuda.synchronize()
+    assert psa.read_device_error(again._workspace) == 0
