@@ -204,6 +204,24 @@ def main():
     spec_k_bytes = int(((traffic[..., 0] - blocks_read) * 4096).sum())
     eff_gbs = alg_bytes / (ms_per_step * 1e-3) / 1e9
 
+    # ---- the same step with a depth hint per (request, KV head): the blocks the previous step read.  The
+    # steps of this benchmark are identical, so the hint is exact -- the upper bound of what the similarity
+    # of consecutive decode queries can give; `value` above is measured without any hint. ------------------
+    hints = [o.blocks_read.clone() for o in outs]
+    hinted_tun = [psa.Tuning(depth_hint=hints[i], **tuning_kw) for i in range(L)]
+    step(hinted_tun)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        step(hinted_tun)
+    e1.record()
+    torch.cuda.synchronize()
+    hint_ms = e0.elapsed_time(e1) / args.steps
+    hint_same = all(torch.equal(o.blocks_read, h) for o, h in zip(outs, hints))
+    hinted = {"ms_per_step": hint_ms, "query_heads_per_s": q_heads_per_step / (hint_ms * 1e-3),
+              "same_selection_as_without_hint": bool(hint_same),
+              "hint": "blocks_read of an identical previous step (exact: an upper bound for real decode loops)"}
+
     # ---- per-kernel durations, live, with HIP events recorded by the library around its kernels ----
     hev = HipEvents()
     ev_sets = [[hev.array(6) for _ in range(L)] for _ in range(args.steps)]
@@ -397,6 +415,7 @@ def main():
                        "mean_selected_fraction": float((blocks_read / np.maximum(N_total, 1)).mean()),
                        "phase_avg_ms_per_layer": phase_avg,
                        "kernel_GBps": kern_gbs},
+        "with_depth_hint": hinted,
         "dense_control": dense,
         "topk_control": topk,
         "scorer_comparison": scorers,

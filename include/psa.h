@@ -88,6 +88,11 @@ typedef struct {
     int32_t spin_limit;     /* polls of a waiting workgroup before it gives up (default 1<<17)        */
     int32_t force_bitonic;  /* 1: always rank with the bitonic network (testing); 0: automatic        */
     int32_t workgroups;     /* workgroups of the persistent selection kernel (default 2 per CU)       */
+    const int32_t *depth_hint; /* device pointer or NULL: [batch][num_kv_heads] blocks each (request, KV head)
+                               is expected to need, e.g. blocks_read of the previous decode step of the
+                               same layer (consecutive decode queries select similar sets).  The chunks
+                               that cover it are read at once instead of window by window; a wrong hint
+                               costs time or traffic, never correctness                               */
     void *phase_events;     /* host pointer: NULL, or hipEvent_t[6] the call records on `stream`
                                before scoring and after each of its kernels: scoring, ranking,
                                selection (key pass), attention (value pass), final merge

@@ -42,6 +42,7 @@ DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t) {
         const long long items = (long long)d->batch * d->num_kv_heads * p.max_chunks;
         p.select_grid = (int)(items < p.persistent_wgs ? items : p.persistent_wgs);
     }
+    p.depth_hint = t ? t->depth_hint : nullptr;
     p.events = t ? static_cast<hipEvent_t *>(t->phase_events) : nullptr;
     return p;
 }

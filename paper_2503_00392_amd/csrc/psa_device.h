@@ -232,4 +232,12 @@ __device__ __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b) {
                                                                   __builtin_bit_cast(ushort2_t, b)));
 }
 
+// Chunks of a stream that are inside the read-ahead window from the start because the caller expects
+// the stream to need them (0 without a hint).
+__device__ __forceinline__ int hinted_chunks(const int32_t *depth_hint, int s, int N, int CB) {
+    if (!depth_hint) return 0;
+    const int h = depth_hint[s];
+    return h <= 0 ? 0 : (min(h, N) + CB - 1) / CB;
+}
+
 }  // namespace psa

@@ -49,6 +49,7 @@ struct DecodePlan {
     int persistent_wgs;   // workgroups of the progressive kernel's persistent grid, at most
     int select_grid;      // ... and how many are launched (no more than there are chunks)
     int force_bitonic;
+    const int32_t *depth_hint;   // NULL or [S] expected blocks per stream (device)
     hipEvent_t *events;   // NULL or 6 events recorded between the kernels
 };
 DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t);

@@ -108,7 +108,7 @@ __device__ void bitonic_sort(unsigned long long (&e)[8], unsigned long long *lds
 }
 
 __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int G, int KU, int budget_blocks,
-                                                     int select_grid, int window, int Np,
+                                                     int select_grid, int window, const int32_t *depth_hint, int Np,
                                                       int force_bitonic,
                                                       int32_t *__restrict__ order_out) {
     extern __shared__ unsigned long long lds_raw[];
@@ -144,7 +144,8 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         // those first chunks count as handed out
         const int S = gridDim.y;
         const int starters = s < select_grid ? (select_grid - s + S - 1) / S : 0;
-        c->k_next = min(min(starters, window), (int)nch);
+        const int hinted = hinted_chunks(depth_hint, s, N, KU);
+        c->k_next = min(min(starters, hinted > 0 ? hinted + 1 : window), (int)nch);
         c->k_blocks = 0; c->attached = 0;
         c->key_progress = (unsigned long long)nch << 32;                                  // frontier 0
         for (int g = 0; g < 8; ++g) { c->Lacc[g] = -INFINITY; c->Lmin[g] = INFINITY; c->stop[g] = ~0ull; }
@@ -345,7 +346,7 @@ hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, const Decod
     if (Np < 2048) parts = 1;
     order_kernel<<<dim3(parts, S), Np / 8, lds, st>>>(kv, ws, G, plan.chunk_blocks, budget_blocks, plan.select_grid,
                                                       plan.window_chunks < kMaxWindowChunks ? plan.window_chunks : kMaxWindowChunks,
-                                                      Np, plan.force_bitonic, order_out);
+                                                      plan.depth_hint, Np, plan.force_bitonic, order_out);
     return hipGetLastError();
 }
 

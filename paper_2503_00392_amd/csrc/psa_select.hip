@@ -463,7 +463,8 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
 template <int DT, int G>
 __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, const uint8_t *__restrict__ q,
                                                                 DecodeWs ws, float eps, int m, int CB,
-                                                                int window, int spin_limit, int budget_blocks) {
+                                                                int window, int spin_limit, int budget_blocks,
+                                                                const int32_t *depth_hint) {
     __shared__ SelectShared<G> sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = kv.batch * kv.num_kv_heads;
@@ -476,6 +477,7 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
         const int N = (stream_ctx(kv, home) + kPage - 1) / kPage;
         int k_loaded = 0;
         load_queries<G>(sh, kv, q, home);
+        const int hinted = hinted_chunks(depth_hint, home, N, CB);     // inside the window whatever the frontier
         while (true) {
             [[maybe_unused]] const unsigned long long td = PSA_NOW();
             if (tid == 0) {
@@ -485,7 +487,7 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
                     // ranking kernel has counted these as handed out)
                     const int first = blockIdx.x / S;
                     const int nlim = budget_blocks > 0 ? min(N, budget_blocks) : N;
-                    if (first < window_of(window, 0) && first * CB < nlim) { what = 0; item = first; }
+                    if (first < (hinted > 0 ? hinted + 1 : window_of(window, 0)) && first * CB < nlim) { what = 0; item = first; }
                 }
                 if (what != 0) {
                     // a ticket, taken whether or not the read-ahead window reaches it yet: the wait for the
@@ -516,7 +518,11 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
                         const unsigned long long kp = ld_relaxed(&ctl->key_progress);
                         const int fr = (int)(kp & 0xffffffffull), lim = (int)(kp >> 32);
                         if (item >= lim) { go = 0; break; }
-                        if (item < fr + window_of(window, fr)) break;
+                        // with a hint: everything up to it (and a chunk more) at once; past it, a window that
+                        // starts small and doubles with the distance the hint fell short by
+                        const int reach = hinted > 0 ? max(hinted + 1, fr + min(max(4, 2 * (fr - hinted)), window_of(window, fr)))
+                                                     : fr + window_of(window, fr);
+                        if (item < reach) break;
                         if (tries >= spin_limit) { go = 2; break; }
                         nap(tries);
                     }
@@ -597,7 +603,7 @@ static hipError_t launch_select_t(const KvView &kv, const void *q, const DecodeW
                                   int budget_blocks, const DecodePlan &plan, hipStream_t st) {
     const unsigned grid = (unsigned)plan.select_grid;
     select_kernel<DT, G><<<grid, kSelectThreads, 0, st>>>(kv, (const uint8_t *)q, ws, eps, m, plan.chunk_blocks,
-                                               plan.window_chunks, plan.spin_limit, budget_blocks);
+                                               plan.window_chunks, plan.spin_limit, budget_blocks, plan.depth_hint);
     return hipGetLastError();
 }
 

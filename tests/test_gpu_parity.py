@@ -283,3 +283,25 @@ def test_append_reports_a_full_table_row_and_leaves_the_request_alone(psa):
     assert torch.equal(li.k_pool[page0], before_k[page0]) and torch.equal(meta[page0].view(torch.int16), before_meta[page0].view(torch.int16))
     last = int(li.block_table[1, 3])
     assert torch.equal(li.k_pool[last, :, 15].view(torch.int16), k_new[1].view(torch.int16))
+
+
+@pytest.mark.parametrize("kind", ["exact", "zero", "huge", "random"])
+def test_depth_hint_changes_traffic_not_results(psa, case, kind):
+    """A hint of how deep each stream will go only moves the read-ahead: any hint, right or wrong, gives
+    the same selection and the same bits."""
+    name, cfg, li, pb = case
+    base = gc.run_gpu_decode(li, cfg.threshold, 1)
+    B, H = cfg.batch, cfg.num_kv_heads
+    if kind == "exact":
+        hint = base.blocks_read.clone()
+    elif kind == "zero":
+        hint = torch.zeros((B, H), dtype=torch.int32, device="cuda")
+    elif kind == "huge":
+        hint = torch.full((B, H), 1 << 30, dtype=torch.int32, device="cuda")
+    else:
+        hint = torch.randint(-5, 3000, (B, H), dtype=torch.int32, device="cuda", generator=torch.Generator("cuda").manual_seed(7))
+    alt = gc.run_gpu_decode(li, cfg.threshold, 1, tuning=psa.Tuning(depth_hint=hint))
+    assert torch.equal(base.out, alt.out) and torch.equal(base.n_selected, alt.n_selected)
+    assert torch.equal(base.mass_est, alt.mass_est) and torch.equal(base.order, alt.order)
+    if kind == "exact":          # keys are then read no further than whole chunks of what is needed, plus the window
+        assert (alt.traffic[..., 0] >= base.blocks_read).all()
