@@ -86,7 +86,6 @@ def main():
     ap.add_argument("--threshold", type=float, default=-1.0, help="override the workload's threshold (tuning)")
     ap.add_argument("--scorer", type=int, default=0, help="0 = upper bound (default), 1 = cuboid centre")
     ap.add_argument("--chunk-blocks", type=int, default=0)
-    ap.add_argument("--workgroups", type=int, default=0)
     ap.add_argument("--window-chunks", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
@@ -114,7 +113,7 @@ def main():
         cfg = cfg.scaled(layers=args.layers)
     L, B, Hq, H, G = cfg.layers, cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.group
     eps, m = (args.threshold if args.threshold >= 0 else cfg.threshold), args.check_granularity
-    tuning_kw = dict(chunk_blocks=args.chunk_blocks, window_chunks=args.window_chunks, workgroups=args.workgroups)
+    tuning_kw = dict(chunk_blocks=args.chunk_blocks, window_chunks=args.window_chunks)
 
     # ---- inputs, resident in HBM ---------------------------------------------------------------
     t0 = time.time()

@@ -19,8 +19,7 @@
  *     What the host can see is checked there (null required pointer, shapes, threshold outside
  *     [0,1] or NaN, check_granularity < 1, workspace too small).  What only the device can see
  *     (a block-table entry outside [0,num_pages), a context longer than max_blocks_per_seq pages,
- *     a negative context length, an idle worker whose bounded polling ran out) is clamped by the
- *     kernels, which set a sticky bit in the workspace that psa_read_device_error returns.
+ *     a negative context length) is clamped by the kernels, which set a sticky bit in the workspace that psa_read_device_error returns.
  *   - Element type of Q, K, V and metadata: IEEE binary16 or bfloat16, 2 bytes.
  *   - Supported shapes: head_dim == 128, page_size == 16, num_q_heads / num_kv_heads in
  *     {1, 2, 4, 8}, max_blocks_per_seq <= 8192 for psa_decode_attention (128K tokens).
@@ -49,8 +48,7 @@ typedef enum { PSA_F16 = 0, PSA_BF16 = 1 } psa_dtype;
 /* Bits of the sticky device error word (psa_read_device_error). */
 enum {
     PSA_DEVERR_PAGE_RANGE = 1,   /* block-table entry outside [0, num_pages): page 0 was used   */
-    PSA_DEVERR_CTX_RANGE = 2,    /* ctx_len < 0 or > 16*max_blocks_per_seq: clamped             */
-    PSA_DEVERR_WAIT_EXPIRED = 4  /* a worker's bounded polling ran out: results are not reliable */
+    PSA_DEVERR_CTX_RANGE = 2     /* ctx_len < 0 or > 16*max_blocks_per_seq: clamped             */
 };
 
 /* Shapes and layout of ONE layer's paged KV cache (PagedAttention layout, Sec. 2.1 "KV Cache"). */
@@ -82,12 +80,12 @@ typedef struct {
  * speculatively and how work is cut, never which blocks are selected. */
 typedef struct {
     int32_t chunk_blocks;   /* ranked blocks per work item: a multiple of 4 in 8..64 (default 32)      */
-    int32_t window_chunks;  /* least number of chunks of one (request, KV head) handed out beyond the
-                               chunks already folded into the stop rule; the window grows to half the
-                               folded count, at most 256 (default: from the number of streams)        */
-    int32_t spin_limit;     /* polls of a waiting workgroup before it gives up (default 1<<17)        */
+    int32_t window_chunks;  /* least number of chunks of one (request, KV head) read beyond the chunks
+                               already folded into the stop rule; the window grows to half the folded
+                               count, at most 256 (default: from the number of streams)               */
+    int32_t spin_limit;     /* looks (about a microsecond apart) a workgroup takes at the window before it
+                               reads its chunk regardless (default 1<<14); the wait only limits read-ahead  */
     int32_t force_bitonic;  /* 1: always rank with the bitonic network (testing); 0: automatic        */
-    int32_t workgroups;     /* workgroups of the persistent selection kernel (default 2 per CU)       */
     const int32_t *depth_hint; /* device pointer or NULL: [batch][num_kv_heads] blocks each (request, KV head)
                                is expected to need, e.g. blocks_read of the previous decode step of the
                                same layer (consecutive decode queries select similar sets).  The chunks

@@ -17,7 +17,7 @@ _LIB_PATH = os.path.join(_HERE, "libpsa.so")
 
 PSA_F16, PSA_BF16 = 0, 1
 PSA_OK = 0
-DEVERR_PAGE_RANGE, DEVERR_CTX_RANGE, DEVERR_WAIT_EXPIRED = 1, 2, 4
+DEVERR_PAGE_RANGE, DEVERR_CTX_RANGE = 1, 2
 
 
 class PsaError(RuntimeError):
@@ -36,7 +36,7 @@ class _KvDesc(C.Structure):
 
 class _Tuning(C.Structure):
     _fields_ = [("chunk_blocks", C.c_int32), ("window_chunks", C.c_int32), ("spin_limit", C.c_int32),
-                ("force_bitonic", C.c_int32), ("workgroups", C.c_int32), ("depth_hint", C.c_void_p),
+                ("force_bitonic", C.c_int32), ("depth_hint", C.c_void_p),
                 ("phase_events", C.c_void_p)]
 
 
@@ -46,15 +46,13 @@ class Tuning:
     window_chunks: int = 0
     spin_limit: int = 0
     force_bitonic: int = 0
-    workgroups: int = 0
     depth_hint: object = None     # int32 device tensor [B][Hkv], or None
     phase_events: object = None   # ctypes array of 6 hipEvent_t (c_void_p), or None
 
     def c(self) -> _Tuning:
         ev = C.cast(self.phase_events, C.c_void_p) if self.phase_events is not None else None
         hint = self.depth_hint.data_ptr() if self.depth_hint is not None else None
-        return _Tuning(self.chunk_blocks, self.window_chunks, self.spin_limit, self.force_bitonic,
-                       self.workgroups, hint, ev)
+        return _Tuning(self.chunk_blocks, self.window_chunks, self.spin_limit, self.force_bitonic, hint, ev)
 
 
 _lib = None

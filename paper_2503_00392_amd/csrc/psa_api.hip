@@ -90,8 +90,7 @@ static psa_status decode_common(const psa_kv_desc *d, const void *q, const void 
     if (tuning) {
         const int cb = tuning->chunk_blocks;
         if (cb != 0 && (cb < 8 || cb > psa::kMaxChunkBlocks || cb % 4 != 0)) return PSA_ERR_INVALID_ARG;
-        if (tuning->window_chunks < 0 || tuning->spin_limit < 0 || tuning->workgroups < 0)
-            return PSA_ERR_INVALID_ARG;
+        if (tuning->window_chunks < 0 || tuning->spin_limit < 0) return PSA_ERR_INVALID_ARG;
         if (tuning->force_bitonic < 0 || tuning->force_bitonic > 1) return PSA_ERR_INVALID_ARG;
     }
     if (d->batch == 0) return PSA_OK;

@@ -25,23 +25,18 @@ DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t) {
     DecodePlan p;
     const int S = d->batch * d->num_kv_heads;
     p.chunk_blocks = (t && t->chunk_blocks) ? t->chunk_blocks : 32;
-    p.persistent_wgs = (t && t->workgroups > 0) ? t->workgroups : compute_units() * 2;   // 512-thread workgroups
     if (t && t->window_chunks > 0) {
         p.window_chunks = t->window_chunks;
     } else {
-        // about 64 MiB of key slices in flight over all streams (with 2 workgroups per CU: one chunk per
-        // workgroup), 2 to 32 chunks per stream
-        const long long per_stream = (64ll << 20) / ((long long)(S > 0 ? S : 1) * p.chunk_blocks * kSliceBytes);
+        // about 128 MiB of key slices in flight over all streams (four 4-wave workgroups per CU, one 128 KiB
+        // chunk each, on 256 CUs), 2 to 32 chunks per stream
+        const long long per_stream = (128ll << 20) / ((long long)(S > 0 ? S : 1) * p.chunk_blocks * kSliceBytes);
         p.window_chunks = per_stream < 2 ? 2 : (per_stream > 32 ? 32 : (int)per_stream);
     }
-    p.spin_limit = (t && t->spin_limit > 0) ? t->spin_limit : (1 << 17);
+    p.spin_limit = (t && t->spin_limit > 0) ? t->spin_limit : (1 << 14);
     p.max_chunks = (d->max_blocks_per_seq + p.chunk_blocks - 1) / p.chunk_blocks;
     if (p.max_chunks < 1) p.max_chunks = 1;
     p.force_bitonic = t ? t->force_bitonic : 0;
-    {
-        const long long items = (long long)d->batch * d->num_kv_heads * p.max_chunks;
-        p.select_grid = (int)(items < p.persistent_wgs ? items : p.persistent_wgs);
-    }
     p.depth_hint = t ? t->depth_hint : nullptr;
     p.events = t ? static_cast<hipEvent_t *>(t->phase_events) : nullptr;
     return p;
@@ -115,7 +110,7 @@ hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const Decode
     if (ev) (void)hipEventRecord(ev[1], st);
     if ((e = launch_order(kv, ws, G, plan, a.budget_blocks, a.order_out, st)) != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[2], st);
-    if ((e = launch_select(kv, d->dtype, G, a.q, ws, a.threshold, a.check_granularity, a.budget_blocks, plan, st)) != hipSuccess)
+    if ((e = launch_select(kv, d->dtype, G, a.q, ws, a.threshold, a.check_granularity, plan, st)) != hipSuccess)
         return e;
     if (ev) (void)hipEventRecord(ev[3], st);
     if ((e = launch_attend(kv, d->dtype, G, ws, plan, st)) != hipSuccess) return e;

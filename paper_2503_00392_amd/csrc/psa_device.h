@@ -35,23 +35,20 @@ struct KvView {
 // "Chunk" = `CB` consecutive ranked blocks: the unit in which keys are read and folded into the
 // stop rule, and in which values are read.
 //
-// Per-stream control block of the progressive kernel: four 128-byte lines, so that the ticket
-// counter, the progress word that idle workgroups poll, the bookkeeping counters and the fold's own
-// state never share a cache line (accesses to one line are served one after the other).
+// Per-stream control block of the progressive kernel: three 128-byte lines, so that the progress word
+// that waiting workgroups poll, the traffic counter and the fold's own state never share a cache line
+// (accesses to one line are served one after the other).
 struct alignas(128) StreamCtl {
-    // line 0: key tickets
-    int32_t k_next;     // next key chunk to hand out (fetch-and-add)
-    int32_t pad0[31];
-    // line 1: progress, written by the folding wave only, as ONE 64-bit store
+    // line 0: progress, written by the folding wave only, as ONE 64-bit store; polled by workgroups that
+    // wait for the read-ahead window
     unsigned long long key_progress;    // low: frontier = key chunks folded into the stop rule so far;
                                         // high: k_limit = key chunks worth reading (all of them, or what a
                                         // block budget covers, until the fold has finished; then what it used)
-    int32_t pad1[30];
-    // line 2: counters
+    int32_t pad0[30];
+    // line 1: counters
     int32_t k_blocks;   // key slices loaded (traffic accounting)
-    int32_t attached;   // workgroups working on this stream beyond its first ones (joiners)
-    int32_t pad2[30];
-    // line 3: fold state, owned by the folding wave
+    int32_t pad1[31];
+    // line 2: fold state, owned by the folding wave
     float Lacc[8];               // per head: log2 of AS_acc over the folded chunks
     float Lmin[8];               // per head: log2 of AS_min over the folded chunks
     unsigned long long stop[8];  // per head: (n << 32) | float bits of P_acc at the stop; ~0 = not stopped
@@ -77,11 +74,12 @@ struct DecodeWs {
 #endif
 };
 #ifdef PSA_ENABLE_TRACE
-constexpr int kTracePerWave = 256;
-constexpr int kTraceRecords = 4096 * kTracePerWave;   // up to 4096 waves
+constexpr int kTracePerWave = 32;                      // records per workgroup
+constexpr int kTraceWgs = 32768;                       // workgroups that keep records
+constexpr int kTraceRecords = kTraceWgs * kTracePerWave;
 #endif
 constexpr int kPartialStride = 132;  // M, l, pad, pad, acc[128]
-constexpr int kMaxWindowChunks = 256; // chunks handed out beyond the fold's frontier, at most
+constexpr int kMaxWindowChunks = 256; // chunks read beyond the fold's frontier, at most
 constexpr int kValueCount = 32;      // index of the value-item counter in the workspace header
 // A chunk word holds (L_chunk, Lmin_chunk) as two floats once the chunk is published.  Before that
 // it holds one of two NaN patterns no computation produces: "not published", or -- word 0 only --

@@ -46,8 +46,6 @@ struct DecodePlan {
     int window_chunks;
     int spin_limit;
     int max_chunks;
-    int persistent_wgs;   // workgroups of the progressive kernel's persistent grid, at most
-    int select_grid;      // ... and how many are launched (no more than there are chunks)
     int force_bitonic;
     const int32_t *depth_hint;   // NULL or [S] expected blocks per stream (device)
     hipEvent_t *events;   // NULL or 6 events recorded between the kernels
@@ -77,7 +75,7 @@ hipError_t launch_score(const KvView &kv, int dtype, int G, int scorer, const vo
 hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, const DecodePlan &plan, int budget_blocks,
                         int32_t *order_out, hipStream_t st);
 hipError_t launch_select(const KvView &kv, int dtype, int G, const void *q, const DecodeWs &ws, float eps,
-                         int m, int budget_blocks, const DecodePlan &plan, hipStream_t st);
+                         int m, const DecodePlan &plan, hipStream_t st);
 hipError_t launch_attend(const KvView &kv, int dtype, int G, const DecodeWs &ws, const DecodePlan &plan,
                          hipStream_t st);
 hipError_t launch_finalize(const KvView &kv, const DecodeWs &ws, int G, int VU, float *out,

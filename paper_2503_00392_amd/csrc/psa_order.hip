@@ -32,7 +32,7 @@ constexpr int kBucketLimit = 192;
 #ifdef PSA_ENABLE_TRACE
 // Tuning aid (not built by default): phase timestamps of workgroup 0, 100 MHz.
 #define PSA_ORDER_STAMP(K)                                                                     \
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) ws.trace[8 + ((size_t)4095 * kTracePerWave + (K)) * 4 + 2] = wall_clock64();
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) ws.trace[8 + ((size_t)(kTraceWgs - 1) * kTracePerWave + (K)) * 4 + 2] = wall_clock64();
 #else
 #define PSA_ORDER_STAMP(K)
 #endif
@@ -107,8 +107,7 @@ __device__ void bitonic_sort(unsigned long long (&e)[8], unsigned long long *lds
     }
 }
 
-__global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int G, int KU, int budget_blocks,
-                                                     int select_grid, int window, const int32_t *depth_hint, int Np,
+__global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int G, int KU, int budget_blocks, int Np,
                                                       int force_bitonic,
                                                       int32_t *__restrict__ order_out) {
     extern __shared__ unsigned long long lds_raw[];
@@ -140,13 +139,7 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         // key chunks that may ever be handed out: all of them, or those a fixed budget of blocks covers
         const int nlim = budget_blocks > 0 ? min(N, budget_blocks) : N;
         const unsigned nch = (unsigned)((nlim + KU - 1) / KU);
-        // the selection kernel's workgroup b starts on stream b mod S with chunk b / S, without asking:
-        // those first chunks count as handed out
-        const int S = gridDim.y;
-        const int starters = s < select_grid ? (select_grid - s + S - 1) / S : 0;
-        const int hinted = hinted_chunks(depth_hint, s, N, KU);
-        c->k_next = min(min(starters, hinted > 0 ? hinted + 1 : window), (int)nch);
-        c->k_blocks = 0; c->attached = 0;
+        c->k_blocks = 0;
         c->key_progress = (unsigned long long)nch << 32;                                  // frontier 0
         for (int g = 0; g < 8; ++g) { c->Lacc[g] = -INFINITY; c->Lmin[g] = INFINITY; c->stop[g] = ~0ull; }
     }
@@ -344,9 +337,8 @@ hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, const Decod
     int parts = 256 / (S > 0 ? S : 1);
     parts = parts < 1 ? 1 : (parts > 4 ? 4 : parts);
     if (Np < 2048) parts = 1;
-    order_kernel<<<dim3(parts, S), Np / 8, lds, st>>>(kv, ws, G, plan.chunk_blocks, budget_blocks, plan.select_grid,
-                                                      plan.window_chunks < kMaxWindowChunks ? plan.window_chunks : kMaxWindowChunks,
-                                                      plan.depth_hint, Np, plan.force_bitonic, order_out);
+    order_kernel<<<dim3(parts, S), Np / 8, lds, st>>>(kv, ws, G, plan.chunk_blocks, budget_blocks, Np, plan.force_bitonic,
+                                                      order_out);
     return hipGetLastError();
 }
 

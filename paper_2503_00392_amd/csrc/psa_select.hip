@@ -5,37 +5,41 @@
 // Terms.  "Stream": one (request, KV head) pair -- one ranking, G query heads.  "Chunk": CB
 // consecutive ranked blocks, the unit of work of a workgroup.
 //
-// A persistent grid of workgroups (8 waves each).  A workgroup attached to a stream repeats:
-//   1. take the stream's next chunk ticket (fetch-and-add), fetch the chunk's page numbers, then wait
-//      until the chunk is inside the read-ahead window -- chunks read beyond the fold's frontier are at
-//      most max(window, frontier/2), 256 at most, which bounds the keys read beyond the stop -- or
-//      drop the ticket if the stream closes first;
-//   2. read the chunk's key slices (each wave keeps 4 slices = 16 KiB in flight), compute the
+// One workgroup (4 waves) per (chunk, stream), in a one-dimensional grid with the streams varying
+// fastest: the hardware hands workgroups out in that order, so each stream's chunks start in rank
+// order, interleaved over the streams, and a compute unit takes the next one the moment a slot is free
+// (four fit).  A workgroup
+//   1. returns at once if its chunk lies beyond the stream's blocks or the stream is closed;
+//   2. fetches the chunk's page numbers and waits (napping about a microsecond between looks at one
+//      progress word, a bounded number of times) until the chunk is inside the read-ahead window --
+//      chunks read beyond the fold's frontier are at most max(window, frontier/2), 256 at most, which
+//      bounds the keys read beyond the stop -- or the stream closes before it;
+//   3. reads the chunk's key slices (each wave keeps 4 slices = 16 KiB in flight), computes the
 //      scaled logits of all G heads as a 16-token x 16-head x 128-channel product on the matrix
-//      cores (heads beyond G are zero columns), store them for the value pass, and reduce each
+//      cores (heads beyond G are zero columns), stores them for the value pass, and reduces each
 //      block's log-sum-exp L_b (= log AS of line 10);
-//   3. publish the chunk's (log-sum-exp, minimum) of L_b per head as one 64-bit word per head.
+//   4. publishes the chunk's (log-sum-exp, minimum) of L_b per head as one 64-bit word per head.
+// The wait of step 2 is a courtesy, not a dependency: no workgroup needs another one to proceed
+// (when the polls run out it simply reads its chunk), so the grid drains whatever order it runs in.
 // THE FOLD applies lines 12-17 strictly in rank order: AS_acc, AS_min, N_left and P_acc at the end
 // of each published chunk after the frontier and, in the first chunk where P_acc exceeds the
 // threshold, with a prefix scan over the chunk's blocks to find the head's exact stop.  It is a
-// token: exactly one wave at a time folds.  When it reaches a chunk that is not yet published it marks that chunk's word "the
-// fold waits here" and its workgroup goes back to key work; the workgroup that later publishes over
-// the mark (an atomic exchange tells it) picks the fold up from the state left in the control
-// block.  So no workgroup ever waits for another one, nobody polls for the fold, nothing is locked.
-// Once every head has stopped (or the blocks ran out) the fold closes the stream: tickets beyond
-// what it used are dropped.  A workgroup whose stream has handed out all its chunks joins another
-// stream that still has some (a bounded number of joiners per stream), or leaves.
+// token: exactly one wave at a time folds.  When it reaches a chunk that is not yet published it
+// marks that chunk's word "the fold waits here" and returns; the workgroup that later publishes
+// over the mark (an atomic exchange tells it) picks the fold up from the state left in the control
+// block.  So nobody polls for the fold and nothing is locked.  Once every head has stopped (or the
+// blocks ran out) the fold closes the stream: the chunks beyond what it used are never read.
 //
 // Communication between workgroups: every shared word is read and written with relaxed agent-scope
 // atomics (coherent accesses); a writer waits for its data stores to complete before it stores the
-// word that announces them (chunk word 0, the progress words, the fold mark), and a reader looks at
+// word that announces them (chunk word 0, the progress word, the fold mark), and a reader looks at
 // the announcing word before it issues the loads that depend on it.  Accesses to one cache line are
 // served one at a time (tens of nanoseconds each), which is why one thread per workgroup touches the
-// stream's control block about once per chunk and the fold hand-over goes through the chunks' own
-// words.  The logits are plain stores: their reader is the next kernel.
+// stream's control block and the fold hand-over goes through the chunks' own words.  The logits
+// are plain stores: their reader is the next kernel.
 //
-// Every fold is sequential in rank order and every reduction has a fixed shape, so results are
-// bitwise reproducible although the scheduling is dynamic.
+// The fold is one scan in rank order and every reduction has a fixed shape, so results are bitwise
+// reproducible although the scheduling is dynamic.
 #include <limits.h>
 
 #include "psa_host.h"
@@ -81,7 +85,7 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
 // Tuning aid (not built by default): every workgroup keeps its own list of records (kind, stream,
 // index, begin, end; 100 MHz timestamps), so tracing adds no shared traffic.
 #define PSA_TRACE(KIND, S, IDX, T0)                                                            \
-    if (threadIdx.x == 0 && trace_n < kTracePerWave) {                                         \
+    if (threadIdx.x == 0 && trace_n < kTracePerWave && blockIdx.x < kTraceWgs) {                                         \
         unsigned long long *rec_ = ws.trace + 8 + ((size_t)blockIdx.x * kTracePerWave + trace_n) * 4; \
         rec_[0] = ((unsigned long long)(KIND) << 56) | ((unsigned long long)(S) << 32) | (unsigned)(IDX); \
         rec_[1] = (unsigned long long)blockIdx.x;                                              \
@@ -94,7 +98,7 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
 #define PSA_FOLD_ARGS , unsigned long long *fold_t, int *fold_n
 #define PSA_FOLD_PASS , sh.fold_stamp, &sh.fold_stamps
 #define PSA_TRACE_SPAN(KIND, S, IDX, T0, T1)                                                   \
-    if (threadIdx.x == 0 && trace_n < kTracePerWave) {                                         \
+    if (threadIdx.x == 0 && trace_n < kTracePerWave && blockIdx.x < kTraceWgs) {                                         \
         unsigned long long *rec_ = ws.trace + 8 + ((size_t)blockIdx.x * kTracePerWave + trace_n) * 4; \
         rec_[0] = ((unsigned long long)(KIND) << 56) | ((unsigned long long)(S) << 32) | (unsigned)(IDX); \
         rec_[1] = (unsigned long long)blockIdx.x;                                              \
@@ -112,8 +116,7 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
 #endif
 
 constexpr int kBatch = 4;            // key slices a wave keeps in flight
-constexpr int kSelectThreads = 512;  // 8 waves: a 32-block chunk is one batch per wave
-constexpr int kMaxJoiners = 32;      // workgroups that may join a stream beyond its first ones
+constexpr int kSelectThreads = 256;  // 4 waves; four such workgroups fit a CU (register budget)
 
 // Tokens of stream s's request, clamped like everywhere else.
 __device__ __forceinline__ int stream_ctx(const KvView &kv, int s) {
@@ -144,10 +147,7 @@ struct SelectShared {
     float Lb[kMaxChunkBlocks][G];          // per-block log2-sum-exp2
     int page[kMaxChunkBlocks];
     int valid[kMaxChunkBlocks];
-    int what;                              // 0: chunk `item`; 3: all handed out; 4: give up
-    int item;
-    int go;                                // after the wait for the window: 1 = read the chunk, 0 = dropped, 2 = gave up
-    int next;                              // stream to join, -1 = leave
+    int go;                                // after the wait for the window: 1 = read the chunk, 0 = the stream closed
 #ifdef PSA_ENABLE_TRACE
     unsigned long long stamp[8];
     unsigned long long fold_stamp[16];
@@ -457,160 +457,71 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
 }
 
 // =================================================================================================
-// The persistent scheduler.  grid = two workgroups per CU; 512 threads.  Thread 0 decides what the
-// workgroup does next and tells the others through LDS.
+// grid = S * max_chunks workgroups, streams fastest; 256 threads.
 // =================================================================================================
 template <int DT, int G>
 __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, const uint8_t *__restrict__ q,
                                                                 DecodeWs ws, float eps, int m, int CB,
-                                                                int window, int spin_limit, int budget_blocks,
+                                                                int window, int spin_limit,
                                                                 const int32_t *depth_hint) {
     __shared__ SelectShared<G> sh;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = kv.batch * kv.num_kv_heads;
-    int home = blockIdx.x % S;
-    bool joined = false, starting = true;
+    const int s = blockIdx.x % S, c = blockIdx.x / S;
+    const int N = (stream_ctx(kv, s) + kPage - 1) / kPage;
+    if (c * CB >= N) return;
     [[maybe_unused]] int trace_n = 0;
-    PSA_TRACE(5, home, 0, PSA_NOW());
-    while (true) {
-        StreamCtl *ctl = &ws.ctl[home];
-        const int N = (stream_ctx(kv, home) + kPage - 1) / kPage;
-        int k_loaded = 0;
-        load_queries<G>(sh, kv, q, home);
-        const int hinted = hinted_chunks(depth_hint, home, N, CB);     // inside the window whatever the frontier
-        while (true) {
-            [[maybe_unused]] const unsigned long long td = PSA_NOW();
-            if (tid == 0) {
-                int what = 3, item = -1;
-                if (starting) {
-                    // the first chunk needs no ticket: workgroup b takes chunk b / S of stream b mod S (the
-                    // ranking kernel has counted these as handed out)
-                    const int first = blockIdx.x / S;
-                    const int nlim = budget_blocks > 0 ? min(N, budget_blocks) : N;
-                    if (first < (hinted > 0 ? hinted + 1 : window_of(window, 0)) && first * CB < nlim) { what = 0; item = first; }
-                }
-                if (what != 0) {
-                    // a ticket, taken whether or not the read-ahead window reaches it yet: the wait for the
-                    // window comes afterwards, with the chunk's page numbers already on their way
-                    // (a ticket beyond the limit means the stream has none left; the counter then simply
-                    // runs ahead of the limit, which reads as "nothing to hand out" everywhere)
-                    const unsigned long long kp = ld_relaxed(&ctl->key_progress);
-                    item = atomicAdd(&ctl->k_next, 1);
-                    if (item < (int)(kp >> 32)) what = 0;
-                }
-                sh.what = what;
-                sh.item = item;
-            }
-            lds_barrier();
-            const bool started = starting;
-            starting = false;
-            const int what = sh.what, item = sh.item;
-            PSA_TRACE(9, home, what, td);
-            if (what != 0) break;                      // the stream has no chunk left to hand out
-            stage_pages<G>(sh, kv, ws, CB, home, item);
-            if (tid == 0) {
-                // chunks handed out beyond the fold's frontier are at most the window: wait until this one is
-                // inside it, or the stream closes before it (then the ticket is dropped)
-                int go = 1;
-                if (!started) {
-                    [[maybe_unused]] const unsigned long long t0 = PSA_NOW();
-                    for (int tries = 0;; ++tries) {
-                        const unsigned long long kp = ld_relaxed(&ctl->key_progress);
-                        const int fr = (int)(kp & 0xffffffffull), lim = (int)(kp >> 32);
-                        if (item >= lim) { go = 0; break; }
-                        // with a hint: everything up to it (and a chunk more) at once; past it, a window that
-                        // starts small and doubles with the distance the hint fell short by
-                        const int reach = hinted > 0 ? max(hinted + 1, fr + min(max(4, 2 * (fr - hinted)), window_of(window, fr)))
-                                                     : fr + window_of(window, fr);
-                        if (item < reach) break;
-                        if (tries >= spin_limit) { go = 2; break; }
-                        nap(tries);
-                    }
-                    PSA_TRACE(4, home, item, t0);
-                }
-                sh.go = go;
-            }
-            lds_barrier();
-            const int go = sh.go;
-            if (go == 1) {
-                [[maybe_unused]] const unsigned long long t0 = PSA_NOW();
-                process_chunk<DT, G>(sh, kv, q, ws, eps, m, CB, home, item);
-                PSA_TRACE(1, home, item, t0);
-                PSA_TRACE_SPAN(10, home, item, t0, sh.stamp[0]);             // queries loaded
-                PSA_TRACE_SPAN(11, home, item, sh.stamp[0], sh.stamp[1]);    // keys loaded, logits computed (wave 0)
-                PSA_TRACE_SPAN(12, home, item, sh.stamp[1], sh.stamp[2]);    // the other waves
-                PSA_TRACE_SPAN(13, home, item, sh.stamp[2], sh.stamp[3]);    // stores complete
-                PSA_TRACE_SPAN(14, home, item, sh.stamp[3], sh.stamp[4]);    // published
-                PSA_TRACE_SPAN(15, home, item, sh.stamp[4], sh.stamp[5]);    // fold, if it was this chunk's turn
-#ifdef PSA_ENABLE_TRACE
-                if (tid == 0)
-                    for (int fj = 0; fj < sh.fold_stamps; ++fj) { PSA_TRACE_SPAN(20 + fj, home, item, sh.stamp[4], sh.fold_stamp[fj]); }
-#endif
-                k_loaded += min(CB, N - item * CB);
-            } else if (go == 2) {
-                if (tid == 0) sh.what = 4;
-                lds_barrier();
-                break;
-            }
-            lds_barrier();      // everyone has read sh.what before thread 0 decides again
+    [[maybe_unused]] const unsigned long long t_begin = PSA_NOW();
+    load_queries<G>(sh, kv, q, s);
+    stage_pages<G>(sh, kv, ws, CB, s, c);
+    if (threadIdx.x == 0) {
+        // chunks read beyond the fold's frontier are at most the window: wait until this one is inside
+        // it, or the stream closes before it.  With a hint: everything up to it (and a chunk more) at
+        // once; past it, a window that starts small and doubles with the distance the hint fell short by.
+        const int hinted = hinted_chunks(depth_hint, s, N, CB);
+        int go = 1;
+        for (int tries = 0;; ++tries) {
+            const unsigned long long kp = ld_relaxed(&ws.ctl[s].key_progress);
+            const int fr = (int)(kp & 0xffffffffull), lim = (int)(kp >> 32);
+            if (c >= lim) { go = 0; break; }       // closed, or a block budget ends before this chunk
+            const int reach = hinted > 0 ? max(hinted + 1, fr + min(max(4, 2 * (fr - hinted)), window_of(window, fr)))
+                                         : fr + window_of(window, fr);
+            if (c < reach || tries >= spin_limit) break;
+            nap(tries);
         }
-        lds_barrier();
-        if (tid == 0) {
-            if (k_loaded) atomicAdd(&ctl->k_blocks, k_loaded);
-            if (joined) atomicAdd(&ctl->attached, -1);
-            if (sh.what == 4) set_error(ws.header, PSA_DEVERR_WAIT_EXPIRED);
-        }
-        if (sh.what == 4) break;
-        // ---- the stream has handed out all its chunks: join one that has some and room, or leave ---------------
-        if (wave == 0) {
-            int next = -1;
-            const int off0 = 1 + (int)((blockIdx.x * 40503u) % (unsigned)S);     // where this workgroup starts looking
-            for (int b0 = 0; b0 < S && next < 0; b0 += 64) {
-                int open = 0, cand = 0;
-                if (b0 + lane < S) {
-                    cand = (home + off0 + b0 + lane) % S;
-                    const StreamCtl *o = &ws.ctl[cand];
-                    open = ld_relaxed(&o->k_next) < (int)(ld_relaxed(&o->key_progress) >> 32) &&
-                           ld_relaxed(&o->attached) < kMaxJoiners;
-                }
-                unsigned long long mask = __ballot(open);
-                while (mask && next < 0) {
-                    const int src = __ffsll((long long)mask) - 1;
-                    const int c2 = __shfl(cand, src);
-                    int ok = 0;
-                    if (lane == 0) {
-                        ok = atomicAdd(&ws.ctl[c2].attached, 1) < kMaxJoiners;
-                        if (!ok) atomicAdd(&ws.ctl[c2].attached, -1);
-                    }
-                    if (uniform(ok)) next = c2;
-                    mask &= mask - 1;
-                }
-            }
-            if (lane == 0) sh.next = next;
-        }
-        lds_barrier();
-        const int next = sh.next;
-        lds_barrier();
-        if (next < 0) break;
-        PSA_TRACE(6, next, home, PSA_NOW());
-        home = next;
-        joined = true;
+        sh.go = go;
     }
+    lds_barrier();
+    PSA_TRACE(4, s, c, t_begin);
+    if (!sh.go) return;
+    if (threadIdx.x == 0) atomicAdd(&ws.ctl[s].k_blocks, min(CB, N - c * CB));     // traffic accounting
+    [[maybe_unused]] const unsigned long long t0 = PSA_NOW();
+    process_chunk<DT, G>(sh, kv, q, ws, eps, m, CB, s, c);
+    PSA_TRACE(1, s, c, t0);
+    PSA_TRACE_SPAN(10, s, c, t0, sh.stamp[0]);             // queries in registers
+    PSA_TRACE_SPAN(11, s, c, sh.stamp[0], sh.stamp[1]);    // keys loaded, logits computed (wave 0)
+    PSA_TRACE_SPAN(12, s, c, sh.stamp[1], sh.stamp[2]);    // the other waves
+    PSA_TRACE_SPAN(13, s, c, sh.stamp[2], sh.stamp[3]);    // stores complete
+    PSA_TRACE_SPAN(14, s, c, sh.stamp[3], sh.stamp[4]);    // published
+    PSA_TRACE_SPAN(15, s, c, sh.stamp[4], sh.stamp[5]);    // fold, if it was this chunk's turn
+#ifdef PSA_ENABLE_TRACE
+    if (threadIdx.x == 0)
+        for (int fj = 0; fj < sh.fold_stamps; ++fj) { PSA_TRACE_SPAN(20 + fj, s, c, sh.stamp[4], sh.fold_stamp[fj]); }
+#endif
 }
 
 template <int DT, int G>
 static hipError_t launch_select_t(const KvView &kv, const void *q, const DecodeWs &ws, float eps, int m,
-                                  int budget_blocks, const DecodePlan &plan, hipStream_t st) {
-    const unsigned grid = (unsigned)plan.select_grid;
+                                  const DecodePlan &plan, hipStream_t st) {
+    const unsigned grid = (unsigned)(kv.batch * kv.num_kv_heads) * (unsigned)plan.max_chunks;
     select_kernel<DT, G><<<grid, kSelectThreads, 0, st>>>(kv, (const uint8_t *)q, ws, eps, m, plan.chunk_blocks,
-                                               plan.window_chunks, plan.spin_limit, budget_blocks, plan.depth_hint);
+                                               plan.window_chunks, plan.spin_limit, plan.depth_hint);
     return hipGetLastError();
 }
 
 hipError_t launch_select(const KvView &kv, int dtype, int G, const void *q, const DecodeWs &ws, float eps,
-                         int m, int budget_blocks, const DecodePlan &plan, hipStream_t st) {
+                         int m, const DecodePlan &plan, hipStream_t st) {
 #define PSA_CASE(DT, GG) \
-    if (dtype == DT && G == GG) return launch_select_t<DT, GG>(kv, q, ws, eps, m, budget_blocks, plan, st);
+    if (dtype == DT && G == GG) return launch_select_t<DT, GG>(kv, q, ws, eps, m, plan, st);
     PSA_CASE(0, 1) PSA_CASE(0, 2) PSA_CASE(0, 4) PSA_CASE(0, 8)
     PSA_CASE(1, 1) PSA_CASE(1, 2) PSA_CASE(1, 4) PSA_CASE(1, 8)
 #undef PSA_CASE

@@ -102,13 +102,13 @@ def test_decode_rejects_bad_scalars_and_null_buffers(lib):
     for name in ("q", "meta", "out", "nsel", "mass", "ws"):
         assert _decode(lib, d, **{name: None}) == 1, name
     assert _decode(lib, d, ws_bytes=1024) == 3
-    T = pb._Tuning        # chunk_blocks, window_chunks, spin_limit, force_bitonic, workgroups, depth_hint, events
-    assert _decode(lib, d, tuning=T(7, 0, 0, 0, 0, None, None)) == 1       # too small
-    assert _decode(lib, d, tuning=T(10, 0, 0, 0, 0, None, None)) == 1      # not a multiple of 4
-    assert _decode(lib, d, tuning=T(68, 0, 0, 0, 0, None, None)) == 1      # too large
-    assert _decode(lib, d, tuning=T(0, -1, 0, 0, 0, None, None)) == 1
-    assert _decode(lib, d, tuning=T(0, 0, 0, 2, 0, None, None)) == 1
-    assert _decode(lib, d, tuning=T(0, 0, 0, 0, -3, None, None)) == 1
+    T = pb._Tuning        # chunk_blocks, window_chunks, spin_limit, force_bitonic, depth_hint, events
+    assert _decode(lib, d, tuning=T(7, 0, 0, 0, None, None)) == 1       # too small
+    assert _decode(lib, d, tuning=T(10, 0, 0, 0, None, None)) == 1      # not a multiple of 4
+    assert _decode(lib, d, tuning=T(68, 0, 0, 0, None, None)) == 1      # too large
+    assert _decode(lib, d, tuning=T(0, -1, 0, 0, None, None)) == 1
+    assert _decode(lib, d, tuning=T(0, 0, 0, 2, None, None)) == 1
+    assert _decode(lib, d, tuning=T(0, 0, -1, 0, None, None)) == 1
     assert lib.psa_decode_attention(None, 1, 1, 0.5, 1, 0, 1, 1, 1, None, None, None, None, None, None, 1,
                                     1 << 30, None) == 1
     assert lib.psa_topk_attention(C.byref(d), 0x10, 0x20, 0, 0, 0x30, 0x40, 0x50, None, None, None, None, None,

@@ -106,14 +106,14 @@ def test_threshold_zero_takes_one_microbatch(psa, case):
         assert gc.rel_l2(gpu.out.cpu().numpy().astype(np.float64), own).max() <= gc.OUT_RTOL
 
 
-@pytest.mark.parametrize("chunk,window,wgs", [(8, 1, 0), (16, 3, 7), (64, 2, 0), (32, 64, 0), (12, 1, 1)])
-def test_result_does_not_depend_on_tuning(psa, case, chunk, window, wgs):
-    """Chunk size, read-ahead window and grid size change traffic and scheduling, not the selection:
+@pytest.mark.parametrize("chunk,window,spin", [(8, 1, 0), (16, 3, 0), (64, 2, 0), (32, 64, 0), (12, 1, 1)])
+def test_result_does_not_depend_on_tuning(psa, case, chunk, window, spin):
+    """Chunk size, read-ahead window and the patience of waiting workgroups change traffic and scheduling, not the selection:
     the selected sets are identical and outputs agree to rounding."""
     name, cfg, li, pb = case
     eps = cfg.threshold
     base = gc.run_gpu_decode(li, eps, 1)
-    alt = gc.run_gpu_decode(li, eps, 1, tuning=psa.Tuning(chunk_blocks=chunk, window_chunks=window, workgroups=wgs))
+    alt = gc.run_gpu_decode(li, eps, 1, tuning=psa.Tuning(chunk_blocks=chunk, window_chunks=window, spin_limit=spin))
     assert torch.equal(base.order, alt.order)
     rep = gc.check_decode_against_oracle(pb, alt, eps, 1)
     same = (base.n_selected == alt.n_selected)
