@@ -91,6 +91,7 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-topk-comparison", action="store_true")
     ap.add_argument("--no-scorer-comparison", action="store_true")
+    ap.add_argument("--no-depth-hint", action="store_true")
     ap.add_argument("--cpu-layers", type=str, default="", help="layers the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -206,20 +207,22 @@ def main():
     # ---- the same step with a depth hint per (request, KV head): the blocks the previous step read.  The
     # steps of this benchmark are identical, so the hint is exact -- the upper bound of what the similarity
     # of consecutive decode queries can give; `value` above is measured without any hint. ------------------
-    hints = [o.blocks_read.clone() for o in outs]
-    hinted_tun = [psa.Tuning(depth_hint=hints[i], **tuning_kw) for i in range(L)]
-    step(hinted_tun)
-    torch.cuda.synchronize()
-    e0.record()
-    for _ in range(args.steps):
+    hinted = None
+    if not args.no_depth_hint:
+        hints = [o.blocks_read.clone() for o in outs]
+        hinted_tun = [psa.Tuning(depth_hint=hints[i], **tuning_kw) for i in range(L)]
         step(hinted_tun)
-    e1.record()
-    torch.cuda.synchronize()
-    hint_ms = e0.elapsed_time(e1) / args.steps
-    hint_same = all(torch.equal(o.blocks_read, h) for o, h in zip(outs, hints))
-    hinted = {"ms_per_step": hint_ms, "query_heads_per_s": q_heads_per_step / (hint_ms * 1e-3),
-              "same_selection_as_without_hint": bool(hint_same),
-              "hint": "blocks_read of an identical previous step (exact: an upper bound for real decode loops)"}
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            step(hinted_tun)
+        e1.record()
+        torch.cuda.synchronize()
+        hint_ms = e0.elapsed_time(e1) / args.steps
+        hint_same = all(torch.equal(o.blocks_read, h) for o, h in zip(outs, hints))
+        hinted = {"ms_per_step": hint_ms, "query_heads_per_s": q_heads_per_step / (hint_ms * 1e-3),
+                  "same_selection_as_without_hint": bool(hint_same),
+                  "hint": "blocks_read of an identical previous step (exact: an upper bound for real decode loops)"}
 
     # ---- per-kernel durations, live, with HIP events recorded by the library around its kernels ----
     hev = HipEvents()
