@@ -92,6 +92,9 @@ def main():
     ap.add_argument("--no-topk-comparison", action="store_true")
     ap.add_argument("--no-scorer-comparison", action="store_true")
     ap.add_argument("--no-depth-hint", action="store_true")
+    ap.add_argument("--decode-loop", type=int, default=0,
+                    help="also run this many consecutive decode steps (append a token, drift the queries), with and "
+                         "without the previous step's blocks_read as depth hint")
     ap.add_argument("--cpu-layers", type=str, default="", help="layers the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -396,6 +399,49 @@ def main():
                "sample": f"config {cfg.index}, layers {sample}, requests {reqs}, all {Hq} query heads, "
                          f"scoring+ranking+progressive loop in fp64 ({t_cpu:.1f}s of CPU time)"}
 
+    # ---- consecutive decode steps: every step appends one token per request to every layer's cache
+    # (K, V, metadata, length: psa_append_kv) and decodes with queries that drifted a little; the depth
+    # hint of a step is what the same layer read in the step before -------------------------------------
+    loop = None
+    if args.decode_loop > 0:
+        from workloads import step_inputs
+        n_steps = args.decode_loop
+        # room for the appended tokens: the loop starts from contexts cut back by whole pages (at 128K the
+        # block table is full), and refills those pages -- in place, this is the last leg of the run
+        cut = 16 * ((n_steps + 15) // 16)
+        roomy, kvs2, metas2, ws2 = layers, kvs, metas, ws
+        inputs = [[step_inputs(roomy[i], t) for i in range(L)] for t in range(1, n_steps + 1)]
+        ctx0 = [torch.clamp(li.ctx_lens - cut, min=0) for li in roomy]
+        louts = [psa.DecodeOutput(torch.empty((B, Hq, 128), dtype=torch.float32, device=dev),
+                                  torch.empty((B, Hq), dtype=torch.int32, device=dev),
+                                  torch.empty((B, Hq), dtype=torch.float32, device=dev),
+                                  torch.empty((B, H), dtype=torch.int32, device=dev),
+                                  torch.empty((B, Hq), dtype=torch.float32, device=dev), None, None, None) for _ in range(L)]
+        loop = {"steps": n_steps}
+        for mode in ("without_hint", "with_previous_step_hint"):
+            for i in range(L):
+                roomy[i].ctx_lens.copy_(ctx0[i])
+            prev = [None] * L
+            read = []
+            torch.cuda.synchronize()
+            e0.record()
+            for t in range(n_steps):
+                for i in range(L):
+                    qt, kt, vt = inputs[t][i]
+                    psa.append_kv(kvs2[i], kt, vt, metas2[i])
+                    tn = psa.Tuning(depth_hint=prev[i], **tuning_kw) if (mode != "without_hint" and prev[i] is not None) else tun
+                    psa.decode_attention(kvs2[i], qt, metas2[i], eps, m, workspace=ws2, outputs=louts[i], tuning=tn,
+                                         scorer=args.scorer)
+                    if mode != "without_hint":
+                        prev[i] = louts[i].blocks_read.clone()
+                if t == n_steps - 1:
+                    read = [o.blocks_read.double().mean().item() for o in louts]
+            e1.record()
+            torch.cuda.synchronize()
+            assert psa.read_device_error(ws2) == 0
+            loop[mode] = {"ms_per_step": e0.elapsed_time(e1) / n_steps, "blocks_read_per_stream_mean_last_step": float(np.mean(read))}
+        log(f"[bench] decode loop: {loop}")
+
     traffic = read_measured_traffic(cfg.name, dom)
 
     result = {
@@ -418,6 +464,7 @@ def main():
                        "phase_avg_ms_per_layer": phase_avg,
                        "kernel_GBps": kern_gbs},
         "with_depth_hint": hinted,
+        "decode_loop": loop,
         "dense_control": dense,
         "topk_control": topk,
         "scorer_comparison": scorers,
