@@ -143,7 +143,7 @@ __device__ __forceinline__ void nap(int tries) {
 
 template <int G>
 struct SelectShared {
-    uint4 qb[4][64];                       // B operand of the QK^T product for the attached stream, by lane
+    uint4 qb[4][64];                       // B operand of the QK^T product of the workgroup's stream, by lane
     float Lb[kMaxChunkBlocks][G];          // per-block log2-sum-exp2
     int page[kMaxChunkBlocks];
     int valid[kMaxChunkBlocks];
@@ -309,12 +309,8 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
     for (int i = lane; i < units; i += 64) ws.value_items[base + i] = s * ws.max_chunks + i;
 }
 
-// =================================================================================================
-// Key work of one workgroup: chunk c of stream s.  Ends with the chunk published; wave 0 carries
-// the fold on if it was waiting for this chunk.
-// =================================================================================================
-// Physical page and valid-token count of each ranked block of chunk c of stream s -> LDS.  Issued as soon
-// as the workgroup holds the chunk's ticket, so that the loads overlap its wait for the window.
+// Physical page and valid-token count of each ranked block of chunk c of stream s -> LDS.  Issued before
+// the workgroup looks at the window, so that the loads overlap its wait.
 template <int G>
 __device__ __forceinline__ void stage_pages(SelectShared<G> &sh, const KvView &kv, const DecodeWs &ws, int CB,
                                             int s, int c) {
@@ -329,7 +325,7 @@ __device__ __forceinline__ void stage_pages(SelectShared<G> &sh, const KvView &k
     }
 }
 
-// B operand of the QK^T product of stream s -> LDS, once per stream a workgroup attaches to: column
+// B operand of the QK^T product of stream s -> LDS (every wave of the workgroup reads it from there): column
 // n = lane%16 is query head n (zero beyond the group), k block kq = lane/16; for step kk the lane holds
 // channels 8*(4*kk + kq) .. +7.  (The caller's next barrier makes it visible.)
 template <int G>
@@ -345,6 +341,10 @@ __device__ __forceinline__ void load_queries(SelectShared<G> &sh, const KvView &
     }
 }
 
+// =================================================================================================
+// Key work of one workgroup: chunk c of stream s.  Ends with the chunk published; wave 0 carries
+// the fold on if it was waiting for this chunk.
+// =================================================================================================
 template <int DT, int G>
 __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8_t *__restrict__ q,
                               const DecodeWs &ws, float eps, int m, int CB, int s, int c) {
