@@ -21,7 +21,11 @@
  *                               2-4 and 7-19; Sec. 3.2 prose on the microbatch size m and on the
  *                               batched form where every query stops on its own).
  *   oracle_attend_prefix        softmax attention restricted to the first n ranked blocks, by the
- *                               definition (used to check the merge of Algorithm 1, line 11).
+ *                               definition (used to check the merge of Algorithm 1, line 11, and as
+ *                               the fixed top-k control of Sec. 1 / Sec. 2.2), with the log of its
+ *                               denominator.
+ * The Python side (psa_oracle.py) adds, in numpy: topk_attention (ranking + oracle_attend_prefix) and
+ * append_kv (the cache after one more token per request, Sec. 3.1).
  *
  * Readings of points the paper leaves open are listed where they are used; they are the same list
  * the repository's design document carries.
@@ -33,7 +37,8 @@
  * three-block case stored under tests/golden.
  * Parity unpinned (no passage or closed form fixes them; they are this build's readings): the max
  * reduce over a GQA group, the treatment of a partly filled last block, the order of -0 and +0 in
- * the metadata.
+ * the metadata, and the cuboid-centre scorer as a reading of the "cuboid-mean" metadata the paper
+ * names without defining (its arithmetic is pinned; that it is what the paper means is not).
  *
  * Storage formats: K, V, Q and metadata are IEEE binary16 ("f16", dtype 0) or bfloat16 (dtype 1),
  * passed as raw uint16_t and decoded exactly to double here.
