@@ -81,8 +81,8 @@ typedef struct {
 typedef struct {
     int32_t chunk_blocks;   /* ranked blocks per work item: a multiple of 4 in 8..64 (default 32)      */
     int32_t window_chunks;  /* least number of chunks of one (request, KV head) read beyond the chunks
-                               already folded into the stop rule; the window grows to half the folded
-                               count, at most 256 (default: from the number of streams)               */
+                               already folded into the stop rule; the window grows to a quarter of the
+                               folded count, at most 256 (default: from the number of streams)               */
     int32_t spin_limit;     /* looks (about a microsecond apart) a workgroup takes at the window before it
                                reads its chunk regardless (default 1<<14); the wait only limits read-ahead  */
     int32_t force_bitonic;  /* 1: always rank with the bitonic network (testing); 0: automatic        */

@@ -12,7 +12,7 @@
 //   1. returns at once if its chunk lies beyond the stream's blocks or the stream is closed;
 //   2. fetches the chunk's page numbers and waits (napping about a microsecond between looks at one
 //      progress word, a bounded number of times) until the chunk is inside the read-ahead window --
-//      chunks read beyond the fold's frontier are at most max(window, frontier/2), 256 at most, which
+//      chunks read beyond the fold's frontier are at most max(window, frontier/4), 256 at most, which
 //      bounds the keys read beyond the stop -- or the stream closes before it;
 //   3. reads the chunk's key slices (each wave keeps 4 slices = 16 KiB in flight), computes the
 //      scaled logits of all G heads as a 16-token x 16-head x 128-channel product on the matrix
@@ -125,7 +125,7 @@ __device__ __forceinline__ int stream_ctx(const KvView &kv, int s) {
 }
 
 __device__ __forceinline__ int window_of(int window, int frontier) {
-    const int w = max(window, frontier >> 1);
+    const int w = max(window, frontier >> 2);
     return w > kMaxWindowChunks ? kMaxWindowChunks : w;
 }
 
