@@ -198,6 +198,19 @@ psa_status psa_dense_attention(const psa_kv_desc *desc, const void *q, float *ou
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Measurement aid, not a step of the method: one plain kernel reads `bytes` (rounded down to a
+ * multiple of 16) of device memory at `src` once, front to back, and keeps nothing.  Timed by the
+ * caller over a buffer much larger than the last-level cache it gives the streaming-read rate the
+ * memory system delivers in practice, the ceiling the decode path's rates are quoted against
+ * beside the published peak.
+ *   src   device pointer, 16-byte aligned; read only
+ *   sink  device pointer to 8 writable bytes, 8-byte aligned, or NULL; practically never written
+ *         (it only keeps the loads alive)
+ * Errors: PSA_ERR_INVALID_ARG for a NULL or misaligned pointer; bytes == 0 is a no-op.
+ */
+psa_status psa_stream_read_probe(const void *src, size_t bytes, void *sink, void *stream);
+
+/*
  * Copies the sticky device error word of a workspace to the host and clears nothing.
  * Synchronises `stream`.  host_flags: host pointer, receives an OR of PSA_DEVERR_* bits.
  */

@@ -90,6 +90,8 @@ def load_library() -> C.CDLL:
                                            vp, vp, C.POINTER(_Tuning), vp, sz, vp]
         lib.psa_dense_attention.restype = C.c_int
         lib.psa_dense_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, vp, sz, vp]
+        lib.psa_stream_read_probe.restype = C.c_int
+        lib.psa_stream_read_probe.argtypes = [vp, sz, vp, vp]
         lib.psa_read_device_error.restype = C.c_int
         lib.psa_read_device_error.argtypes = [vp, C.POINTER(C.c_int32), vp]
         _lib = lib
@@ -276,6 +278,14 @@ def dense_attention(kv: KvCache, q: torch.Tensor, *, workspace: torch.Tensor | N
     _check(st, "psa_dense_attention")
     out._workspace = workspace
     return out, lse
+
+
+def stream_read_probe(src: torch.Tensor, sink=None, stream=None) -> None:
+    """Reads the whole of `src` (a contiguous device tensor) once with a plain kernel; for timing."""
+    assert src.is_contiguous()
+    st = load_library().psa_stream_read_probe(_ptr(src), src.numel() * src.element_size(),
+                                              _ptr(sink) if sink is not None else None, _stream(stream))
+    _check(st, "psa_stream_read_probe")
 
 
 def read_device_error(workspace: torch.Tensor, stream=None) -> int:

@@ -1,6 +1,7 @@
 // The C ABI of libpsa: argument validation on the host, then kernel launches.  See include/psa.h
 // for the contract of every entry point.
 #include <math.h>
+#include <stdint.h>
 
 #include "psa_host.h"
 
@@ -135,6 +136,14 @@ psa_status psa_dense_attention(const psa_kv_desc *d, const void *q, float *out, 
     if (!q || !out || !workspace) return PSA_ERR_INVALID_ARG;
     if (workspace_bytes < psa::dense_workspace_bytes(d)) return PSA_ERR_WORKSPACE_TOO_SMALL;
     hipError_t e = psa::launch_dense(d, q, out, lse, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
+}
+
+psa_status psa_stream_read_probe(const void *src, size_t bytes, void *sink, void *stream) {
+    if (bytes == 0) return PSA_OK;
+    if (!src || (reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(sink) & 7u))
+        return PSA_ERR_INVALID_ARG;
+    hipError_t e = psa::launch_read_probe(src, bytes, sink, (hipStream_t)stream);
     return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
 }
 

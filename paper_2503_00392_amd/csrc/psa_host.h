@@ -66,6 +66,7 @@ struct DecodeArgs {
     float *scores_out;
     int32_t *traffic_out;
 };
+hipError_t launch_read_probe(const void *src, size_t bytes, void *sink, hipStream_t st);
 hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const DecodePlan &plan, void *ws,
                          hipStream_t st);
 

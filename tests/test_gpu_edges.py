@@ -115,3 +115,18 @@ def test_inputs_only_the_device_can_see_are_wrong(psa):
     again = psa.decode_attention(kv, li.q, meta, 0.9, 1, workspace=bad._workspace)
     torch.cuda.synchronize()
     assert psa.read_device_error(again._workspace) == 0
+
+
+def test_stream_read_probe_sizes_and_alignment(psa):
+    """The measurement aid reads and keeps nothing: any size runs (empty, below one load, ragged, several
+    workgroups' worth), the source is unchanged, and a misaligned source is refused on the host."""
+    buf = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    before = buf.clone()
+    sink = torch.zeros(1, dtype=torch.int64, device="cuda")
+    for n in (0, 1, 4, 5, 1000, 2048 * 4 + 12, 1 << 20):
+        psa.stream_read_probe(buf[:n].contiguous() if n else buf[:0], sink)
+    psa.stream_read_probe(buf, None)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, before)
+    with pytest.raises(psa.PsaError):
+        psa.stream_read_probe(buf[1:], sink)        # 4 bytes past a 16-byte boundary
