@@ -148,6 +148,7 @@ struct SelectShared {
     int page[kMaxChunkBlocks];
     int valid[kMaxChunkBlocks];
     int go;                                // after the wait for the window: 1 = read the chunk, 0 = the stream closed
+    uint4 stage[kSelectThreads / 64][16 * 17];   // per wave: one key slice, rows padded to 272 bytes
 #ifdef PSA_ENABLE_TRACE
     unsigned long long stamp[8];
     unsigned long long fold_stamp[16];
@@ -365,23 +366,17 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     lds_barrier();
     PSA_STAMP(0)
 
-    // ---- keys: wave w takes blocks [32*it + 4*w, +4).  A operand: row n = token n of the block,
-    //      same channel assignment as the queries; 64 contiguous bytes per token and step. ------------
+    // ---- keys: wave w takes blocks [16*it + 4*w, +4), each a 4 KiB slice read as four coalesced 1 KiB
+    //      loads.  A operand of the product: row n = token n of the block, same channel assignment as
+    //      the queries. ----------------------------------------------------------------------------
     for (int i0 = wave * kBatch; i0 < nblk; i0 += (kSelectThreads / 64) * kBatch) {
         uint4 ka[kBatch][4];
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             if (i0 + u < nblk) {
-#ifdef PSA_EXP_COALESCED_K
                 const uint8_t *kp = kv.k_pool + ((size_t)sh.page[i0 + u] * kv.num_kv_heads + h) * kSliceBytes + lane * 16;
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) ka[u][kk] = ld16(kp + kk * 1024);
-#else
-                const uint8_t *kp = kv.k_pool + ((size_t)sh.page[i0 + u] * kv.num_kv_heads + h) * kSliceBytes +
-                                    n * kRowBytes + kq * 16;
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) ka[u][kk] = ld16(kp + kk * 64);
-#endif
             }
         }
 #pragma unroll
@@ -389,8 +384,22 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
             const int i = i0 + u;
             if (i < nblk) {
                 f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+                // the slice arrived as four coalesced 1 KiB rows of lanes (loading it in the operand's layout
+                // would touch sixteen 64-byte segments per instruction); the wave turns it into that layout
+                // through its own LDS patch (row = token, 17 16-byte words apart: no bank conflicts)
+                uint4 *stg = sh.stage[wave];
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) acc = mfma_16x16x32<DT>(ka[u][kk], qb[kk], acc);
+                for (int kk = 0; kk < 4; ++kk) stg[(kk * 4 + (lane >> 4)) * 17 + (lane & 15)] = ka[u][kk];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+                uint4 a[4];
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) a[kk] = stg[n * 17 + kk * 4 + kq];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) acc = mfma_16x16x32<DT>(a[kk], qb[kk], acc);
                 // the lane now holds head n's logits of tokens 4*kq .. 4*kq+3
                 const int valid = sh.valid[i];
                 float sc[4];
