@@ -61,6 +61,29 @@ enum {
  *                            reading of the "cuboid-mean" metadata Sec. 3.1 names as its default      */
 typedef enum { PSA_SCORE_UPPER_BOUND = 0, PSA_SCORE_CUBOID_CENTER = 1 } psa_scorer;
 
+/*
+ * Optional second tier (Sec. 3.1 KV cache manager, Sec. 3.4 unified memory management).  With a tier the
+ * pools of a psa_kv_desc live in HOST memory that the GPU can address (pinned, e.g. hipHostMalloc), and
+ * the GPU caches (page, KV head) "slices" -- one 4 KiB key slice and one 4 KiB value slice -- in ONE pool
+ * of slots shared by all layers.  A slice has a global id: slice_base + page * num_kv_heads + h; the
+ * layers that share a pool use disjoint id ranges inside [0, total_slices).
+ * psa_decode_attention / psa_topk_attention read a slice from its slot if it has one and straight from
+ * host memory (over the host link) if not; results do not depend on where a slice was read from.
+ * psa_tier_update brings the pool up to date after a call (least recently used goes first).
+ *   state      device, psa_tier_state_bytes(total_slices, num_slots) bytes, 256-byte aligned; the library's own
+ *              tables (slice -> slot, slot -> slice, slot -> time of last use, clock); set up by
+ *              psa_tier_init, owned by the caller, shared by every descriptor that names this pool
+ *   slot_pool  device, num_slots * 8192 bytes, 16-byte aligned: slot s holds a key slice at s * 8192 and a
+ *              value slice at s * 8192 + 4096, each [page_size][head_dim]
+ */
+typedef struct {
+    void *state;
+    void *slot_pool;
+    int64_t total_slices;       /* 1 .. 2^31 - 1                                                   */
+    int64_t num_slots;          /* 1 .. 2^31 - 1                                                   */
+    int64_t slice_base;         /* id of this descriptor's page 0, KV head 0                       */
+} psa_tier;
+
 typedef struct {
     int32_t batch;              /* decode requests, one query token each                          */
     int32_t num_q_heads;        /* Hq                                                             */
@@ -74,6 +97,9 @@ typedef struct {
     const void *v_pool;         /* same layout                                                    */
     const int32_t *block_table; /* [batch][max_blocks_per_seq]: logical block -> physical page    */
     const int32_t *ctx_lens;    /* [batch]: tokens of each request; need not be a multiple of 16  */
+    const psa_tier *tier;       /* host pointer or NULL.  NULL: k_pool and v_pool are device memory and
+                                   hold everything.  Otherwise they are GPU-addressable host memory and
+                                   the slot pool caches slices of them (see psa_tier)              */
 } psa_kv_desc;
 
 /* Tuning knobs of psa_decode_attention; all zero = library defaults.  They change how much is read
@@ -196,6 +222,42 @@ psa_status psa_topk_attention(const psa_kv_desc *desc, const void *q, const void
  */
 psa_status psa_dense_attention(const psa_kv_desc *desc, const void *q, float *out, float *lse,
                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Two-tier block store (Sec. 3.1, 3.4).  All of it runs on the GPU, on `stream`; the host is not in the loop.
+ *
+ * psa_tier_state_bytes: bytes of psa_tier.state for these sizes (0 if they are out of range).
+ * psa_tier_init: empties the pool (no slice has a slot, clock 0).  Only state, total_slices and num_slots
+ *   of `tier` are read.
+ * psa_tier_update_workspace_bytes: bytes of scratch psa_tier_update needs for this descriptor (0 on an
+ *   invalid one or one without a tier).
+ * psa_tier_update: after a decode call on `desc` (same stream, or ordered after it), with that call's
+ *   `order_out` and `blocks_read`: the slices the attention used -- the first blocks_read[r][h] ranked
+ *   blocks of every (request, KV head) -- are marked used now; those without a slot are copied from host
+ *   memory into slots, in the order (request, KV head, rank), taking empty slots first (lowest index
+ *   first) and then the least recently used (ties: lowest slot index).  Not taken: a slot used by this
+ *   very update, and a slot whose slice id lies in [busy_first, busy_first + busy_count) -- name there the
+ *   id range of the layer whose attention may run at the same time on another stream, whose slots are
+ *   being read; busy_count = 0 for none.  If the misses outnumber the slots that may be taken, the first
+ *   in that order are placed and the rest stay in host memory.  The clock advances by one per call.
+ *   A page shared between two requests of the batch is not supported with a tier (its slices would
+ *   be placed twice; nothing faults, one of the two slots is wasted until it ages out).
+ *     order        device [batch][num_kv_heads][max_blocks_per_seq] int32, as written by the decode call
+ *     blocks_read  device [batch][num_kv_heads] int32, as written by the decode call
+ *     stats_out    device int32[4] or NULL: slices used that had a slot, that had none, slices placed,
+ *                  slices that lost their slot
+ *   Concurrency: calls that share a state must not overlap each other; a decode call may overlap an
+ *   update only if its slices are in the update's busy range and it was enqueued after the previous
+ *   update of its own layer completed.
+ * Errors: PSA_ERR_INVALID_ARG (NULL pointers, sizes out of range, id range outside [0, total_slices),
+ * pools the GPU cannot address), PSA_ERR_WORKSPACE_TOO_SMALL, PSA_ERR_LAUNCH.
+ */
+size_t psa_tier_state_bytes(int64_t total_slices, int64_t num_slots);
+psa_status psa_tier_init(const psa_tier *tier, void *stream);
+size_t psa_tier_update_workspace_bytes(const psa_kv_desc *desc);
+psa_status psa_tier_update(const psa_kv_desc *desc, const int32_t *order, const int32_t *blocks_read,
+                           int64_t busy_first, int64_t busy_count, int32_t *stats_out, void *workspace,
+                           size_t workspace_bytes, void *stream);
 
 /*
  * Measurement aid, not a step of the method: one plain kernel reads `bytes` (rounded down to a

@@ -31,7 +31,12 @@ class _KvDesc(C.Structure):
                 ("head_dim", C.c_int32), ("page_size", C.c_int32), ("num_pages", C.c_int32),
                 ("max_blocks_per_seq", C.c_int32), ("dtype", C.c_int32),
                 ("k_pool", C.c_void_p), ("v_pool", C.c_void_p),
-                ("block_table", C.c_void_p), ("ctx_lens", C.c_void_p)]
+                ("block_table", C.c_void_p), ("ctx_lens", C.c_void_p), ("tier", C.c_void_p)]
+
+
+class _Tier(C.Structure):
+    _fields_ = [("state", C.c_void_p), ("slot_pool", C.c_void_p), ("total_slices", C.c_int64),
+                ("num_slots", C.c_int64), ("slice_base", C.c_int64)]
 
 
 class _Tuning(C.Structure):
@@ -90,6 +95,14 @@ def load_library() -> C.CDLL:
                                            vp, vp, C.POINTER(_Tuning), vp, sz, vp]
         lib.psa_dense_attention.restype = C.c_int
         lib.psa_dense_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, vp, sz, vp]
+        lib.psa_tier_state_bytes.restype = sz
+        lib.psa_tier_state_bytes.argtypes = [C.c_int64, C.c_int64]
+        lib.psa_tier_init.restype = C.c_int
+        lib.psa_tier_init.argtypes = [C.POINTER(_Tier), vp]
+        lib.psa_tier_update_workspace_bytes.restype = sz
+        lib.psa_tier_update_workspace_bytes.argtypes = [C.POINTER(_KvDesc)]
+        lib.psa_tier_update.restype = C.c_int
+        lib.psa_tier_update.argtypes = [C.POINTER(_KvDesc), vp, vp, C.c_int64, C.c_int64, vp, vp, sz, vp]
         lib.psa_stream_read_probe.restype = C.c_int
         lib.psa_stream_read_probe.argtypes = [vp, sz, vp, vp]
         lib.psa_read_device_error.restype = C.c_int
@@ -120,14 +133,50 @@ def _dtype_code(dt: torch.dtype) -> int:
     raise TypeError(f"unsupported element type {dt}")
 
 
+class Tier:
+    """One pool of slots on the GPU shared by the layers of a model whose KV pools live in pinned host
+    memory (see psa_tier).  Allocates the state and the slot pool and empties them."""
+
+    def __init__(self, total_slices: int, num_slots: int, device="cuda", stream=None):
+        lib = load_library()
+        nbytes = int(lib.psa_tier_state_bytes(total_slices, num_slots))
+        if nbytes == 0:
+            raise ValueError("tier sizes out of range")
+        self.total_slices, self.num_slots = int(total_slices), int(num_slots)
+        self.state = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.slot_pool = torch.empty((num_slots, 2, 16, 128), dtype=torch.int16, device=device)
+        _check(lib.psa_tier_init(C.byref(self.c(0)), _stream(stream)), "psa_tier_init")
+
+    def c(self, slice_base: int) -> _Tier:
+        return _Tier(self.state.data_ptr(), self.slot_pool.data_ptr(), self.total_slices, self.num_slots,
+                     int(slice_base))
+
+    def tables(self):
+        """(slot_of [total_slices], owner [num_slots], stamp [num_slots], clock) as host arrays: a look
+        into the library's state for tests and statistics."""
+        def al(v):
+            return (v + 255) // 256 * 256
+        raw = self.state.cpu().numpy()
+        a = 256
+        b = a + al(self.total_slices * 4)
+        c = b + al(self.num_slots * 4)
+        slot_of = raw[a:a + self.total_slices * 4].view("int32").copy()
+        owner = raw[b:b + self.num_slots * 4].view("int32").copy()
+        stamp = raw[c:c + self.num_slots * 4].view("uint32").copy()
+        return slot_of, owner, stamp, int(raw[:4].view("uint32")[0])
+
+
 @dataclass
 class KvCache:
-    """One layer's paged KV cache and its tables (device tensors, see psa_kv_desc)."""
+    """One layer's paged KV cache and its tables (device tensors, see psa_kv_desc).  With `tier` the
+    pools are pinned host tensors and `slice_base` is the id of this layer's first slice in the tier."""
     k_pool: torch.Tensor       # [P][Hkv][16][128] fp16 / bf16
     v_pool: torch.Tensor
     block_table: torch.Tensor  # int32 [B][max_blocks]
     ctx_lens: torch.Tensor     # int32 [B]
     num_q_heads: int
+    tier: object = None        # Tier or None
+    slice_base: int = 0
 
     def desc(self) -> _KvDesc:
         P, H, T, D = self.k_pool.shape
@@ -137,7 +186,17 @@ class KvCache:
         return _KvDesc(self.block_table.shape[0], self.num_q_heads, H, D, T, P,
                        self.block_table.shape[1], _dtype_code(self.k_pool.dtype),
                        _ptr(self.k_pool), _ptr(self.v_pool), _ptr(self.block_table),
-                       _ptr(self.ctx_lens))
+                       _ptr(self.ctx_lens), self._tier_ptr())
+
+    def _tier_ptr(self):
+        if self.tier is None:
+            return None
+        assert self.k_pool.is_pinned() and self.v_pool.is_pinned(), "with a tier the pools are pinned host tensors"
+        # one struct per cache, kept alive (and in place) for as long as any descriptor may point to it
+        key = (id(self.tier), int(self.slice_base))
+        if getattr(self, "_tier_key", None) != key:
+            self._tier_c, self._tier_key = self.tier.c(self.slice_base), key
+        return C.addressof(self._tier_c)
 
 
 def _check(status: int, where: str) -> None:
@@ -278,6 +337,38 @@ def dense_attention(kv: KvCache, q: torch.Tensor, *, workspace: torch.Tensor | N
     _check(st, "psa_dense_attention")
     out._workspace = workspace
     return out, lse
+
+
+def tier_state_bytes(total_slices: int, num_slots: int) -> int:
+    return int(load_library().psa_tier_state_bytes(total_slices, num_slots))
+
+
+def tier_init(tier: Tier, stream=None) -> None:
+    _check(load_library().psa_tier_init(C.byref(tier.c(0)), _stream(stream)), "psa_tier_init")
+
+
+def tier_update_workspace_bytes(kv: KvCache) -> int:
+    d = kv.desc()
+    return int(load_library().psa_tier_update_workspace_bytes(C.byref(d)))
+
+
+def tier_update(kv: KvCache, order: torch.Tensor, blocks_read: torch.Tensor, busy_first: int = 0, busy_count: int = 0,
+                stats: torch.Tensor | None = None, workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """Brings the slot pool up to date with the slices the decode call that wrote `order` and
+    `blocks_read` used.  Returns `stats` (device int32[4]: hits, misses, placed, evicted)."""
+    d = kv.desc()
+    dev = order.device
+    if workspace is None:
+        workspace = torch.empty(tier_update_workspace_bytes(kv), dtype=torch.uint8, device=dev)
+    if stats is None:
+        stats = torch.zeros(4, dtype=torch.int32, device=dev)
+    assert order.dtype == torch.int32 and order.is_contiguous()
+    assert blocks_read.dtype == torch.int32 and blocks_read.is_contiguous()
+    st = load_library().psa_tier_update(C.byref(d), _ptr(order), _ptr(blocks_read), int(busy_first), int(busy_count),
+                                        _ptr(stats), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, "psa_tier_update")
+    stats._workspace = workspace
+    return stats
 
 
 def stream_read_probe(src: torch.Tensor, sink=None, stream=None) -> None:

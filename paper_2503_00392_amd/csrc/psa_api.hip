@@ -29,6 +29,38 @@ psa_status check_desc(const psa_kv_desc *d, bool need_tables, bool need_v) {
     return PSA_OK;
 }
 
+// A descriptor with a second tier: the tier's own fields, the id range, and the pools -- they must be
+// memory the GPU can address (device memory, or pinned host memory); `out` gets the descriptor with the
+// pools' device-side addresses.
+psa_status check_tier(const psa_kv_desc *d, psa_kv_desc *out) {
+    const psa_tier *t = d->tier;
+    if (!t || !t->state || !t->slot_pool) return PSA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(t->state) & 255u) || (reinterpret_cast<uintptr_t>(t->slot_pool) & 15u))
+        return PSA_ERR_INVALID_ARG;
+    if (t->total_slices < 1 || t->total_slices > INT32_MAX || t->num_slots < 1 || t->num_slots > INT32_MAX)
+        return PSA_ERR_INVALID_ARG;
+    if (t->slice_base < 0 || t->slice_base + (long long)d->num_pages * d->num_kv_heads > t->total_slices)
+        return PSA_ERR_INVALID_ARG;
+    *out = *d;
+    const void *pools[2] = {d->k_pool, d->v_pool};
+    const void *resolved[2] = {nullptr, nullptr};
+    for (int i = 0; i < 2; ++i) {
+        if (!pools[i]) continue;                       // (num_pages == 0)
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, pools[i]) != hipSuccess) {
+            (void)hipGetLastError();
+            return PSA_ERR_INVALID_ARG;
+        }
+        if (attr.type != hipMemoryTypeHost && attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)
+            return PSA_ERR_INVALID_ARG;
+        if (!attr.devicePointer) return PSA_ERR_INVALID_ARG;
+        resolved[i] = attr.devicePointer;
+    }
+    out->k_pool = resolved[0];
+    out->v_pool = resolved[1];
+    return PSA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -59,6 +91,11 @@ psa_status psa_build_block_metadata(const psa_kv_desc *d, void *meta, const int3
                                     const int32_t *page_list, int32_t num_listed, void *stream) {
     psa_status st = check_desc(d, false, false);
     if (st != PSA_OK) return st;
+    psa_kv_desc tiered;
+    if (d->tier) {      // pools in host memory: the kernels read them over the host link
+        if ((st = check_tier(d, &tiered)) != PSA_OK) return st;
+        d = &tiered;
+    }
     if (!meta && d->num_pages > 0) return PSA_ERR_INVALID_ARG;
     if (num_listed < 0 || (num_listed > 0 && !page_list)) return PSA_ERR_INVALID_ARG;
     if ((long long)d->num_pages * d->num_kv_heads > INT32_MAX) return PSA_ERR_UNSUPPORTED;
@@ -71,6 +108,11 @@ psa_status psa_append_kv(const psa_kv_desc *d, const void *k_new, const void *v_
                          int32_t *status, void *stream) {
     psa_status st = check_desc(d, true, true);
     if (st != PSA_OK) return st;
+    psa_kv_desc tiered;
+    if (d->tier) {
+        if ((st = check_tier(d, &tiered)) != PSA_OK) return st;
+        d = &tiered;
+    }
     if (d->batch == 0) return PSA_OK;
     if (!k_new || !v_new || !meta) return PSA_ERR_INVALID_ARG;
     hipError_t e = psa::launch_append(d, k_new, v_new, meta, status, (hipStream_t)stream);
@@ -93,6 +135,11 @@ static psa_status decode_common(const psa_kv_desc *d, const void *q, const void 
         if (cb != 0 && (cb < 8 || cb > psa::kMaxChunkBlocks || cb % 4 != 0)) return PSA_ERR_INVALID_ARG;
         if (tuning->window_chunks < 0 || tuning->spin_limit < 0) return PSA_ERR_INVALID_ARG;
         if (tuning->force_bitonic < 0 || tuning->force_bitonic > 1) return PSA_ERR_INVALID_ARG;
+    }
+    psa_kv_desc tiered;
+    if (d->tier) {
+        if ((st = check_tier(d, &tiered)) != PSA_OK) return st;
+        d = &tiered;
     }
     if (d->batch == 0) return PSA_OK;
     if (!q || !out || !n_selected || !mass_est || !workspace) return PSA_ERR_INVALID_ARG;
@@ -132,10 +179,49 @@ psa_status psa_dense_attention(const psa_kv_desc *d, const void *q, float *out, 
                                void *workspace, size_t workspace_bytes, void *stream) {
     psa_status st = check_desc(d, true, true);
     if (st != PSA_OK) return st;
+    psa_kv_desc tiered;
+    if (d->tier) {      // the control reads every slice from where the pools are, slots play no part
+        if ((st = check_tier(d, &tiered)) != PSA_OK) return st;
+        d = &tiered;
+    }
     if (d->batch == 0) return PSA_OK;
     if (!q || !out || !workspace) return PSA_ERR_INVALID_ARG;
     if (workspace_bytes < psa::dense_workspace_bytes(d)) return PSA_ERR_WORKSPACE_TOO_SMALL;
     hipError_t e = psa::launch_dense(d, q, out, lse, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
+}
+
+size_t psa_tier_state_bytes(int64_t total_slices, int64_t num_slots) {
+    if (total_slices < 1 || total_slices > INT32_MAX || num_slots < 1 || num_slots > INT32_MAX) return 0;
+    return psa::tier_state_bytes(total_slices, num_slots);
+}
+
+psa_status psa_tier_init(const psa_tier *tier, void *stream) {
+    if (!tier || !tier->state || (reinterpret_cast<uintptr_t>(tier->state) & 255u)) return PSA_ERR_INVALID_ARG;
+    if (psa_tier_state_bytes(tier->total_slices, tier->num_slots) == 0) return PSA_ERR_INVALID_ARG;
+    return psa::launch_tier_init(tier, (hipStream_t)stream) == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
+}
+
+size_t psa_tier_update_workspace_bytes(const psa_kv_desc *d) {
+    if (check_desc(d, false, false) != PSA_OK || !d->tier) return 0;
+    if (psa_tier_state_bytes(d->tier->total_slices, d->tier->num_slots) == 0) return 0;
+    return psa::tier_update_workspace_bytes(d);
+}
+
+psa_status psa_tier_update(const psa_kv_desc *d, const int32_t *order, const int32_t *blocks_read,
+                           int64_t busy_first, int64_t busy_count, int32_t *stats_out, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+    psa_status st = check_desc(d, true, true);
+    if (st != PSA_OK) return st;
+    psa_kv_desc tiered;
+    if ((st = check_tier(d, &tiered)) != PSA_OK) return st;
+    if (busy_count < 0) return PSA_ERR_INVALID_ARG;
+    if (tiered.batch == 0) return PSA_OK;
+    if (!order || !blocks_read || !workspace) return PSA_ERR_INVALID_ARG;
+    if ((long long)tiered.batch * tiered.num_kv_heads * tiered.max_blocks_per_seq > INT32_MAX) return PSA_ERR_UNSUPPORTED;
+    if (workspace_bytes < psa::tier_update_workspace_bytes(&tiered)) return PSA_ERR_WORKSPACE_TOO_SMALL;
+    hipError_t e = psa::launch_tier_update(&tiered, order, blocks_read, busy_first, busy_count, stats_out, workspace,
+                                           (hipStream_t)stream);
     return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
 }
 

@@ -3,7 +3,8 @@
 // block fills and stays there).  The metadata of a partly filled block covers its valid tokens, so it
 // is maintained per token: the first token of a block sets min = max = key, later ones fold in with
 // the same order-preserving 16-bit min/max the bulk build uses -- the result is bit for bit what the
-// bulk build gives on the new cache.
+// bulk build gives on the new cache.  With a second tier the token is written to host memory and, if the
+// slice has a slot, to the slot as well.
 #include "psa_host.h"
 
 namespace psa {
@@ -16,7 +17,9 @@ __global__ __launch_bounds__(256) void append_kernel(uint8_t *__restrict__ k_poo
                                                      const uint8_t *__restrict__ k_new,
                                                      const uint8_t *__restrict__ v_new,
                                                      uint8_t *__restrict__ meta, int32_t *__restrict__ status,
-                                                     int num_kv_heads, int num_pages, int max_blocks) {
+                                                     int num_kv_heads, int num_pages, int max_blocks,
+                                                     const int32_t *__restrict__ slot_of, uint8_t *__restrict__ slot_pool,
+                                                     long long slice_base) {
     const int r = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ctx = ctx_lens[r];
     int err = 0, page = 0;
@@ -36,6 +39,14 @@ __global__ __launch_bounds__(256) void append_kernel(uint8_t *__restrict__ k_poo
             const size_t dst = unit * kSliceBytes + (size_t)slot * kRowBytes + lane * 4;
             *reinterpret_cast<uint32_t *>(k_pool + dst) = kw;
             *reinterpret_cast<uint32_t *>(v_pool + dst) = vw;
+            if (slot_of) {      // second tier: the pools are host memory; a cached copy of the slice gets the token too
+                const int cached = slot_of[slice_base + (long long)unit];
+                if (cached >= 0) {
+                    uint8_t *c = slot_pool + (size_t)cached * (2 * kSliceBytes) + (size_t)slot * kRowBytes + lane * 4;
+                    *reinterpret_cast<uint32_t *>(c) = kw;
+                    *reinterpret_cast<uint32_t *>(c + kSliceBytes) = vw;
+                }
+            }
             uint32_t *mn = reinterpret_cast<uint32_t *>(meta + unit * kMetaBytes + lane * 4);
             uint32_t *mx = reinterpret_cast<uint32_t *>(meta + unit * kMetaBytes + 256 + lane * 4);
             if (slot == 0) {
@@ -58,10 +69,13 @@ __global__ __launch_bounds__(256) void append_kernel(uint8_t *__restrict__ k_poo
 hipError_t launch_append(const psa_kv_desc *d, const void *k_new, const void *v_new, void *meta,
                          int32_t *status, hipStream_t st) {
     if (d->batch == 0) return hipSuccess;
+    TierView t{};
+    if (d->tier) t = make_tier_view(d->tier);
     append_kernel<<<d->batch, 256, 0, st>>>((uint8_t *)d->k_pool, (uint8_t *)d->v_pool, d->block_table,
                                             (int32_t *)d->ctx_lens, (const uint8_t *)k_new,
                                             (const uint8_t *)v_new, (uint8_t *)meta, status, d->num_kv_heads,
-                                            d->num_pages, d->max_blocks_per_seq);
+                                            d->num_pages, d->max_blocks_per_seq, d->tier ? t.slot_of : nullptr,
+                                            t.slot_pool, t.slice_base);
     return hipGetLastError();
 }
 

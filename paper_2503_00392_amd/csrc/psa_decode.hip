@@ -109,6 +109,7 @@ hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const Decode
     if ((e = launch_score(kv, d->dtype, G, a.scorer, a.q, a.meta, ws, a.scores_out, st)) != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[1], st);
     if ((e = launch_order(kv, ws, G, plan, a.budget_blocks, a.order_out, st)) != hipSuccess) return e;
+    if (d->tier && (e = launch_tier_resolve(kv, d->tier, ws.ranked_page, st)) != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[2], st);
     if ((e = launch_select(kv, d->dtype, G, a.q, ws, a.threshold, a.check_granularity, plan, st)) != hipSuccess)
         return e;

@@ -28,7 +28,30 @@ struct KvView {
     const int32_t *block_table;
     const int32_t *ctx_lens;
     int32_t batch, num_q_heads, num_kv_heads, num_pages, max_blocks;
+    const uint8_t *slot_pool;   // second tier only: 8 KiB slots (key slice, value slice); else NULL
 };
+
+// Kernel-side view of a psa_tier and its state.
+struct TierView {
+    uint32_t *header;       // [64]: clock and the counters of the update in progress
+    int32_t *slot_of;       // [total_slices] slice -> slot, -1 = host memory only
+    int32_t *owner;         // [num_slots] slot -> slice, -1 = empty
+    uint32_t *stamp;        // [num_slots] clock value of the slot's last use, 0 = never
+    uint8_t *slot_pool;
+    long long slice_base, total_slices;
+    int num_slots;
+};
+
+// Where the key slice of ranked block `loc` of KV head h lives: loc >= 0 is a page of the pool, loc < 0
+// is ~slot of the second tier's slot pool (whose value slice follows its key slice).
+__device__ __forceinline__ const uint8_t *key_slice(const KvView &kv, int loc, int h) {
+    return loc >= 0 ? kv.k_pool + ((size_t)loc * kv.num_kv_heads + h) * kSliceBytes
+                    : kv.slot_pool + (size_t)(~loc) * (2 * kSliceBytes);
+}
+__device__ __forceinline__ const uint8_t *value_slice(const KvView &kv, int loc, int h) {
+    return loc >= 0 ? kv.v_pool + ((size_t)loc * kv.num_kv_heads + h) * kSliceBytes
+                    : kv.slot_pool + (size_t)(~loc) * (2 * kSliceBytes) + kSliceBytes;
+}
 
 // ---- workspace of psa_decode_attention -----------------------------------------------------
 // "Stream" = one (request, KV head) pair: one ranking, G query heads.

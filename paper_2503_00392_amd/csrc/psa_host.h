@@ -18,6 +18,7 @@ inline KvView make_view(const psa_kv_desc *d) {
     kv.num_kv_heads = d->num_kv_heads;
     kv.num_pages = d->num_pages;
     kv.max_blocks = d->max_blocks_per_seq;
+    kv.slot_pool = d->tier ? static_cast<const uint8_t *>(d->tier->slot_pool) : nullptr;
     return kv;
 }
 
@@ -66,6 +67,16 @@ struct DecodeArgs {
     float *scores_out;
     int32_t *traffic_out;
 };
+// psa_tier.hip
+size_t tier_state_bytes(long long total_slices, long long num_slots);
+TierView make_tier_view(const psa_tier *t);
+size_t tier_update_workspace_bytes(const psa_kv_desc *d);
+hipError_t launch_tier_init(const psa_tier *tier, hipStream_t st);
+hipError_t launch_tier_resolve(const KvView &kv, const psa_tier *tier, int32_t *ranked_page, hipStream_t st);
+hipError_t launch_tier_update(const psa_kv_desc *d, const int32_t *order, const int32_t *blocks_read,
+                              long long busy_first, long long busy_count, int32_t *stats_out, void *workspace,
+                              hipStream_t st);
+
 hipError_t launch_read_probe(const void *src, size_t bytes, void *sink, hipStream_t st);
 hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const DecodePlan &plan, void *ws,
                          hipStream_t st);

@@ -374,7 +374,7 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
 #pragma unroll
         for (int u = 0; u < kBatch; ++u) {
             if (i0 + u < nblk) {
-                const uint8_t *kp = kv.k_pool + ((size_t)sh.page[i0 + u] * kv.num_kv_heads + h) * kSliceBytes + lane * 16;
+                const uint8_t *kp = key_slice(kv, sh.page[i0 + u], h) + lane * 16;
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) ka[u][kk] = ld16(kp + kk * 1024);
             }

@@ -68,8 +68,7 @@ __device__ void attend_unit(AttendShared<G> &sh, const KvView &kv, const DecodeW
     for (int u = 0; u < kBatch; ++u) {
         const int i = wave * kBatch + u;
         if (i < maxcnt) {
-            const size_t off = ((size_t)sh.page[i] * kv.num_kv_heads + h) * kSliceBytes;
-            v[u] = load_slice(kv.v_pool + off, lane);
+            v[u] = load_slice(value_slice(kv, sh.page[i], h), lane);
         }
     }
     // logits of the chunk (contiguous in the workspace as [block][head][token]) -> LDS as
@@ -120,8 +119,7 @@ __device__ void attend_unit(AttendShared<G> &sh, const KvView &kv, const DecodeW
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
                 if (i0 + u < maxcnt) {
-                    const size_t off = ((size_t)sh.page[i0 + u] * kv.num_kv_heads + h) * kSliceBytes;
-                    v[u] = load_slice(kv.v_pool + off, lane);
+                    v[u] = load_slice(value_slice(kv, sh.page[i0 + u], h), lane);
                 }
             }
         }

@@ -141,3 +141,13 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(pb, "_LIB_PATH", str(tmp_path / "libpsa.so"))
     with pytest.raises(FileNotFoundError):
         pb.load_library()
+
+
+def test_tier_state_sizes(lib):
+    # header + slice table + two slot tables, each rounded up to 256 bytes; 0 for sizes out of range
+    assert psa.tier_state_bytes(1, 1) == 256 + 3 * 256
+    assert psa.tier_state_bytes(1000, 100) == 256 + 4096 + 2 * 512
+    for bad in ((0, 1), (1, 0), (-5, 3), (1 << 31, 1), (1, 1 << 31)):
+        assert psa.tier_state_bytes(*bad) == 0
+    # a descriptor without a tier has no update scratch
+    assert lib.psa_tier_update_workspace_bytes(C.byref(_desc())) == 0
