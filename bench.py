@@ -75,6 +75,123 @@ def read_measured_traffic(workload: str, kernel: str):
     return None
 
 
+def host_tier_leg(psa, args, cfg, layers, metas, eps, m, tuning_kw, dev):
+    """Sec. 3.1 / 3.4 on this machine: the KV pools of a few layers live in pinned host memory, one pool of slots
+    on the GPU caches their (page, KV head) slices, least recently used goes first.  Consecutive decode steps
+    with slowly drifting queries; attention reads cached slices from HBM and the others over the host link;
+    after each layer's attention the pool is updated on a second stream while the next layer computes."""
+    import numpy as np
+    import torch
+    from workloads import step_inputs
+
+    ids = [int(x) for x in args.host_tier_layers.split(",") if int(x) < len(layers)]
+    n_steps, Lt = args.host_tier, len(ids)
+    if Lt < 3:
+        return {"error": "the leg needs at least three layers"}
+    B, Hq, H = cfg.batch, cfg.num_q_heads, cfg.num_kv_heads
+    per_layer = [layers[i].k_pool.shape[0] * H for i in ids]
+    bases = [int(sum(per_layer[:j])) for j in range(Lt)]
+    total = int(sum(per_layer))
+    num_slots = max(int(total * args.slot_share), 1)
+    t0 = time.time()
+    tier = psa.Tier(total, num_slots)
+    hosts = []
+    for j, i in enumerate(ids):
+        kh = torch.empty(layers[i].k_pool.shape, dtype=layers[i].k_pool.dtype, pin_memory=True)
+        vh = torch.empty(layers[i].v_pool.shape, dtype=layers[i].v_pool.dtype, pin_memory=True)
+        kh.copy_(layers[i].k_pool)
+        vh.copy_(layers[i].v_pool)
+        hosts.append(psa.KvCache(kh, vh, layers[i].block_table, layers[i].ctx_lens, Hq, tier=tier, slice_base=bases[j]))
+    devs = [psa.KvCache(layers[i].k_pool, layers[i].v_pool, layers[i].block_table, layers[i].ctx_lens, Hq) for i in ids]
+    torch.cuda.synchronize()
+    log(f"[bench] host tier: {Lt} layers, {total * 8192 / 2**30:.1f} GiB pinned, {num_slots} slots "
+        f"({num_slots * 8192 / 2**30:.1f} GiB) ready in {time.time() - t0:.1f}s")
+    qs = [[step_inputs(layers[i], t)[0] for i in ids] for t in range(1, n_steps + 1)]
+    MB = layers[ids[0]].block_table.shape[1]
+
+    def new_outs():
+        return [psa.DecodeOutput(torch.empty((B, Hq, 128), dtype=torch.float32, device=dev),
+                                 torch.empty((B, Hq), dtype=torch.int32, device=dev),
+                                 torch.empty((B, Hq), dtype=torch.float32, device=dev),
+                                 torch.empty((B, H), dtype=torch.int32, device=dev),
+                                 torch.empty((B, Hq), dtype=torch.float32, device=dev),
+                                 torch.empty((B, H, MB), dtype=torch.int32, device=dev), None, None) for _ in range(Lt)]
+
+    tun = psa.Tuning(**tuning_kw)
+    ws = torch.empty(max(psa.decode_workspace_bytes(kv, tun) for kv in hosts), dtype=torch.uint8, device=dev)
+    uws = torch.empty(max(psa.tier_update_workspace_bytes(kv) for kv in hosts), dtype=torch.uint8, device=dev)
+    main_s, side_s = torch.cuda.current_stream(), torch.cuda.Stream()
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def run(caches, overlap, with_tier, use_hint=True):
+        outs = new_outs()
+        hint = [torch.zeros((B, H), dtype=torch.int32, device=dev) for _ in range(Lt)]
+        stats = torch.zeros((n_steps, Lt, 4), dtype=torch.int32, device=dev)
+        marks = [ev() for _ in range(n_steps + 1)]
+        done = [None] * Lt                      # event: the last update of layer j has finished
+        decoded = [ev() for _ in range(Lt)]
+        torch.cuda.synchronize()
+        marks[0].record(main_s)
+        for t in range(n_steps):
+            for j in range(Lt):
+                if with_tier and overlap and done[(j - 2) % Lt] is not None:
+                    main_s.wait_event(done[(j - 2) % Lt])     # the update that ran beside layer j-1 may have evicted anything else
+                # the depth hint of a step is what the same layer read in the step before (a copy: the call rewrites it)
+                tn = psa.Tuning(depth_hint=hint[j], **tuning_kw) if (use_hint and t > 0) else tun
+                psa.decode_attention(caches[j], qs[t][j], metas[ids[j]], eps, m, workspace=ws, outputs=outs[j], tuning=tn)
+                if use_hint:
+                    hint[j].copy_(outs[j].blocks_read)
+                if not with_tier:
+                    continue
+                if overlap:
+                    decoded[j].record(main_s)
+                    side_s.wait_event(decoded[j])
+                    nxt = (j + 1) % Lt
+                    psa.tier_update(caches[j], outs[j].order, outs[j].blocks_read, bases[nxt], per_layer[nxt],
+                                    stats=stats[t, j], workspace=uws, stream=side_s)
+                    done[j] = ev()
+                    done[j].record(side_s)
+                    # the next decode of this layer overwrites outs[j]: not before this update has read them
+                else:
+                    psa.tier_update(caches[j], outs[j].order, outs[j].blocks_read, 0, 0, stats=stats[t, j], workspace=uws)
+            if with_tier and overlap:
+                main_s.wait_event(done[Lt - 1])               # (also keeps outs[] from being overwritten too early)
+            marks[t + 1].record(main_s)
+        torch.cuda.synchronize()
+        ms = [marks[t].elapsed_time(marks[t + 1]) for t in range(n_steps)]
+        return ms, stats.cpu().numpy().astype(np.int64), [o.blocks_read.clone() for o in outs], [o.out.clone() for o in outs]
+
+    hbm_ms, _, hbm_read, hbm_out = run(devs, False, False)
+    psa.tier_init(tier)
+    ser_ms, ser_stats, ser_read, ser_out = run(hosts, False, True)
+    psa.tier_init(tier)
+    ovl_ms, ovl_stats, ovl_read, ovl_out = run(hosts, True, True)
+    psa.tier_init(tier)
+    noh_ms, noh_stats, _, noh_out = run(hosts, True, True, use_hint=False)
+    same = all(torch.equal(a, b) for a, b in zip(hbm_out, ser_out)) and all(torch.equal(a, b) for a, b in zip(hbm_out, ovl_out))
+    assert psa.read_device_error(ws) == 0
+
+    def summary(ms, st):
+        used = st[..., 0] + st[..., 1]
+        half = n_steps // 2
+        return {"first_step_ms": ms[0], "steady_ms_per_step": float(np.median(ms[half:])),
+                "hit_ratio_first_step": float(st[0, :, 0].sum() / max(used[0].sum(), 1)),
+                "hit_ratio_steady": float(st[half:, :, 0].sum() / max(used[half:].sum(), 1)),
+                "slices_used_per_step": float(used[half:].sum(1).mean()),
+                "host_link_MB_per_step_steady": float((st[half:, :, 1] + st[half:, :, 2]).sum(1).mean() * 8192 / 1e6),
+                "evicted_per_step_steady": float(st[half:, :, 3].sum(1).mean())}
+
+    return {"layers": ids, "steps": n_steps, "pinned_GiB": total * 8192 / 2**30, "slots": num_slots,
+            "slot_pool_GiB": num_slots * 8192 / 2**30, "slot_share": args.slot_share,
+            "all_in_hbm_ms_per_step": float(np.median(hbm_ms[n_steps // 2:])),
+            "tier_update_on_the_same_stream": summary(ser_ms, ser_stats),
+            "tier_update_on_a_second_stream": summary(ovl_ms, ovl_stats),
+            "tier_update_on_a_second_stream_no_depth_hint": summary(noh_ms, noh_stats),
+            "outputs_equal_all_in_hbm": bool(same),
+            "note": "queries drift from step to step, the cache does not grow; host_link_MB counts slices read in "
+                    "place by the attention kernels (misses) plus slices copied into slots"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -96,6 +213,11 @@ def main():
                     help="also run this many consecutive decode steps (append a token, drift the queries), with and "
                          "without the previous step's blocks_read as depth hint")
     ap.add_argument("--cpu-layers", type=str, default="", help="layers the oracle is timed on")
+    ap.add_argument("--host-tier", type=int, default=12,
+                    help="decode steps of the two-tier leg (KV of a few layers in pinned host memory, a slot pool on "
+                         "the GPU); 0 = skip")
+    ap.add_argument("--host-tier-layers", type=str, default="2,3,4,5")
+    ap.add_argument("--slot-share", type=float, default=0.25, help="slots of the pool / slices of the tiered layers")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -498,6 +620,14 @@ def main():
             loop[mode] = {"ms_per_step": e0.elapsed_time(e1) / n_steps, "blocks_read_per_stream_mean_last_step": float(np.mean(read))}
         log(f"[bench] decode loop: {loop}")
 
+    tier_leg = None
+    if args.host_tier > 0:
+        try:
+            tier_leg = host_tier_leg(psa, args, cfg, layers, metas, eps, m, tuning_kw, dev)
+        except Exception as exc:                      # e.g. no pinned memory to be had: the leg is an extra
+            tier_leg = {"error": f"{type(exc).__name__}: {exc}"}
+        log(f"[bench] host tier: {tier_leg}")
+
     traffic = read_measured_traffic(cfg.name, dom)
 
     result = {
@@ -528,6 +658,7 @@ def main():
         "dense_control": dense,
         "topk_control": topk,
         "scorer_comparison": scorers,
+        "host_tier": tier_leg,
         "metadata_bulk_build": {"ms": meta_ms, "GBps": meta_bytes / (meta_ms * 1e-3) / 1e9},
     }
     for n in ("select", "attend"):

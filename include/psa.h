@@ -235,7 +235,8 @@ psa_status psa_dense_attention(const psa_kv_desc *desc, const void *q, float *ou
  *   `order_out` and `blocks_read`: the slices the attention used -- the first blocks_read[r][h] ranked
  *   blocks of every (request, KV head) -- are marked used now; those without a slot are copied from host
  *   memory into slots, in the order (request, KV head, rank), taking empty slots first (lowest index
- *   first) and then the least recently used (ties: lowest slot index).  Not taken: a slot used by this
+ *   first) and then the least recently used (ties: lowest slot index; slots unused for 65535 updates or
+ *   more count as equally old).  Not taken: a slot used by this
  *   very update, and a slot whose slice id lies in [busy_first, busy_first + busy_count) -- name there the
  *   id range of the layer whose attention may run at the same time on another stream, whose slots are
  *   being read; busy_count = 0 for none.  If the misses outnumber the slots that may be taken, the first

@@ -22,6 +22,8 @@ of the stop), the paper's LRU policy at the granularity the GPU works at:
   * if there are more misses than candidates the first misses in that order get the slots and the
     rest stay in host memory.
 
+(The GPU path lets ages saturate at 65535 updates; the model does not, and no test runs that long.)
+
 With one used slice per update and no busy range this is textbook LRU; tests/test_tier_oracle.py pins it to
 the textbook's worked reference string and to an independent ordered-dictionary LRU on random traces.
 A slice used by two streams in one update (a page shared between requests) is outside the model: it

@@ -39,6 +39,7 @@ psa_status check_tier(const psa_kv_desc *d, psa_kv_desc *out) {
         return PSA_ERR_INVALID_ARG;
     if (t->total_slices < 1 || t->total_slices > INT32_MAX || t->num_slots < 1 || t->num_slots > INT32_MAX)
         return PSA_ERR_INVALID_ARG;
+    if (d->num_pages < 1) return PSA_ERR_INVALID_ARG;
     if (t->slice_base < 0 || t->slice_base + (long long)d->num_pages * d->num_kv_heads > t->total_slices)
         return PSA_ERR_INVALID_ARG;
     *out = *d;

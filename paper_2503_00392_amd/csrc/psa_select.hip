@@ -482,7 +482,15 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
     [[maybe_unused]] const unsigned long long t_begin = PSA_NOW();
     load_queries<G>(sh, kv, q, s);
     stage_pages<G>(sh, kv, ws, CB, s, c);
+    // Second tier: a chunk with slices that are not cached is read over the host link, where reading ahead
+    // of the stop costs far more than waiting does: such a chunk is read when it is expected to be needed
+    // (inside the hint) or when the fold is about to reach it.
+    const bool tiered = kv.slot_pool != nullptr;
+    if (tiered) lds_barrier();
     if (threadIdx.x == 0) {
+        bool from_host = false;
+        if (tiered)
+            for (int i = 0; i < min(CB, N - c * CB); ++i) from_host |= sh.page[i] >= 0;
         // chunks read beyond the fold's frontier are at most the window: wait until this one is inside
         // it, or the stream closes before it.  With a hint: everything up to it (and a chunk more) at
         // once; past it, a window that starts small and doubles with the distance the hint fell short by.
@@ -492,8 +500,9 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
             const unsigned long long kp = ld_relaxed(&ws.ctl[s].key_progress);
             const int fr = (int)(kp & 0xffffffffull), lim = (int)(kp >> 32);
             if (c >= lim) { go = 0; break; }       // closed, or a block budget ends before this chunk
-            const int reach = hinted > 0 ? max(hinted + 1, fr + min(max(4, 2 * (fr - hinted)), window_of(window, fr)))
-                                         : fr + window_of(window, fr);
+            int reach = hinted > 0 ? max(hinted + 1, fr + min(max(4, 2 * (fr - hinted)), window_of(window, fr)))
+                                   : fr + window_of(window, fr);
+            if (from_host) reach = min(reach, max(hinted, fr + 2));
             if (c < reach || tries >= spin_limit) break;
             nap(tries);
         }

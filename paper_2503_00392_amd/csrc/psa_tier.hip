@@ -7,8 +7,9 @@
 //
 // Replacement is least-recently-used at the granularity of one update (Sec. 3.4): every update has a time
 // stamp; the slices an attention call used get it; the misses, ordered by (stream, rank), take the
-// candidate slots ordered by (stamp, slot index).  Both orders are made by sorting 64-bit keys with the
-// device radix sort of rocPRIM -- the one library routine in this file; bookkeeping, not attention.
+// candidate slots ordered by (age, slot index), oldest first.  The first order comes from prefix sums, the
+// second from sorting 64-bit keys with the device radix sort of rocPRIM -- the one library routine in this
+// file; bookkeeping, not attention.
 #include <rocprim/device/device_radix_sort.hpp>
 
 #include "psa_host.h"
@@ -17,8 +18,9 @@ namespace psa {
 
 constexpr int kTierThreads = 256;
 constexpr unsigned long long kNoKey = ~0ull;
+constexpr uint32_t kMaxAge = 65535;      // updates after which a slot is as old as it gets
 // words of the state header
-constexpr int kClock = 0, kMisses = 1, kCandidates = 2, kHits = 3, kEvicted = 4;
+constexpr int kClock = 0, kMisses = 1, kPlaced = 2, kHits = 3, kEvicted = 4;
 
 static size_t tier_align(size_t v) { return (v + 255) / 256 * 256; }
 
@@ -63,71 +65,144 @@ __global__ __launch_bounds__(kTierThreads) void tier_resolve_kernel(KvView kv, T
     if (slot >= 0) *p = ~slot;
 }
 
-__global__ __launch_bounds__(kTierThreads) void tier_begin_kernel(TierView t, unsigned long long *miss_keys, int cap) {
-    const int i = blockIdx.x * kTierThreads + threadIdx.x;
-    if (i >= 1 && i <= 4) t.header[i] = 0;
-    for (int j = i; j < cap; j += gridDim.x * kTierThreads) miss_keys[j] = kNoKey;
-}
-
-// The slices the call used: stamp the cached ones, list the others.  grid (ceil(max_blocks / 256), S)
+// The slices the call used: stamp the cached ones, list the others -- per stream, in rank order, packed at
+// the front of the stream's row of `miss_ids` (a block-wide prefix sum per tile of 1024 ranks keeps the
+// order).  grid (S), 256 threads, 4 ranks per thread and tile.
+constexpr int kTouchPerThread = 4;
 __global__ __launch_bounds__(kTierThreads) void tier_touch_kernel(KvView kv, TierView t,
                                                                   const int32_t *__restrict__ order,
                                                                   const int32_t *__restrict__ blocks_read,
-                                                                  unsigned long long *miss_keys) {
-    const int s = blockIdx.y, r = s / kv.num_kv_heads, h = s % kv.num_kv_heads;
-    const int i = blockIdx.x * kTierThreads + threadIdx.x;
+                                                                  int32_t *__restrict__ miss_ids,
+                                                                  uint32_t *__restrict__ miss_count) {
+    __shared__ int wave_sum[kTierThreads / 64];
+    const int s = blockIdx.x, r = s / kv.num_kv_heads, h = s % kv.num_kv_heads;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int N = (ctx_clamped_quiet(kv, r) + kPage - 1) / kPage;
     const int used = min(max(blocks_read[s], 0), N);
     const uint32_t now = t.header[kClock] + 1;
-    bool hit = false;
-    if (i < used) {
-        const int b = order[(size_t)s * kv.max_blocks + i];
-        if (b >= 0 && b < kv.max_blocks) {
-            const int page = kv.block_table[(size_t)r * kv.max_blocks + b];
-            if ((unsigned)page < (unsigned)kv.num_pages) {
-                const long long id = t.slice_base + (long long)page * kv.num_kv_heads + h;
-                const int slot = t.slot_of[id];
-                if (slot >= 0) {
-                    t.stamp[slot] = now;
-                    hit = true;
-                } else {
-                    const uint32_t at = atomicAdd(&t.header[kMisses], 1u);
-                    miss_keys[at] = ((unsigned long long)((size_t)s * kv.max_blocks + i) << 32) | (uint32_t)id;
-                }
-            }
+    int32_t *row = miss_ids + (size_t)s * kv.max_blocks;
+    int placed = 0, hits = 0;
+    for (int base = 0; base < used; base += kTierThreads * kTouchPerThread) {
+        // the thread's 4 consecutive ranks: block, page, slot, loaded side by side
+        int b[kTouchPerThread], page[kTouchPerThread], slot[kTouchPerThread];
+        long long id[kTouchPerThread];
+        bool live[kTouchPerThread];
+#pragma unroll
+        for (int u = 0; u < kTouchPerThread; ++u) {
+            const int i = base + tid * kTouchPerThread + u;
+            live[u] = i < used;
+            b[u] = order[(size_t)s * kv.max_blocks + min(i, kv.max_blocks - 1)];
         }
+#pragma unroll
+        for (int u = 0; u < kTouchPerThread; ++u) {
+            live[u] = live[u] && b[u] >= 0 && b[u] < kv.max_blocks;
+            page[u] = kv.block_table[(size_t)r * kv.max_blocks + (live[u] ? b[u] : 0)];
+        }
+#pragma unroll
+        for (int u = 0; u < kTouchPerThread; ++u) {
+            live[u] = live[u] && (unsigned)page[u] < (unsigned)kv.num_pages;
+            id[u] = t.slice_base + (live[u] ? (long long)page[u] * kv.num_kv_heads + h : 0);
+            slot[u] = live[u] ? t.slot_of[id[u]] : -1;
+        }
+        int mine = 0;
+#pragma unroll
+        for (int u = 0; u < kTouchPerThread; ++u) {
+            if (live[u] && slot[u] >= 0) { t.stamp[slot[u]] = now; ++hits; }
+            if (live[u] && slot[u] < 0) ++mine;
+        }
+        // exclusive prefix of `mine` over the workgroup
+        int incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_up(incl, d);
+            if (lane >= d) incl += o;
+        }
+        __syncthreads();                                   // (the previous tile's sums have been read)
+        if (lane == 63) wave_sum[wave] = incl;
+        __syncthreads();
+        int before = incl - mine, total = 0;
+        for (int w = 0; w < kTierThreads / 64; ++w) {
+            if (w < wave) before += wave_sum[w];
+            total += wave_sum[w];
+        }
+        int at = placed + before;
+#pragma unroll
+        for (int u = 0; u < kTouchPerThread; ++u)
+            if (live[u] && slot[u] < 0) row[at++] = (int32_t)id[u];
+        placed += total;
     }
-    const int nh = __popcll(__ballot(hit));
-    if ((threadIdx.x & 63) == 0 && nh) atomicAdd(&t.header[kHits], (uint32_t)nh);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) hits += __shfl_xor(hits, d);
+    if (lane == 0 && hits) atomicAdd(&t.header[kHits], (uint32_t)hits);
+    if (tid == 0) miss_count[s] = (uint32_t)placed;
 }
 
-// Slots that may be given away, as keys (stamp, slot); the others get the key that sorts last.
+// Exclusive prefix sum of the streams' miss counts (one workgroup; S is small) and their total.
+__global__ __launch_bounds__(kTierThreads) void tier_offsets_kernel(TierView t, const uint32_t *__restrict__ miss_count,
+                                                                    uint32_t *__restrict__ miss_offset, int S) {
+    __shared__ uint32_t wave_sum[kTierThreads / 64];
+    __shared__ uint32_t carry;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < S; base += kTierThreads) {
+        const int i = base + tid;
+        const uint32_t v = i < S ? miss_count[i] : 0u;
+        uint32_t incl = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = (uint32_t)__shfl_up((int)incl, d);
+            if (lane >= d) incl += o;
+        }
+        if (lane == 63) wave_sum[wave] = incl;
+        __syncthreads();
+        uint32_t before = carry + incl - v, total = 0;
+        for (int w = 0; w < kTierThreads / 64; ++w) {
+            if (w < wave) before += wave_sum[w];
+            total += wave_sum[w];
+        }
+        if (i < S) miss_offset[i] = before;
+        __syncthreads();
+        if (tid == 0) carry += total;
+        __syncthreads();
+    }
+    if (tid == 0) { miss_offset[S] = carry; t.header[kMisses] = carry; }
+}
+
+// Slots that may be given away, as keys that sort oldest first: (65535 - age) in bits 32..48, where age = updates
+// since the slot's last use, saturating at 65535 (a slot never used counts as that old); the slot index below
+// it, so that the stable sort's ties go to the lower slot.  Slots that may not be taken get the key that sorts last.
 __global__ __launch_bounds__(kTierThreads) void tier_candidates_kernel(TierView t, long long busy_first,
                                                                        long long busy_count,
                                                                        unsigned long long *cand_keys) {
-    const int slot = blockIdx.x * kTierThreads + threadIdx.x;
     const uint32_t now = t.header[kClock] + 1;
-    bool ok = false;
-    if (slot < t.num_slots) {
+    for (int slot = blockIdx.x * kTierThreads + threadIdx.x; slot < t.num_slots; slot += gridDim.x * kTierThreads) {
         const uint32_t st = t.stamp[slot];
         const long long o = t.owner[slot];
-        ok = st < now && !(o >= 0 && o >= busy_first && o < busy_first + busy_count);
-        cand_keys[slot] = ok ? (((unsigned long long)st << 32) | (uint32_t)slot) : kNoKey;
+        const bool ok = st < now && !(o >= 0 && o >= busy_first && o < busy_first + busy_count);
+        const uint32_t age = st == 0 ? kMaxAge : min(now - st, kMaxAge);
+        cand_keys[slot] = ok ? (((unsigned long long)(kMaxAge - age) << 32) | (uint32_t)slot) : kNoKey;
     }
-    const int n = __popcll(__ballot(ok));
-    if ((threadIdx.x & 63) == 0 && n) atomicAdd(&t.header[kCandidates], (uint32_t)n);
 }
 
 // The j-th miss takes the j-th candidate slot: the slice is copied from host memory (two 4 KiB slices, one
 // 16-byte load per thread each) and the tables are brought up to date.  Workgroups stride over the pairs.
 __global__ __launch_bounds__(kTierThreads) void tier_promote_kernel(KvView kv, TierView t,
-                                                                    const unsigned long long *__restrict__ misses,
+                                                                    const int32_t *__restrict__ miss_ids,
+                                                                    const uint32_t *__restrict__ miss_offset, int S,
                                                                     const unsigned long long *__restrict__ cands) {
-    const uint32_t take = min(t.header[kMisses], t.header[kCandidates]);
+    const uint32_t misses_n = t.header[kMisses];
     const uint32_t now = t.header[kClock] + 1;
-    for (uint32_t j = blockIdx.x; j < take; j += gridDim.x) {
-        const long long id = (long long)(uint32_t)misses[j];
-        const int slot = (int)(uint32_t)cands[j];
+    for (uint32_t j = blockIdx.x; j < misses_n && j < (uint32_t)t.num_slots; j += gridDim.x) {
+        const unsigned long long cand = cands[j];
+        if (cand == kNoKey) break;                         // sorted: no slot left to give, here or further on
+        int lo = 0, hi = S;                                // the stream whose misses include the j-th of all
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (miss_offset[mid] <= j) lo = mid; else hi = mid;
+        }
+        const long long id = miss_ids[(size_t)lo * kv.max_blocks + (j - miss_offset[lo])];
+        const int slot = (int)(uint32_t)cand;
         const size_t src = (size_t)(id - t.slice_base) * kSliceBytes + threadIdx.x * 16;
         const uint4 k = ld16(kv.k_pool + src), v = ld16(kv.v_pool + src);
         uint8_t *dst = t.slot_pool + (size_t)slot * (2 * kSliceBytes) + threadIdx.x * 16;
@@ -146,15 +221,23 @@ __global__ __launch_bounds__(kTierThreads) void tier_promote_kernel(KvView kv, T
     }
 }
 
-__global__ void tier_finish_kernel(TierView t, int32_t *stats_out) {
+__global__ void tier_finish_kernel(TierView t, const unsigned long long *__restrict__ cands, int32_t *stats_out) {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     if (stats_out) {
+        int lo = 0, hi = t.num_slots;                      // first position of the sorted keys that is no candidate
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (cands[mid] == kNoKey) hi = mid; else lo = mid + 1;
+        }
         stats_out[0] = (int32_t)t.header[kHits];
         stats_out[1] = (int32_t)t.header[kMisses];
-        stats_out[2] = (int32_t)min(t.header[kMisses], t.header[kCandidates]);
+        stats_out[2] = (int32_t)min(t.header[kMisses], (uint32_t)lo);
         stats_out[3] = (int32_t)t.header[kEvicted];
     }
     t.header[kClock] += 1;
+    t.header[kMisses] = 0;
+    t.header[kHits] = 0;
+    t.header[kEvicted] = 0;
 }
 
 hipError_t launch_tier_init(const psa_tier *tier, hipStream_t st) {
@@ -171,23 +254,24 @@ hipError_t launch_tier_resolve(const KvView &kv, const psa_tier *tier, int32_t *
 }
 
 struct TierScratch {
-    size_t miss_in, miss_out, cand_in, cand_out, temp, temp_bytes, total;
+    size_t miss_ids, miss_count, miss_offset, cand_in, cand_out, temp, temp_bytes, total;
 };
 
 static TierScratch tier_scratch(const psa_kv_desc *d) {
-    const size_t cap = (size_t)d->batch * d->num_kv_heads * d->max_blocks_per_seq;
+    const size_t S = (size_t)d->batch * d->num_kv_heads;
+    const size_t cap = S * d->max_blocks_per_seq;
     const size_t slots = (size_t)d->tier->num_slots;
-    size_t t1 = 0, t2 = 0;
+    size_t tb = 0;
     unsigned long long *none = nullptr;
-    (void)rocprim::radix_sort_keys(nullptr, t1, none, none, cap, 0, 64, (hipStream_t)0);
-    (void)rocprim::radix_sort_keys(nullptr, t2, none, none, slots, 0, 64, (hipStream_t)0);
+    (void)rocprim::radix_sort_keys(nullptr, tb, none, none, slots, 32, 49, (hipStream_t)0);
     TierScratch L;
     size_t at = 0;
-    L.miss_in = at;  at = tier_align(at + cap * 8);
-    L.miss_out = at; at = tier_align(at + cap * 8);
-    L.cand_in = at;  at = tier_align(at + slots * 8);
-    L.cand_out = at; at = tier_align(at + slots * 8);
-    L.temp = at;     L.temp_bytes = t1 > t2 ? t1 : t2;
+    L.miss_ids = at;    at = tier_align(at + cap * 4);
+    L.miss_count = at;  at = tier_align(at + S * 4);
+    L.miss_offset = at; at = tier_align(at + (S + 1) * 4);
+    L.cand_in = at;     at = tier_align(at + slots * 8);
+    L.cand_out = at;    at = tier_align(at + slots * 8);
+    L.temp = at;        L.temp_bytes = tb;
     at = tier_align(at + L.temp_bytes);
     L.total = at;
     return L;
@@ -202,30 +286,27 @@ hipError_t launch_tier_update(const psa_kv_desc *d, const int32_t *order, const 
     const TierView t = make_tier_view(d->tier);
     const TierScratch L = tier_scratch(d);
     uint8_t *base = static_cast<uint8_t *>(workspace);
-    auto *miss_in = reinterpret_cast<unsigned long long *>(base + L.miss_in);
-    auto *miss_out = reinterpret_cast<unsigned long long *>(base + L.miss_out);
+    auto *miss_ids = reinterpret_cast<int32_t *>(base + L.miss_ids);
+    auto *miss_count = reinterpret_cast<uint32_t *>(base + L.miss_count);
+    auto *miss_offset = reinterpret_cast<uint32_t *>(base + L.miss_offset);
     auto *cand_in = reinterpret_cast<unsigned long long *>(base + L.cand_in);
     auto *cand_out = reinterpret_cast<unsigned long long *>(base + L.cand_out);
     const int S = kv.batch * kv.num_kv_heads;
-    const size_t cap = (size_t)S * kv.max_blocks;
     hipError_t e;
-    tier_begin_kernel<<<(unsigned)((cap + kTierThreads - 1) / kTierThreads < 2048 ? (cap + kTierThreads - 1) / kTierThreads : 2048),
-                        kTierThreads, 0, st>>>(t, miss_in, (int)cap);
+    tier_touch_kernel<<<S, kTierThreads, 0, st>>>(kv, t, order, blocks_read, miss_ids, miss_count);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    const dim3 grid((kv.max_blocks + kTierThreads - 1) / kTierThreads, S);
-    tier_touch_kernel<<<grid, kTierThreads, 0, st>>>(kv, t, order, blocks_read, miss_in);
+    tier_offsets_kernel<<<1, kTierThreads, 0, st>>>(t, miss_count, miss_offset, S);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    tier_candidates_kernel<<<(t.num_slots + kTierThreads - 1) / kTierThreads, kTierThreads, 0, st>>>(t, busy_first, busy_count,
-                                                                                              cand_in);
+    const int cgrid = (t.num_slots + kTierThreads - 1) / kTierThreads;
+    tier_candidates_kernel<<<cgrid < 2048 ? cgrid : 2048, kTierThreads, 0, st>>>(t, busy_first, busy_count, cand_in);
     if ((e = hipGetLastError()) != hipSuccess) return e;
+    // candidates by bits 32..48 (the sort is stable: equal ages stay in slot order)
     size_t tb = L.temp_bytes;
-    if ((e = rocprim::radix_sort_keys(base + L.temp, tb, miss_in, miss_out, cap, 0, 64, st)) != hipSuccess) return e;
-    tb = L.temp_bytes;
-    if ((e = rocprim::radix_sort_keys(base + L.temp, tb, cand_in, cand_out, (size_t)t.num_slots, 0, 64, st)) != hipSuccess)
+    if ((e = rocprim::radix_sort_keys(base + L.temp, tb, cand_in, cand_out, (size_t)t.num_slots, 32, 49, st)) != hipSuccess)
         return e;
-    tier_promote_kernel<<<2048, kTierThreads, 0, st>>>(kv, t, miss_out, cand_out);
+    tier_promote_kernel<<<2048, kTierThreads, 0, st>>>(kv, t, miss_ids, miss_offset, S, cand_out);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    tier_finish_kernel<<<1, 64, 0, st>>>(t, stats_out);
+    tier_finish_kernel<<<1, 64, 0, st>>>(t, cand_out, stats_out);
     return hipGetLastError();
 }
 
