@@ -217,7 +217,7 @@ def main():
                     help="decode steps of the two-tier leg (KV of a few layers in pinned host memory, a slot pool on "
                          "the GPU); 0 = skip")
     ap.add_argument("--host-tier-layers", type=str, default="2,3,4,5")
-    ap.add_argument("--slot-share", type=float, default=0.25, help="slots of the pool / slices of the tiered layers")
+    ap.add_argument("--slot-share", type=float, default=0.19, help="slots of the pool / slices of the tiered layers")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
