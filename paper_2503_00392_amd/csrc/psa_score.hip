@@ -4,6 +4,9 @@
 
 namespace psa {
 
+constexpr int kScoreIts = 4;                  // blocks per 16-lane row of a wave (2 and 8 measured: no faster)
+constexpr int kScoreBlocks = 16 * kScoreIts;  // blocks per workgroup
+
 // =================================================================================================
 // Scoring.  Upper bound (CENTER = 0):
 //   UB[g][b] = (1/sqrt d) sum_c max(q_c kmin_c, q_c kmax_c) = (1/sqrt d) (q+ . kmax + q- . kmin)
@@ -27,7 +30,7 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 2) header[kValueCount] = 0;   // value work list
     const int ctx = ctx_clamped_quiet(kv, r);
     const int N = (ctx + kPage - 1) / kPage;
-    const int base = blockIdx.x * 64 + wave * 16;
+    const int base = blockIdx.x * kScoreBlocks + wave * (4 * kScoreIts);
     if (base >= N) return;
 
     // the lane's 16 channels of every query head, with the entries of the wrong sign zeroed
@@ -45,9 +48,9 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
     }
 
     const int32_t *table = kv.block_table + (size_t)r * kv.max_blocks;
-    uint4 ma[4], mb[4];
+    uint4 ma[kScoreIts], mb[kScoreIts];
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
+    for (int it = 0; it < kScoreIts; ++it) {
         const int b = base + it * 4 + row;
         if (b < N) {
             const int page = clamp_page_quiet(table[b], kv.num_pages);
@@ -60,7 +63,7 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
         }
     }
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
+    for (int it = 0; it < kScoreIts; ++it) {
         const int b = base + it * 4 + row;
         const uint32_t w[8] = {ma[it].x, ma[it].y, ma[it].z, ma[it].w, mb[it].x, mb[it].y, mb[it].z, mb[it].w};
         float cs = -INFINITY;
@@ -83,7 +86,7 @@ template <int DT, int G>
 static hipError_t launch_score_t(const KvView &kv, int scorer, const void *q, const void *meta, const DecodeWs &ws,
                                  float *scores_out, hipStream_t st) {
     const int S = kv.batch * kv.num_kv_heads;
-    const dim3 grid((kv.max_blocks + 63) / 64, S);
+    const dim3 grid((kv.max_blocks + kScoreBlocks - 1) / kScoreBlocks, S);
     if (scorer == 1)
         score_kernel<DT, G, 1><<<grid, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
                                                      scores_out, ws.header);
