@@ -13,8 +13,11 @@
 //   2. fetches the chunk's page numbers and waits (napping about a microsecond between looks at one
 //      progress word, a bounded number of times) until the chunk is inside the read-ahead window --
 //      chunks read beyond the fold's frontier are at most max(window, frontier/4), 256 at most, which
-//      bounds the keys read beyond the stop -- or the stream closes before it;
-//   3. reads the chunk's key slices (each wave keeps 4 slices = 16 KiB in flight), computes the
+//      bounds the keys read beyond the stop -- or the stream closes before it (with a second tier, a
+//      chunk that has slices in host memory waits until the fold is one chunk away, unless it lies
+//      inside the depth hint: the host link is too slow to read ahead over it);
+//   3. reads the chunk's key slices (each wave keeps 4 slices = 16 KiB in flight, loaded as coalesced
+//      1 KiB rows and turned into the matrix-operand layout through a patch of LDS), computes the
 //      scaled logits of all G heads as a 16-token x 16-head x 128-channel product on the matrix
 //      cores (heads beyond G are zero columns), stores them for the value pass, and reduces each
 //      block's log-sum-exp L_b (= log AS of line 10);
