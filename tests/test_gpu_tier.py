@@ -191,3 +191,56 @@ def test_tier_arguments_are_checked_on_the_host(psa):
     with pytest.raises(psa.PsaError):
         psa.tier_update(L.host, out.order, out.blocks_read, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
     assert psa.tier_state_bytes(0, 4) == 0 and psa.tier_state_bytes(4, 0) == 0 and psa.tier_state_bytes(1 << 31, 4) == 0
+
+
+def test_updates_on_a_second_stream_beside_the_next_layer(psa):
+    """The overlap protocol of Sec. 3.3 as the benchmark runs it: layer j's update goes to a second stream
+    with layer j+1 named busy and runs beside layer j+1's attention; layer j+2 waits for it.  Outputs equal
+    the single-tier run's and the tables end up exactly as the model's, which applies the same updates one
+    after the other."""
+    steps, nl = 4, 3
+    cfg = get_config(3).scaled(batch=2, ctx=4096, layers=nl)
+    lis = [generate_layer(cfg, layer=2 + i, device="cuda") for i in range(nl)]
+    sizes = [li.k_pool.shape[0] * li.k_pool.shape[1] for li in lis]
+    bases = [int(sum(sizes[:i])) for i in range(nl)]
+    total = int(sum(sizes))
+    num_slots = total // 12
+    tier = psa.Tier(total, num_slots)
+    model = TierModel(total, num_slots)
+    layers = [Layer(psa, lis[i], tier, bases[i]) for i in range(nl)]
+    main_s, side_s = torch.cuda.current_stream(), torch.cuda.Stream()
+    uws = torch.empty(max(psa.tier_update_workspace_bytes(L.host) for L in layers), dtype=torch.uint8, device="cuda")
+    stats = torch.zeros((steps, nl, 4), dtype=torch.int32, device="cuda")
+    done = [None] * nl
+    log = []                                  # what each update saw, for the model: (layer, order, blocks_read)
+    for t in range(1, steps + 1):
+        outs = []
+        for j, L in enumerate(layers):
+            q = step_inputs(L.li, t)[0]
+            if done[(j - 2) % nl] is not None:
+                main_s.wait_event(done[(j - 2) % nl])
+            got = psa.decode_attention(L.host, q, L.meta_host, 0.9, 1, want_order=True)
+            ref = psa.decode_attention(L.dev, q, L.meta_dev, 0.9, 1, want_order=True)
+            outs.append((got, ref))
+            decoded = torch.cuda.Event()
+            decoded.record(main_s)
+            side_s.wait_event(decoded)
+            nxt = (j + 1) % nl
+            psa.tier_update(L.host, got.order, got.blocks_read, bases[nxt], sizes[nxt], stats=stats[t - 1, j],
+                            workspace=uws, stream=side_s)
+            done[j] = torch.cuda.Event()
+            done[j].record(side_s)
+            log.append((j, got.order, got.blocks_read, nxt))
+        main_s.wait_event(done[nl - 1])
+        torch.cuda.synchronize()
+        for got, ref in outs:
+            _same(got, ref)
+    got_stats = stats.cpu().numpy().reshape(-1, 4)
+    for k, (j, order, read, nxt) in enumerate(log):
+        L = layers[j]
+        ids = used_slices(L.li.block_table.cpu().numpy(), order.cpu().numpy(), read.cpu().numpy(), L.li.k_pool.shape[1],
+                          L.slice_base)
+        want = model.update(ids, bases[nxt], sizes[nxt])
+        assert got_stats[k].tolist() == [want.hits, want.misses, want.promoted, want.evicted], f"update {k}"
+    _check_tables(tier, model, layers)
+    assert got_stats[:, 3].sum() > 0, "the pool was meant to be too small"
