@@ -105,7 +105,7 @@ def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, request
     assert rep.worst_out_vs_own_set <= OUT_RTOL, f"output vs own set: {rep.worst_out_vs_own_set}"
 
     # -- stop index, selected set, estimate ---------------------------------------------------------
-    curves = None
+    own_rank = None
     for i in range(len(requests)):
         N = int(nb[i])
         for hq in range(Hq):
@@ -118,11 +118,20 @@ def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, request
                 continue
             assert g_mass[i, hq] > eps or n_g == N, "estimate must exceed eps unless all blocks were used"
             if n_g != n_o:
-                if curves is None:
-                    curves = po.psa_decode(sub, eps, m, curves=True, scorer=scorer)
-                p_at = curves.p_acc[i, hq, min(n_g, n_o) - 1]
+                # Two rankings that differ only where scores agree within SCORE_ATOL are equally valid (checked
+                # rank by rank above), and a swap of two such blocks right at the stop moves AS_min and with
+                # it the stop.  So the stop is first compared with Algorithm 1 run by the oracle over the
+                # GPU's own ranking; only if that differs too must P_acc sit at the boundary.
+                if own_rank is None:
+                    own_rank = po.psa_decode_ordered(sub, g_order, eps, m, curves=True)
+                if int(own_rank.n_selected[i, hq]) == n_g:
+                    assert abs(g_mass[i, hq] - own_rank.mass_est[i, hq]) <= 1e-4
+                    rep.set_tolerated += 1
+                    continue
+                p_at = own_rank.p_acc[i, hq, min(n_g, int(own_rank.n_selected[i, hq])) - 1]
                 assert abs(p_at - eps) <= PACC_ATOL, \
-                    f"stop index {n_g} vs oracle {n_o} with P_acc {p_at} not at the boundary {eps}"
+                    f"stop index {n_g} vs oracle {n_o} ({int(own_rank.n_selected[i, hq])} on the GPU's ranking) " \
+                    f"with P_acc {p_at} not at the boundary {eps}"
                 rep.stop_flips += 1
                 continue
             sg, so = set(g_order[i, h, :n_g].tolist()), set(ora.order[i, h, :n_o].tolist())

@@ -1,0 +1,65 @@
+"""Seeded sweep of random shapes, thresholds, test granularities, tunings, hints and scorers through the C
+ABI against the oracle: a broad net for what the hand-picked cases miss.  Also two cases it once caught
+in which fp32 and fp64 scoring order two blocks 2e-6 apart differently right at the stop."""
+import numpy as np
+import pytest
+import torch
+
+import gpu_common as gc
+from workloads import generate_layer, get_config
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def psa():
+    import paper_2503_00392_amd as psa
+    psa.load_library()
+    assert torch.cuda.is_available()
+    return psa
+
+
+def _run(psa, cfg, layer, eps, m, tun, scorer):
+    li = generate_layer(cfg, layer=layer, device="cuda", poison_tail=True)
+    out = gc.run_gpu_decode(li, eps, m, tuning=tun, scorer=scorer)
+    rep = gc.check_decode_against_oracle(gc.to_problem(li), out, eps, m, scorer=scorer)
+    assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads
+    return rep
+
+
+@pytest.mark.parametrize("seed", [101, 202])
+def test_random_shapes_against_the_oracle(psa, seed):
+    rng = np.random.default_rng(seed)
+    flips = heads = 0
+    for case in range(120):
+        idx = int(rng.choice([1, 2, 3, 4, 5]))
+        G, H = int(rng.choice([1, 2, 4, 8])), int(rng.choice([1, 2, 4, 8]))
+        batch, ctx = int(rng.integers(1, 5)), int(rng.integers(1, 9000))
+        kw = dict(batch=batch, ctx=ctx, num_q_heads=G * H, num_kv_heads=H, dtype=str(rng.choice(["f16", "bf16"])))
+        if idx == 4:
+            kw["ctx_min"] = int(rng.integers(1, ctx + 1))
+        if idx == 3:
+            kw["layers"] = 1
+        cfg = get_config(idx).scaled(**kw)
+        eps = float(rng.choice([0.0, 0.3, 0.8, 0.9, 0.95, 0.99, 1.0]))
+        m = int(rng.choice([1, 1, 2, 5, 16, 100]))
+        tun = psa.Tuning(chunk_blocks=int(rng.choice([0, 8, 16, 32, 64])), window_chunks=int(rng.choice([0, 1, 2, 7, 40])),
+                         spin_limit=int(rng.choice([0, 0, 1, 50])))
+        layer = int(rng.integers(0, 32)) if idx == 3 else 0
+        if rng.random() < 0.5:
+            MB = (ctx + 15) // 16
+            tun.depth_hint = torch.from_numpy(rng.integers(0, MB + 5, size=(batch, H)).astype(np.int32)).cuda()
+        scorer = int(rng.choice([0, 0, 1]))
+        print(f"case {case}: config {idx} {kw} layer {layer} eps {eps} m {m} "
+              f"tuning {tun.chunk_blocks}/{tun.window_chunks}/{tun.spin_limit} scorer {scorer}", flush=True)
+        rep = _run(psa, cfg, layer, eps, m, tun, scorer)
+        flips += rep.stop_flips
+        heads += rep.heads
+    assert flips <= heads // 200
+
+
+@pytest.mark.parametrize("kw,m", [(dict(batch=3, ctx=5011, num_q_heads=64, num_kv_heads=8, dtype="f16"), 1),
+                                  (dict(batch=3, ctx=7181, num_q_heads=16, num_kv_heads=2, dtype="f16"), 2)])
+def test_near_tied_scores_at_the_stop(psa, kw, m):
+    rep = _run(psa, get_config(1).scaled(**kw), 0, 0.99, m, None, 0)
+    assert rep.set_tolerated >= 1
