@@ -151,3 +151,26 @@ def test_tier_state_sizes(lib):
         assert psa.tier_state_bytes(*bad) == 0
     # a descriptor without a tier has no update scratch
     assert lib.psa_tier_update_workspace_bytes(C.byref(_desc())) == 0
+
+
+def test_binding_structs_have_the_layout_of_the_header(tmp_path):
+    """The ctypes mirrors of psa_kv_desc, psa_tuning and psa_tier against what a C compiler makes of
+    include/psa.h: total sizes and the offset of every field."""
+    import subprocess
+    from paper_2503_00392_amd import binding as b
+    structs = {"psa_kv_desc": b._KvDesc, "psa_tuning": b._Tuning, "psa_tier": b._Tier}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', f'#include "{HEADER}"', 'int main(void) {']
+    for cname, ct in structs.items():
+        lines.append(f'  printf("{cname} %zu\\n", sizeof({cname}));')
+        for fname, _ in ct._fields_:
+            lines.append(f'  printf("{cname}.{fname} %zu\\n", offsetof({cname}, {fname}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-o", str(exe), str(src)], check=True)
+    got = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for cname, ct in structs.items():
+        assert int(got[cname]) == C.sizeof(ct), cname
+        for fname, _ in ct._fields_:
+            assert int(got[f"{cname}.{fname}"]) == getattr(ct, fname).offset, f"{cname}.{fname}"
