@@ -115,8 +115,9 @@ typedef struct {
     const int32_t *depth_hint; /* device pointer or NULL: [batch][num_kv_heads] blocks each (request, KV head)
                                is expected to need, e.g. blocks_read of the previous decode step of the
                                same layer (consecutive decode queries select similar sets).  The chunks
-                               that cover it are read at once instead of window by window; a wrong hint
-                               costs time or traffic, never correctness                               */
+                               that cover it, plus a margin of a sixteenth and two chunks, are read at once
+                               instead of window by window; a wrong hint costs time or traffic, never
+                               correctness                                                            */
     void *phase_events;     /* host pointer: NULL, or hipEvent_t[6] the call records on `stream`
                                before scoring and after each of its kernels: scoring, ranking,
                                selection (key pass), attention (value pass), final merge

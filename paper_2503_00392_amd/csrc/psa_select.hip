@@ -495,15 +495,18 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
         if (tiered)
             for (int i = 0; i < min(CB, N - c * CB); ++i) from_host |= sh.page[i] >= 0;
         // chunks read beyond the fold's frontier are at most the window: wait until this one is inside
-        // it, or the stream closes before it.  With a hint: everything up to it (and a chunk more) at
-        // once; past it, a window that starts small and doubles with the distance the hint fell short by.
+        // it, or the stream closes before it
         const int hinted = hinted_chunks(depth_hint, s, N, CB);
         int go = 1;
         for (int tries = 0;; ++tries) {
             const unsigned long long kp = ld_relaxed(&ws.ctl[s].key_progress);
             const int fr = (int)(kp & 0xffffffffull), lim = (int)(kp >> 32);
             if (c >= lim) { go = 0; break; }       // closed, or a block budget ends before this chunk
-            int reach = hinted > 0 ? max(hinted + 1, fr + min(max(4, 2 * (fr - hinted)), window_of(window, fr)))
+            // with a hint: everything up to it plus a margin (a sixteenth and two chunks: the depth of a
+            // decode step differs a little from the previous step's) at once; past that, a window that
+            // starts at 8 chunks and doubles with the distance the hint fell short by
+            const int padded = hinted + (hinted >> 4) + 2;
+            int reach = hinted > 0 ? max(padded, fr + min(max(8, 2 * (fr - hinted)), window_of(window, fr)))
                                    : fr + window_of(window, fr);
             if (from_host) reach = min(reach, max(hinted, fr + 2));
             if (c < reach || tries >= spin_limit) break;
