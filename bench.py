@@ -87,7 +87,7 @@ def host_tier_leg(psa, args, cfg, layers, metas, eps, m, tuning_kw, dev):
     ids = [int(x) for x in args.host_tier_layers.split(",") if int(x) < len(layers)]
     n_steps, Lt = args.host_tier, len(ids)
     if Lt < 3:
-        return {"error": "the leg needs at least three layers"}
+        return {"skipped": "the leg needs at least three layers of the workload"}
     B, Hq, H = cfg.batch, cfg.num_q_heads, cfg.num_kv_heads
     per_layer = [layers[i].k_pool.shape[0] * H for i in ids]
     bases = [int(sum(per_layer[:j])) for j in range(Lt)]
@@ -209,8 +209,8 @@ def main():
     ap.add_argument("--no-topk-comparison", action="store_true")
     ap.add_argument("--no-scorer-comparison", action="store_true")
     ap.add_argument("--no-depth-hint", action="store_true")
-    ap.add_argument("--decode-loop", type=int, default=0,
-                    help="also run this many consecutive decode steps (append a token, drift the queries), with and "
+    ap.add_argument("--decode-loop", type=int, default=8,
+                    help="also run this many consecutive decode steps (append a token, drift the queries; 0 = skip), with and "
                          "without the previous step's blocks_read as depth hint")
     ap.add_argument("--cpu-layers", type=str, default="", help="layers the oracle is timed on")
     ap.add_argument("--host-tier", type=int, default=12,
@@ -577,6 +577,14 @@ def main():
         log(f"[bench] oracle on one thread: {t_one:.1f}s")
         del pb, sub
 
+    tier_leg = None
+    if args.host_tier > 0:
+        try:
+            tier_leg = host_tier_leg(psa, args, cfg, layers, metas, eps, m, tuning_kw, dev)
+        except Exception as exc:                      # e.g. no pinned memory to be had: the leg is an extra
+            tier_leg = {"error": f"{type(exc).__name__}: {exc}"}
+        log(f"[bench] host tier: {tier_leg}")
+
     # ---- consecutive decode steps: every step appends one token per request to every layer's cache
     # (K, V, metadata, length: psa_append_kv) and decodes with queries that drifted a little; the depth
     # hint of a step is what the same layer read in the step before -------------------------------------
@@ -622,14 +630,6 @@ def main():
                 loop[mode] = {"ms_per_step": e0.elapsed_time(e1) / n_steps,
                               "blocks_read_per_stream_mean_last_step": float(np.mean(read))}
         log(f"[bench] decode loop: {loop}")
-
-    tier_leg = None
-    if args.host_tier > 0:
-        try:
-            tier_leg = host_tier_leg(psa, args, cfg, layers, metas, eps, m, tuning_kw, dev)
-        except Exception as exc:                      # e.g. no pinned memory to be had: the leg is an extra
-            tier_leg = {"error": f"{type(exc).__name__}: {exc}"}
-        log(f"[bench] host tier: {tier_leg}")
 
     traffic = read_measured_traffic(cfg.name, dom)
 
