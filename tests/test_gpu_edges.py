@@ -130,3 +130,33 @@ def test_stream_read_probe_sizes_and_alignment(psa):
     assert torch.equal(buf, before)
     with pytest.raises(psa.PsaError):
         psa.stream_read_probe(buf[1:], sink)        # 4 bytes past a 16-byte boundary
+
+
+@pytest.mark.parametrize("bad", ["nan", "inf", "huge"])
+def test_non_finite_keys_do_not_disturb_other_requests(psa, bad):
+    """Keys that are NaN, infinite or as large as the type allows in one request: the call completes (every
+    loop of the kernels is bounded whatever the data), the other request's results are bit for bit those
+    of a clean run, and the damaged request still reports a block count within its range."""
+    cfg = get_config(1).scaled(batch=2, ctx=3000)
+    li = generate_layer(cfg, device="cuda")
+    clean = gc.run_gpu_decode(li, 0.9, 1)
+    val = {"nan": float("nan"), "inf": float("inf"), "huge": 65504.0}[bad]
+    pages = li.block_table[0, :188].long()
+    k = li.k_pool.clone()
+    k[pages[5], :, 3, :17] = val
+    k[pages[100], 2, :, 64] = -val if bad != "nan" else val
+    k[pages[187], :, 7, :] = val
+    li.k_pool.copy_(k)
+    kv = gc.to_kv(li)
+    meta = psa.build_block_metadata(kv, page_fill=li.page_fill)
+    out = psa.decode_attention(kv, li.q, meta, 0.9, 1, want_order=True)
+    dense, _ = psa.dense_attention(kv, li.q)
+    torch.cuda.synchronize()
+    assert psa.read_device_error(out._workspace) == 0
+    for name in ("out", "n_selected", "mass_est", "blocks_read", "lse"):
+        assert torch.equal(getattr(out, name)[1], getattr(clean, name)[1]), name
+    N0 = (int(li.ctx_lens[0]) + 15) // 16
+    assert int(out.n_selected[0].min()) >= 0 and int(out.n_selected[0].max()) <= N0
+    o = out.order[0, :, :N0].sort(dim=-1).values
+    assert torch.equal(o, torch.arange(N0, device="cuda", dtype=torch.int32).expand_as(o)), "ranking must stay a permutation"
+    assert torch.isfinite(dense[1]).all()
