@@ -63,3 +63,29 @@ def test_random_shapes_against_the_oracle(psa, seed):
 def test_near_tied_scores_at_the_stop(psa, kw, m):
     rep = _run(psa, get_config(1).scaled(**kw), 0, 0.99, m, None, 0)
     assert rep.set_tolerated >= 1
+
+
+def test_odd_head_counts_and_large_batches_of_tiny_requests(psa):
+    rng = np.random.default_rng(303)
+    for case in range(60):
+        idx = int(rng.choice([1, 2, 4, 5]))
+        G, H = int(rng.choice([1, 2, 4, 8])), int(rng.choice([3, 5, 6, 7, 12, 16]))
+        if rng.random() < 0.4:
+            batch, ctx = int(rng.integers(30, 200)), int(rng.integers(1, 120))
+        else:
+            batch, ctx = int(rng.integers(1, 4)), int(rng.integers(1, 6000))
+        kw = dict(batch=batch, ctx=ctx, num_q_heads=G * H, num_kv_heads=H, dtype=str(rng.choice(["f16", "bf16"])))
+        if idx == 4:
+            kw["ctx_min"] = int(rng.integers(1, ctx + 1))
+        cfg = get_config(idx).scaled(**kw)
+        eps, m = float(rng.choice([0.0, 0.5, 0.9, 0.95, 0.99, 1.0])), int(rng.choice([1, 1, 3, 8]))
+        tun = psa.Tuning(chunk_blocks=int(rng.choice([0, 8, 32, 64])), window_chunks=int(rng.choice([0, 1, 5])),
+                         spin_limit=int(rng.choice([0, 1])))
+        scorer = int(rng.choice([0, 1]))
+        print(f"case {case}: config {idx} {kw} eps {eps} m {m} tuning {tun.chunk_blocks}/{tun.window_chunks}/{tun.spin_limit} "
+              f"scorer {scorer}", flush=True)
+        li = generate_layer(cfg, device="cuda", poison_tail=True)
+        out = gc.run_gpu_decode(li, eps, m, tuning=tun, scorer=scorer)
+        reqs = None if batch <= 8 else sorted(rng.choice(batch, size=6, replace=False).tolist())
+        rep = gc.check_decode_against_oracle(gc.to_problem(li), out, eps, m, requests=reqs, scorer=scorer)
+        assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads
