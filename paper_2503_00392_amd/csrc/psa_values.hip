@@ -6,8 +6,8 @@
 // slices of the selected blocks -- every workgroup independent, no waiting, and only blocks
 // actually selected are read.
 //   attend_kernel    per value unit (chunk, stream) on the work list the selection kernel wrote:
-//                    p = exp(logit - chunk max), partial numerator sum_t p_t v_t per head, exp-sum and
-//                    reference maximum
+//                    p = exp(logit - chunk max), partial numerator sum_t p_t v_t per head (on the matrix
+//                    cores, the weights as a sum of two 16-bit halves), exp-sum and reference maximum
 //   finalize_kernel  merges a head's chunks (the online-softmax merge of line 11, all at once):
 //                    out_g = sum over the chunks of the head's own prefix of the partial numerators,
 //                    over the sum of the partial exp-sums, both rescaled to one reference maximum
@@ -18,13 +18,48 @@ namespace psa {
 
 constexpr int kBatch = 4;   // slices a wave keeps in flight
 
-template <int G>
+// D(16x16, fp32) += A(16x16) * B(16x16) on the matrix cores, 16-bit inputs.  Lane l supplies row l%16 of A
+// and column l%16 of B, k values 4*(l/16) .. +3 of each; it receives column l%16 of D, rows 4*(l/16) .. +3.
+typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+template <int DT>
+__device__ __forceinline__ f32x4_t mfma_16x16x16(const uint2 &a, const uint2 &b, f32x4_t c) {
+    if constexpr (DT == 0) {
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, a), __builtin_bit_cast(f16x4_t, b), c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a), __builtin_bit_cast(s16x4_t, b), c, 0, 0, 0);
+    }
+}
+
+// p = hi + lo with both halves in the 16-bit type of the cache (round to nearest each): the bits of the two.
+template <int DT>
+__device__ __forceinline__ void split16(float p, uint32_t &hi, uint32_t &lo) {
+    if constexpr (DT == 0) {
+        const _Float16 h = (_Float16)p;
+        const _Float16 l = (_Float16)(p - (float)h);
+        hi = __builtin_bit_cast(uint16_t, h);
+        lo = __builtin_bit_cast(uint16_t, l);
+    } else {
+        const uint32_t u = __float_as_uint(p);
+        hi = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+        const uint32_t w = __float_as_uint(p - __uint_as_float(hi << 16));
+        lo = (w + 0x7fffu + ((w >> 16) & 1u)) >> 16;
+    }
+}
+
+__device__ __forceinline__ uint32_t pick_word(const uint4 &v, int w) {
+    return w == 0 ? v.x : (w == 1 ? v.y : (w == 2 ? v.z : v.w));
+}
+
+// CBMAX: blocks per value unit at most (32 for the default chunk size and below, else 64): it sizes the LDS
+// arrays, and with them how many workgroups fit a CU.
+template <int G, int CBMAX>
 struct AttendShared {
-    float p[kMaxChunkBlocks][kPage][G];    // logits, then softmax numerators
+    float p[CBMAX][kPage][G];              // logits, then softmax numerators
     float st_acc[4][G][kHeadDim];          // per-wave partial numerators
     float red[256];
-    int page[kMaxChunkBlocks];
-    int valid[kMaxChunkBlocks];
+    int page[CBMAX];
+    int valid[CBMAX];
     int cnt[G];
     float Mref[G];
     float lsum[G];
@@ -37,8 +72,8 @@ __device__ __forceinline__ int head_stop(const StreamCtl *ctl, int g, int N) {
 }
 
 // One value unit: chunk c of stream s.  Called by all 256 threads of a workgroup.
-template <int DT, int G>
-__device__ void attend_unit(AttendShared<G> &sh, const KvView &kv, const DecodeWs &ws, int CB, int s, int c) {
+template <int DT, int G, int CBMAX>
+__device__ void attend_unit(AttendShared<G, CBMAX> &sh, const KvView &kv, const DecodeWs &ws, int CB, int s, int c) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, rg = lane >> 4, cl = lane & 15;
     const int h = s % kv.num_kv_heads;
     int ctx = kv.ctx_lens[s / kv.num_kv_heads];
@@ -109,11 +144,15 @@ __device__ void attend_unit(AttendShared<G> &sh, const KvView &kv, const DecodeW
         sh.lsum[tid] = l;
     }
 
-    float acc[G][8];
+    // Numerators on the matrix cores: per block D[head][channel] += P[head][token] V[token][channel] as eight
+    // 16x16x16 products (one per channel of the lane's eight) with the softmax weights split into two
+    // 16-bit halves (hi + lo keeps fp32 accuracy; the values are 16-bit already).  The k index of both
+    // operands is the token: lane (rg, *) holds tokens rg, 4+rg, 8+rg, 12+rg -- exactly the rows its four
+    // loads fetched -- so the B operand is four 16-bit picks from registers, no transposition.  A: row =
+    // head lane%16 (zero beyond G).  D: lane (rg, cl) gets heads 4rg..4rg+3 of channel 8cl + tile.
+    f32x4_t acc[8];
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int x = 0; x < 8; ++x) acc[g][x] = 0.0f;
+    for (int t = 0; t < 8; ++t) acc[t] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
     for (int i0 = wave * kBatch; i0 < maxcnt; i0 += 4 * kBatch) {
         if (i0 != wave * kBatch) {
 #pragma unroll
@@ -128,39 +167,33 @@ __device__ void attend_unit(AttendShared<G> &sh, const KvView &kv, const DecodeW
             const int i = i0 + u;
             if (i < maxcnt) {
                 if (sh.valid[i] < kPage) zero_invalid_rows(v[u], rg, sh.valid[i]);
+                uint32_t hi[4], lo[4];
 #pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    float vf[8];
-                    vf[0] = cvt_lo<DT>(v[u].r[x].x); vf[1] = cvt_hi<DT>(v[u].r[x].x);
-                    vf[2] = cvt_lo<DT>(v[u].r[x].y); vf[3] = cvt_hi<DT>(v[u].r[x].y);
-                    vf[4] = cvt_lo<DT>(v[u].r[x].z); vf[5] = cvt_hi<DT>(v[u].r[x].z);
-                    vf[6] = cvt_lo<DT>(v[u].r[x].w); vf[7] = cvt_hi<DT>(v[u].r[x].w);
-                    const float *pp = sh.p[i][4 * x + rg];
+                for (int j = 0; j < 4; ++j) {
+                    const float pj = cl < G ? sh.p[i][4 * j + rg][cl] : 0.0f;
+                    split16<DT>(pj, hi[j], lo[j]);
+                }
+                const uint2 a_hi = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
+                const uint2 a_lo = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
 #pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        const float p = pp[g];
-#pragma unroll
-                        for (int y = 0; y < 8; ++y) acc[g][y] = fmaf(p, vf[y], acc[g][y]);
-                    }
+                for (int t = 0; t < 8; ++t) {
+                    const uint32_t w0 = pick_word(v[u].r[0], t >> 1), w1 = pick_word(v[u].r[1], t >> 1);
+                    const uint32_t w2 = pick_word(v[u].r[2], t >> 1), w3 = pick_word(v[u].r[3], t >> 1);
+                    const uint2 b = (t & 1) ? make_uint2((w0 >> 16) | (w1 & 0xffff0000u), (w2 >> 16) | (w3 & 0xffff0000u))
+                                            : make_uint2((w0 & 0xffffu) | (w1 << 16), (w2 & 0xffffu) | (w3 << 16));
+                    acc[t] = mfma_16x16x16<DT>(a_hi, b, acc[t]);
+                    acc[t] = mfma_16x16x16<DT>(a_lo, b, acc[t]);
                 }
             }
         }
     }
-    // sum the 4 row groups of the wave, then the 4 waves
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+    for (int r = 0; r < 4; ++r) {
+        const int g = 4 * rg + r;
+        if (g < G) {
 #pragma unroll
-        for (int x = 0; x < 8; ++x) {
-            float a = acc[g][x];
-            a += __shfl_xor(a, 16);
-            a += __shfl_xor(a, 32);
-            acc[g][x] = a;
+            for (int t = 0; t < 8; ++t) sh.st_acc[wave][g][cl * 8 + t] = acc[t][r];
         }
-    if (rg == 0) {
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int x = 0; x < 8; ++x) sh.st_acc[wave][g][cl * 8 + x] = acc[g][x];
     }
     lds_barrier();
     float *dst = ws.partial + ((size_t)s * ws.max_units + c) * G * kPartialStride;
@@ -174,12 +207,12 @@ __device__ void attend_unit(AttendShared<G> &sh, const KvView &kv, const DecodeW
 
 // One workgroup per entry of the work list the selection kernel left; the grid is sized for the most
 // there can be, and a workgroup beyond the list's end returns after one load.
-template <int DT, int G>
+template <int DT, int G, int CBMAX>
 __global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int CB) {
-    __shared__ AttendShared<G> sh;
+    __shared__ AttendShared<G, CBMAX> sh;
     if ((int)blockIdx.x >= ws.header[kValueCount]) return;
     const int item = ws.value_items[blockIdx.x];
-    attend_unit<DT, G>(sh, kv, ws, CB, item / ws.max_chunks, item % ws.max_chunks);
+    attend_unit<DT, G, CBMAX>(sh, kv, ws, CB, item / ws.max_chunks, item % ws.max_chunks);
 }
 
 constexpr int kUnitLanes = 16;   // value units merged side by side by one workgroup
@@ -285,7 +318,10 @@ __global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, i
 template <int DT, int G>
 static hipError_t launch_attend_t(const KvView &kv, const DecodeWs &ws, const DecodePlan &plan, hipStream_t st) {
     const unsigned grid = (unsigned)(kv.batch * kv.num_kv_heads) * (unsigned)plan.max_chunks;
-    attend_kernel<DT, G><<<grid, 256, 0, st>>>(kv, ws, plan.chunk_blocks);
+    if (plan.chunk_blocks <= 32)
+        attend_kernel<DT, G, 32><<<grid, 256, 0, st>>>(kv, ws, plan.chunk_blocks);
+    else
+        attend_kernel<DT, G, kMaxChunkBlocks><<<grid, 256, 0, st>>>(kv, ws, plan.chunk_blocks);
     return hipGetLastError();
 }
 
