@@ -1,5 +1,6 @@
-// Per-block building blocks shared by the dense control kernel and the progressive kernel:
-// how one wave reads a 4 KiB (page, KV head) slice and what each lane holds.
+// Per-block building blocks shared by the dense control kernel, the value pass and the metadata kernel:
+// how one wave reads a 4 KiB (page, KV head) slice and what each lane holds, and the 16x16x16 matrix
+// product with 16-bit operands that both attention kernels accumulate values with.
 //
 // Lane layout of a wave over one K or V slice [16 tokens][128 channels] of 2-byte elements:
 //   rg = lane / 16  (row group 0..3),  cl = lane % 16  (channel slot: channels 8*cl .. 8*cl+7)
@@ -23,62 +24,44 @@ __device__ __forceinline__ Slice load_slice(const uint8_t *slice_base, int lane)
     return s;
 }
 
-// Query of head g as this lane sees it: the 8 channels of its channel slot, packed in pairs.
-template <int G>
-struct QueryRegs {
-    uint32_t w[G][4];
-};
-
-template <int G>
-__device__ __forceinline__ QueryRegs<G> load_query(const uint8_t *q, int r, int h, int num_q_heads,
-                                                   int cl) {
-    QueryRegs<G> out;
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        uint4 t = ld16(q + ((size_t)(r * num_q_heads + h * G + g) * kHeadDim + cl * 8) * 2);
-        out.w[g][0] = t.x; out.w[g][1] = t.y; out.w[g][2] = t.z; out.w[g][3] = t.w;
-    }
-    return out;
-}
-
-// Scaled logits (log2 units) of token rows 4*i + rg for i = 0..3 and every head of the group.
-// Rows at or beyond `valid` get -inf.  Every lane of a row group ends up with the same values.
-template <int DT, int G>
-__device__ __forceinline__ void slice_logits(const Slice &k, const QueryRegs<G> &q, int rg, int valid,
-                                             float (&s)[4][G]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const bool ok = (4 * i + rg) < valid;
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float p = dot2<DT>(k.r[i].x, q.w[g][0], 0.0f);
-            p = dot2<DT>(k.r[i].y, q.w[g][1], p);
-            p = dot2<DT>(k.r[i].z, q.w[g][2], p);
-            p = dot2<DT>(k.r[i].w, q.w[g][3], p);
-            p = row_sum16(p);
-            s[i][g] = ok ? p * kScaleLog2 : -INFINITY;
-        }
-    }
-}
-
-// acc[c] += p * v[c] for the lane's 8 channels of one token row.
-template <int DT>
-__device__ __forceinline__ void axpy_row(const uint4 &v, float p, float (&acc)[8]) {
-    acc[0] = fmaf(p, cvt_lo<DT>(v.x), acc[0]);
-    acc[1] = fmaf(p, cvt_hi<DT>(v.x), acc[1]);
-    acc[2] = fmaf(p, cvt_lo<DT>(v.y), acc[2]);
-    acc[3] = fmaf(p, cvt_hi<DT>(v.y), acc[3]);
-    acc[4] = fmaf(p, cvt_lo<DT>(v.z), acc[4]);
-    acc[5] = fmaf(p, cvt_hi<DT>(v.z), acc[5]);
-    acc[6] = fmaf(p, cvt_lo<DT>(v.w), acc[6]);
-    acc[7] = fmaf(p, cvt_hi<DT>(v.w), acc[7]);
-}
-
 // Rows of a partly filled block beyond `valid` may hold anything (NaN included): make them zero.
 __device__ __forceinline__ void zero_invalid_rows(Slice &v, int rg, int valid) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
         if (4 * i + rg >= valid) v.r[i] = make_uint4(0, 0, 0, 0);
+}
+
+// D(16x16, fp32) += A(16x16) * B(16x16) on the matrix cores, 16-bit inputs.  Lane l supplies row l%16 of A
+// and column l%16 of B, k values 4*(l/16) .. +3 of each; it receives column l%16 of D, rows 4*(l/16) .. +3.
+typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+template <int DT>
+__device__ __forceinline__ f32x4_t mfma_16x16x16(const uint2 &a, const uint2 &b, f32x4_t c) {
+    if constexpr (DT == 0) {
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, a), __builtin_bit_cast(f16x4_t, b), c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a), __builtin_bit_cast(s16x4_t, b), c, 0, 0, 0);
+    }
+}
+
+// p = hi + lo with both halves in the 16-bit type of the cache (round to nearest each): the bits of the two.
+template <int DT>
+__device__ __forceinline__ void split16(float p, uint32_t &hi, uint32_t &lo) {
+    if constexpr (DT == 0) {
+        const _Float16 h = (_Float16)p;
+        const _Float16 l = (_Float16)(p - (float)h);
+        hi = __builtin_bit_cast(uint16_t, h);
+        lo = __builtin_bit_cast(uint16_t, l);
+    } else {
+        const uint32_t u = __float_as_uint(p);
+        hi = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+        const uint32_t w = __float_as_uint(p - __uint_as_float(hi << 16));
+        lo = (w + 0x7fffu + ((w >> 16) & 1u)) >> 16;
+    }
+}
+
+__device__ __forceinline__ uint32_t pick_word(const uint4 &v, int w) {
+    return w == 0 ? v.x : (w == 1 ? v.y : (w == 2 ? v.z : v.w));
 }
 
 }  // namespace psa

@@ -7,17 +7,16 @@ namespace psa {
 
 constexpr int kDenseStride = 132;  // M, l, pad, pad, acc[128]
 
-template <int DT>
-__device__ __forceinline__ void row_to_float(const uint4 &v, float (&f)[8]) {
-    f[0] = cvt_lo<DT>(v.x); f[1] = cvt_hi<DT>(v.x);
-    f[2] = cvt_lo<DT>(v.y); f[3] = cvt_hi<DT>(v.y);
-    f[4] = cvt_lo<DT>(v.z); f[5] = cvt_hi<DT>(v.z);
-    f[6] = cvt_lo<DT>(v.w); f[7] = cvt_hi<DT>(v.w);
-}
-
-// grid (nsplit, S); 256 threads.  Wave w of the workgroup takes blocks b0+w, b0+w+4, ...; every
-// 16-lane row group keeps its own running (m, l, acc) over the token rows it sees, so the loop has
-// no cross-row-group traffic; the 16 states of a workgroup are merged once at the end.
+// grid (nsplit, S); 256 threads.  Wave w of the workgroup takes blocks b0+w, b0+w+4, ... and carries its own
+// online softmax over them, both products on the matrix cores:
+//   logits  D[token][head] = K[token][channel] Q[channel][head]: four 16x16x32 steps.  Row r of the A operand
+//           stands for token 4*(r%4) + r/4, so that lane (kq, n) = (lane/16, lane%16) ends up with the logits
+//           of head n for tokens kq, 4+kq, 8+kq, 12+kq -- the token rows its value loads fetch;
+//   values  D[head][channel] += P[head][token] V[token][channel]: eight 16x16x16 products per block (one per
+//           channel of the lane's eight), the weights split into two 16-bit halves; lane (kq, cl) accumulates
+//           heads 4kq..4kq+3 of channels 8cl..8cl+7.
+// The running maximum of a head is shared by the wave (two exchanges per block); the four waves are merged
+// once at the end.
 template <int DT, int G>
 __global__ __launch_bounds__(256) void dense_split_kernel(KvView kv, const uint8_t *__restrict__ q,
                                                           float *__restrict__ partial,
@@ -32,81 +31,84 @@ __global__ __launch_bounds__(256) void dense_split_kernel(KvView kv, const uint8
     const int b0 = split * bps;
     const int b1 = min(N, b0 + bps);
 
-    const QueryRegs<G> qr = load_query<G>(q, r, h, kv.num_q_heads, cl);
-    float m[G], l[G], acc[G][8];
+    // B operand of the logits: column cl = head cl (zero beyond the group), channels 8*(4kk + rg) .. +7 in step kk
+    uint4 qb[4];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        m[g] = -INFINITY; l[g] = 0.0f;
-#pragma unroll
-        for (int c = 0; c < 8; ++c) acc[g][c] = 0.0f;
+    for (int kk = 0; kk < 4; ++kk) {
+        qb[kk] = make_uint4(0, 0, 0, 0);
+        if (cl < G) qb[kk] = ld16(q + ((size_t)(r * kv.num_q_heads + h * G + cl) * kHeadDim + (4 * kk + rg) * 8) * 2);
     }
+    const int row_token = 4 * (cl & 3) + (cl >> 2);      // the token this lane's row of the A operand stands for
+    float m = -INFINITY, l = 0.0f;                       // head cl: running maximum (whole wave), exp-sum (this row group)
+    f32x4_t acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 
     const int32_t *table = kv.block_table + (size_t)r * kv.max_blocks;
     for (int b = b0 + wave; b < b1; b += 4) {
         const int page = clamp_page(table[b], kv.num_pages, header);
         const size_t off = ((size_t)page * kv.num_kv_heads + h) * kSliceBytes;
-        Slice k = load_slice(kv.k_pool + off, lane);
+        const uint8_t *kp = kv.k_pool + off + row_token * kRowBytes + rg * 16;
+        uint4 ka[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) ka[kk] = ld16(kp + kk * 64);
         Slice v = load_slice(kv.v_pool + off, lane);
         const int valid = min(kPage, ctx - b * kPage);
-        float sc[4][G];
-        slice_logits<DT, G>(k, qr, rg, valid, sc);
+        f32x4_t s4 = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) s4 = mfma_16x16x32<DT>(ka[kk], qb[kk], s4);
+        float sc[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sc[j] = (4 * j + rg < valid) ? s4[j] * kScaleLog2 : -INFINITY;
         if (valid < kPage) zero_invalid_rows(v, rg, valid);
-        float vf[4][8];
+        float bm = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+        bm = fmaxf(bm, __shfl_xor(bm, 16));
+        bm = fmaxf(bm, __shfl_xor(bm, 32));
+        const float mn = fmaxf(m, bm);                   // finite: every block below N has a valid token
+        const float alpha = exp2_fast(m - mn);
+        float p[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) row_to_float<DT>(v.r[i], vf[i]);
+        for (int j = 0; j < 4; ++j) p[j] = exp2_fast(sc[j] - mn);
+        l = l * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+        m = mn;
+        // the accumulators hold heads 4rg .. 4rg+3: rescale each by its head's factor (held by lane = head)
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float mn = fmaxf(fmaxf(fmaxf(sc[0][g], sc[1][g]), fmaxf(sc[2][g], sc[3][g])), m[g]);
-            if (mn == -INFINITY) continue;   // this row group has seen no valid token yet
-            const float alpha = exp2_fast(m[g] - mn);
-            float p[4];
+        for (int x = 0; x < 4; ++x) {
+            const float ax = __shfl(alpha, 4 * rg + x);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) p[i] = exp2_fast(sc[i][g] - mn);
-            l[g] = l[g] * alpha + ((p[0] + p[1]) + (p[2] + p[3]));
+            for (int t = 0; t < 8; ++t) acc[t][x] *= ax;
+        }
+        uint32_t hi[4], lo[4];
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                float a = acc[g][c] * alpha;
-                a = fmaf(p[0], vf[0][c], a);
-                a = fmaf(p[1], vf[1][c], a);
-                a = fmaf(p[2], vf[2][c], a);
-                a = fmaf(p[3], vf[3][c], a);
-                acc[g][c] = a;
-            }
-            m[g] = mn;
+        for (int j = 0; j < 4; ++j) split16<DT>(p[j], hi[j], lo[j]);
+        const uint2 a_hi = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
+        const uint2 a_lo = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const uint32_t w0 = pick_word(v.r[0], t >> 1), w1 = pick_word(v.r[1], t >> 1);
+            const uint32_t w2 = pick_word(v.r[2], t >> 1), w3 = pick_word(v.r[3], t >> 1);
+            const uint2 bv = (t & 1) ? make_uint2((w0 >> 16) | (w1 & 0xffff0000u), (w2 >> 16) | (w3 & 0xffff0000u))
+                                     : make_uint2((w0 & 0xffffu) | (w1 << 16), (w2 & 0xffffu) | (w3 << 16));
+            acc[t] = mfma_16x16x16<DT>(a_hi, bv, acc[t]);
+            acc[t] = mfma_16x16x16<DT>(a_lo, bv, acc[t]);
         }
     }
-
-    // merge the 4 row groups of the wave (lanes l, l^16, l^32, l^48 hold the same channel slot)
-#pragma unroll
-    for (int step = 16; step <= 32; step <<= 1) {
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float mo = __shfl_xor(m[g], step);
-            const float lo = __shfl_xor(l[g], step);
-            const float mn = fmaxf(m[g], mo);
-            const float a = (mn == -INFINITY) ? 0.0f : exp2_fast(m[g] - mn);
-            const float bsc = (mn == -INFINITY) ? 0.0f : exp2_fast(mo - mn);
-            l[g] = l[g] * a + lo * bsc;
-#pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                const float ao = __shfl_xor(acc[g][c], step);
-                acc[g][c] = acc[g][c] * a + ao * bsc;
-            }
-            m[g] = mn;
-        }
-    }
+    // the exp-sum over the four row groups
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
 
     // merge the 4 waves through LDS
     __shared__ float st_acc[4][G][kHeadDim];
     __shared__ float st_m[4][G], st_l[4][G];
-    if (rg == 0) {
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
+    for (int x = 0; x < 4; ++x) {
+        const int g = 4 * rg + x;
+        if (g < G) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c) st_acc[wave][g][cl * 8 + c] = acc[g][c];
-            if (cl == 0) { st_m[wave][g] = m[g]; st_l[wave][g] = l[g]; }
+            for (int t = 0; t < 8; ++t) st_acc[wave][g][cl * 8 + t] = acc[t][x];
         }
     }
+    if (rg == 0 && cl < G) { st_m[wave][cl] = m; st_l[wave][cl] = l; }
     __syncthreads();
     float *dst = partial + ((size_t)s * nsplit + split) * G * kDenseStride;
     for (int idx = tid; idx < G * kHeadDim; idx += 256) {

@@ -18,39 +18,6 @@ namespace psa {
 
 constexpr int kBatch = 4;   // slices a wave keeps in flight
 
-// D(16x16, fp32) += A(16x16) * B(16x16) on the matrix cores, 16-bit inputs.  Lane l supplies row l%16 of A
-// and column l%16 of B, k values 4*(l/16) .. +3 of each; it receives column l%16 of D, rows 4*(l/16) .. +3.
-typedef _Float16 f16x4_t __attribute__((ext_vector_type(4)));
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-template <int DT>
-__device__ __forceinline__ f32x4_t mfma_16x16x16(const uint2 &a, const uint2 &b, f32x4_t c) {
-    if constexpr (DT == 0) {
-        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4_t, a), __builtin_bit_cast(f16x4_t, b), c, 0, 0, 0);
-    } else {
-        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a), __builtin_bit_cast(s16x4_t, b), c, 0, 0, 0);
-    }
-}
-
-// p = hi + lo with both halves in the 16-bit type of the cache (round to nearest each): the bits of the two.
-template <int DT>
-__device__ __forceinline__ void split16(float p, uint32_t &hi, uint32_t &lo) {
-    if constexpr (DT == 0) {
-        const _Float16 h = (_Float16)p;
-        const _Float16 l = (_Float16)(p - (float)h);
-        hi = __builtin_bit_cast(uint16_t, h);
-        lo = __builtin_bit_cast(uint16_t, l);
-    } else {
-        const uint32_t u = __float_as_uint(p);
-        hi = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-        const uint32_t w = __float_as_uint(p - __uint_as_float(hi << 16));
-        lo = (w + 0x7fffu + ((w >> 16) & 1u)) >> 16;
-    }
-}
-
-__device__ __forceinline__ uint32_t pick_word(const uint4 &v, int w) {
-    return w == 0 ? v.x : (w == 1 ? v.y : (w == 2 ? v.z : v.w));
-}
-
 // CBMAX: blocks per value unit at most (32 for the default chunk size and below, else 64): it sizes the LDS
 // arrays, and with them how many workgroups fit a CU.
 template <int G, int CBMAX>
