@@ -19,11 +19,27 @@ def psa():
     return psa
 
 
+def _dense_check(psa, li, pb, requests=None):
+    from oracle import psa_oracle as po
+    out, lse = psa.dense_attention(gc.to_kv(li), li.q)
+    torch.cuda.synchronize()
+    assert psa.read_device_error(out._workspace) == 0
+    if requests is not None:
+        pb = po.Problem(pb.q[requests], pb.k_pool, pb.v_pool, pb.block_table[requests], pb.ctx_lens[requests], pb.dtype)
+        out, lse = out[requests], lse[requests]
+    want, wlse = po.dense_attention(pb)
+    err = gc.rel_l2(out.cpu().numpy().astype(np.float64), want)
+    assert err.max(initial=0.0) <= gc.OUT_RTOL, err.max()
+    np.testing.assert_allclose(lse.cpu().numpy(), wlse, rtol=0, atol=2e-3)
+
+
 def _run(psa, cfg, layer, eps, m, tun, scorer):
     li = generate_layer(cfg, layer=layer, device="cuda", poison_tail=True)
     out = gc.run_gpu_decode(li, eps, m, tuning=tun, scorer=scorer)
-    rep = gc.check_decode_against_oracle(gc.to_problem(li), out, eps, m, scorer=scorer)
+    pb = gc.to_problem(li)
+    rep = gc.check_decode_against_oracle(pb, out, eps, m, scorer=scorer)
     assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads
+    _dense_check(psa, li, pb)
     return rep
 
 
@@ -87,5 +103,7 @@ def test_odd_head_counts_and_large_batches_of_tiny_requests(psa):
         li = generate_layer(cfg, device="cuda", poison_tail=True)
         out = gc.run_gpu_decode(li, eps, m, tuning=tun, scorer=scorer)
         reqs = None if batch <= 8 else sorted(rng.choice(batch, size=6, replace=False).tolist())
-        rep = gc.check_decode_against_oracle(gc.to_problem(li), out, eps, m, requests=reqs, scorer=scorer)
+        pb = gc.to_problem(li)
+        rep = gc.check_decode_against_oracle(pb, out, eps, m, requests=reqs, scorer=scorer)
         assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads
+        _dense_check(psa, li, pb, reqs)
