@@ -7,9 +7,11 @@
  * a threshold (Algorithm 1, Sec. 3.2).
  *
  * Conventions common to every call
- *   - Every pointer is a DEVICE pointer unless its comment says "host".
+ *   - Every pointer is a DEVICE pointer unless its comment says "host" (with a second tier the KV
+ *     pools are host memory the GPU can address, see psa_tier).
  *   - The caller owns every buffer, the workspace included.  The library allocates no device
- *     memory and keeps no state between calls; calls on distinct streams with distinct workspaces
+ *     memory and keeps no state between calls (the optional second tier keeps its tables in a
+ *     buffer the caller owns, psa_tier.state); calls on distinct streams with distinct workspaces
  *     may overlap, calls sharing a workspace must be ordered by the stream.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   - Calls validate their arguments on the host, enqueue kernels and return.  No call
