@@ -652,6 +652,8 @@ def main():
         "whole_path": {"algorithmic_bytes_per_step": alg_bytes, "GBps": eff_gbs, "hbm_frac": eff_gbs / HBM_PEAK_GBS,
                        "frac_of_read_ceiling": eff_gbs / ceiling_gbs,
                        "speculative_k_bytes_per_step": spec_k_bytes,
+                       "GBps_with_speculative_reads": (alg_bytes + spec_k_bytes) / (ms_per_step * 1e-3) / 1e9,
+                       "hbm_frac_with_speculative_reads": (alg_bytes + spec_k_bytes) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "kv_reduction_vs_dense": kv_reduction,
                        "mean_selected_fraction": float((blocks_read / np.maximum(N_total, 1)).mean()),
                        "phase_avg_ms_per_layer": phase_avg,
