@@ -337,30 +337,31 @@ void oracle_attend_prefix(const oracle_shape *sh, const uint16_t *q, const uint1
     }
 }
 
-/* ---------- the progressive loop (Algorithm 1) ------------------------------------------------ */
+/* ---------- the progressive loop (Algorithm 1, lines 7-19; Sec. 3.2) ------------------------------ */
 /*
- * For every query head on its own (Sec. 3.2, batched form: a query leaves once it is past the
- * threshold), over the ranking of its KV head:
+ * Every query head is walked on its own over the ranking of its KV head (Sec. 3.2, batched form: a
+ * query drops out as soon as it has passed the threshold).  The head keeps four things while it
+ * consumes blocks in ranked order: the attention output over the blocks consumed so far, the sum of
+ * their weights, the smallest weight any single consumed block had, and the count of blocks not yet
+ * consumed.  A block's "weight" AS is the sum over its valid tokens of exp(scaled logit); its own
+ * output O is softmax attention inside the block.  Consuming a block merges O into the running output
+ * in proportion to the two weights, adds AS to the running sum, and lowers the minimum if AS is
+ * smaller.  The share of the total attention already covered is then estimated by pretending that
+ * every block still unread weighs as much as the lightest one seen:
+ *     P_acc = AS_acc / (AS_acc + AS_min * N_left),
+ * and the head stops at the first tested position where P_acc exceeds eps.
  *
- *   O_acc <- 0, AS_acc <- 0, AS_min <- +inf, N_left <- N                    (lines 2-4, 7)
- *   for each block b in ranked order:                                        (line 8)
- *     O, AS <- Attention(q, KV_b)                                            (line 10)
- *     O_acc <- (AS_acc*O_acc + AS*O) / (AS_acc + AS);  AS_acc += AS          (lines 11-12)
- *     AS_min <- min(AS, AS_min);  N_left -= 1                                (lines 13-14)
- *     AS_total = AS_acc + AS_min*N_left;  P_acc = AS_acc / AS_total          (lines 15-16)
- *     if P_acc > eps: break                                                  (lines 17-18)
- *
- * AS is the block's sum of exponentiated scaled logits (Sec. 3.2: "the accumulated sum of the
- * exponentiation of attention scores"), O the block's own softmax output.  Only ratios of AS
- * values enter any result, so every exponent is taken relative to one per-head constant s_ref
- * (the head's largest logit), which keeps exp() inside double range without changing a ratio.
+ * Only ratios of weights enter any result, so every exponent is taken relative to one per-head
+ * constant s_ref (the head's largest logit): exp() stays inside double range, no ratio changes.
  *
  * Readings of open points:
- *   - microbatch m (Sec. 3.2): the test of line 17 is made only after every m-th block, and after
- *     the last block; AS_min and N_left stay per block ("minimum block-level attention score").
- *   - the comparison is strict, as line 17 prints it; so eps = 1 never breaks.
- *   - the comparison is taken in binary32, the precision the GPU kernel decides in:
- *     (float)P_acc > (float)eps.
+ *   - microbatch m (Sec. 3.2): the test is made only after every m-th block and after the last
+ *     block; the minimum stays a per-block quantity and N_left counts blocks.
+ *   - the comparison is strict, as Algorithm 1 prints it; so eps = 1 never stops early.
+ *   - the comparison is taken in binary32: (float)P_acc > (float)eps.  The threshold crosses the C
+ *     ABI as a float, so eps is a binary32 number to begin with; P_acc is rounded to the same type so
+ *     that "exceeds" means the same thing on both sides of a parity test when P_acc and eps agree to
+ *     more digits than binary32 holds (only there can the rounding decide).
  *   - a partly filled last block takes part like any other, with its valid tokens only.
  *
  * Outputs: out [batch][num_q_heads][head_dim]; n_selected, mass_est [batch][num_q_heads];
@@ -410,7 +411,7 @@ void oracle_psa_decode(const oracle_shape *sh, const uint16_t *q, const uint16_t
                 const int page = block_table[(size_t)r * sh->max_blocks + b];
                 const int valid = valid_tokens(ctx, T, b);
                 const uint16_t *vb = v_pool + ((size_t)page * H + h) * T * D;
-                /* line 10: the block's own attention */
+                /* the block's own attention: weight AS and output O */
                 double AS = 0.0;
                 for (int t = 0; t < valid; ++t) AS += exp(s[(size_t)b * T + t] - s_ref);
                 for (int c = 0; c < D; ++c) O[c] = 0.0;
@@ -419,11 +420,11 @@ void oracle_psa_decode(const oracle_shape *sh, const uint16_t *q, const uint16_t
                         double p = exp(s[(size_t)b * T + t] - s_ref) / AS;
                         for (int c = 0; c < D; ++c) O[c] += p * decode(vb[(size_t)t * D + c], sh->dtype);
                     }
-                /* lines 11-12 (only while this head has not stopped: its output is frozen after) */
+                /* merge (only while this head has not stopped: its output is frozen after) */
                 if (!stopped && AS_acc + AS > 0.0)
                     for (int c = 0; c < D; ++c) O_acc[c] = (AS_acc * O_acc[c] + AS * O[c]) / (AS_acc + AS);
                 AS_acc += AS;
-                /* lines 13-16 */
+                /* lightest block so far, blocks left, estimated share */
                 if (AS < AS_min) AS_min = AS;
                 N_left -= 1;
                 double AS_total = AS_acc + AS_min * (double)N_left;
@@ -431,7 +432,7 @@ void oracle_psa_decode(const oracle_shape *sh, const uint16_t *q, const uint16_t
                 if (p_acc_curve) p_acc_curve[qi * sh->max_blocks + (n - 1)] = P_acc;
                 if (true_mass_curve) true_mass_curve[qi * sh->max_blocks + (n - 1)] = AS_acc; /* scaled below */
                 if (as_curve) as_curve[qi * sh->max_blocks + (n - 1)] = log(AS) + s_ref;
-                /* lines 17-18, tested once per microbatch of m blocks and at the end */
+                /* the stop test, once per microbatch of m blocks and at the end */
                 if (!stopped && (n % m == 0 || n == N)) {
                     if ((float)P_acc > (float)eps || n == N) {
                         stopped = 1;

@@ -10,10 +10,13 @@ import torch
 from oracle import psa_oracle as po
 from workloads import LayerInputs, as_bits
 
-OUT_RTOL = 2e-3        # relative L2 error of an output row, fp16/bf16 inputs, fp32 accumulation
+OUT_RTOL = 2e-3        # error of an output row (fp16/bf16 inputs, fp32 accumulation): relative L2, and
+                       # element-wise max |delta| against max |row|
 SCORE_ATOL = 1e-3      # score distance to the stopping boundary inside which a block may differ
 LSE_ATOL = 2e-3        # natural-log units, on values of order 10
 PACC_ATOL = 1e-5       # |P_acc - eps| inside which the stop index itself may flip
+SCORE_ERR = 2.5e-4     # largest error of a GPU score (binary32 dot products) against the oracle's; also the
+                       # largest score gap between two blocks the two rankings may order differently
 
 
 def to_problem(li: LayerInputs) -> po.Problem:
@@ -35,20 +38,64 @@ def rel_l2(a: np.ndarray, b: np.ndarray) -> np.ndarray:
 
 @dataclass
 class ParityReport:
+    """Every query head lands in exactly one class:
+    set_equal        same stop, same selected blocks;
+    set_tolerated    same stop, and the blocks that differ all score within SCORE_ATOL of the boundary;
+    rank_swap_stops  stops differ because binary32 and binary64 scoring order two near-equal blocks differently
+                     at or before the stop (the swap moves AS_min): the stop equals Algorithm 1 run by the oracle
+                     over the GPU's own ranking, and the swapped blocks' scores agree within the score error;
+    stop_flips       stops differ with the oracle's P_acc within PACC_ATOL of eps at the earlier stop;
+    empty            heads of requests without tokens."""
     heads: int = 0
     set_equal: int = 0
-    set_tolerated: int = 0        # sets differ only by blocks within SCORE_ATOL of the boundary
-    stop_flips: int = 0           # stop index differs with the oracle's P_acc within PACC_ATOL of eps
+    set_tolerated: int = 0
+    rank_swap_stops: int = 0
+    stop_flips: int = 0
+    empty: int = 0
+    swap_blocks_outside_boundary: int = 0   # blocks of rank-swap heads' set difference further than SCORE_ATOL from the
+                                            # boundary score (reported, not a failure: see rank_swap_stops)
+    worst_swap_gap: float = 0.0             # largest oracle-score gap between two blocks the rankings swap
     worst_out: float = 0.0
+    worst_out_elem: float = 0.0             # max |delta| / max |row|, against the oracle's output (equal sets)
     worst_out_vs_own_set: float = 0.0
+    worst_out_elem_vs_own_set: float = 0.0
     worst_score: float = 0.0
     worst_mass: float = 0.0
 
     def __str__(self):
         return (f"heads={self.heads} set_equal={self.set_equal} tolerated={self.set_tolerated} "
-                f"stop_flips={self.stop_flips} worst_out={self.worst_out:.2e} "
+                f"rank_swap_stops={self.rank_swap_stops} (blocks outside the boundary {self.swap_blocks_outside_boundary}, "
+                f"worst swapped-score gap {self.worst_swap_gap:.1e}) stop_flips={self.stop_flips} empty={self.empty} "
+                f"worst_out={self.worst_out:.2e} worst_out_elem={self.worst_out_elem:.2e} "
                 f"worst_out_vs_own_set={self.worst_out_vs_own_set:.2e} "
+                f"worst_out_elem_vs_own_set={self.worst_out_elem_vs_own_set:.2e} "
                 f"worst_score_err={self.worst_score:.2e} worst_mass_err={self.worst_mass:.2e}")
+
+    def assert_accounted(self, max_rank_swaps=None, max_stop_flips=None):
+        """Every head is in one class, and the two near-boundary classes stay exceptions: at most one head in 200
+        may stop elsewhere through a rank swap, at most one in 50 (one at least) through P_acc sitting on eps."""
+        assert self.set_equal + self.set_tolerated + self.rank_swap_stops + self.stop_flips + self.empty == self.heads, str(self)
+        if max_rank_swaps is None:
+            max_rank_swaps = self.heads // 200
+        if max_stop_flips is None:
+            max_stop_flips = max(1, self.heads // 50)
+        assert self.rank_swap_stops <= max_rank_swaps, f"rank-swap stops {self.rank_swap_stops} > {max_rank_swaps}: {self}"
+        assert self.stop_flips <= max_stop_flips, f"stop flips {self.stop_flips} > {max_stop_flips}: {self}"
+
+    def add(self, o: "ParityReport"):
+        for f in ("heads", "set_equal", "set_tolerated", "rank_swap_stops", "stop_flips", "empty",
+                  "swap_blocks_outside_boundary"):
+            setattr(self, f, getattr(self, f) + getattr(o, f))
+        for f in ("worst_swap_gap", "worst_out", "worst_out_elem", "worst_out_vs_own_set",
+                  "worst_out_elem_vs_own_set", "worst_score", "worst_mass"):
+            setattr(self, f, max(getattr(self, f), getattr(o, f)))
+
+
+def rel_max(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """Row-wise max |a-b| / max |b| over the last axis: the element-wise bound (0 where both are 0)."""
+    num = np.abs(a - b).max(axis=-1)
+    den = np.abs(b).max(axis=-1)
+    return np.where(den > 0, num / np.where(den > 0, den, 1), num)
 
 
 def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, requests=None,
@@ -92,7 +139,7 @@ def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, request
             # against the oracle's ranking: the score at every rank agrees within the tolerance
             if N:
                 assert np.abs(cs[o[:N]] - cs[ora.order[i, h, :N]]).max() <= SCORE_ATOL
-    assert rep.worst_score <= SCORE_ATOL / 4, f"score error {rep.worst_score}"
+    assert rep.worst_score <= SCORE_ERR, f"score error {rep.worst_score}"
 
     # -- output against attention over the GPU's OWN selected prefix (always) ----------------------
     own, own_lse = po.attend_prefix(sub, g_order, g_n, want_lse=True)
@@ -103,6 +150,10 @@ def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, request
     err_own = rel_l2(g_out, own)
     rep.worst_out_vs_own_set = float(err_own.max()) if err_own.size else 0.0
     assert rep.worst_out_vs_own_set <= OUT_RTOL, f"output vs own set: {rep.worst_out_vs_own_set}"
+    elem_own = rel_max(g_out, own)
+    rep.worst_out_elem_vs_own_set = float(elem_own.max()) if elem_own.size else 0.0
+    assert rep.worst_out_elem_vs_own_set <= OUT_RTOL, \
+        f"output vs own set, element-wise: {rep.worst_out_elem_vs_own_set}"
 
     # -- stop index, selected set, estimate ---------------------------------------------------------
     own_rank = None
@@ -115,18 +166,32 @@ def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, request
             assert 0 <= n_g <= N and (n_g % m == 0 or n_g == N)
             if N == 0:
                 assert n_g == 0 and g_mass[i, hq] == 0 and not g_out[i, hq].any()
+                rep.empty += 1
                 continue
             assert g_mass[i, hq] > eps or n_g == N, "estimate must exceed eps unless all blocks were used"
+            cs = ora.cs[i, h]
+            o_g, o_o = g_order[i, h, :N], ora.order[i, h, :N]
             if n_g != n_o:
-                # Two rankings that differ only where scores agree within SCORE_ATOL are equally valid (checked
-                # rank by rank above), and a swap of two such blocks right at the stop moves AS_min and with
-                # it the stop.  So the stop is first compared with Algorithm 1 run by the oracle over the
-                # GPU's own ranking; only if that differs too must P_acc sit at the boundary.
+                # Algorithm 1 line 6 leaves the order of near-equal scores open, and two rankings that differ
+                # only where scores agree within the score error are equally valid; a swap of two such blocks
+                # at or before the stop moves AS_min and with it the stop.  The GPU's stop must then be exactly
+                # what Algorithm 1 gives, run by the oracle, over the GPU's own ranking -- and the rankings must
+                # really differ that early, by blocks whose oracle scores agree within the score error.
                 if own_rank is None:
                     own_rank = po.psa_decode_ordered(sub, g_order, eps, m, curves=True)
                 if int(own_rank.n_selected[i, hq]) == n_g:
+                    lim = max(n_g, n_o)
+                    d = np.nonzero(o_g[:lim] != o_o[:lim])[0]
+                    assert d.size > 0, \
+                        f"stop {n_g} vs oracle {n_o} although both rankings agree on the first {lim} blocks"
+                    gap = float(np.abs(cs[o_g[d]] - cs[o_o[d]]).max())
+                    assert gap <= SCORE_ERR, f"rankings differ by blocks {gap} apart in score (> {SCORE_ERR})"
+                    rep.worst_swap_gap = max(rep.worst_swap_gap, gap)
                     assert abs(g_mass[i, hq] - own_rank.mass_est[i, hq]) <= 1e-4
-                    rep.set_tolerated += 1
+                    boundary = cs[o_o[n_o - 1]]
+                    diff = set(o_g[:n_g].tolist()) ^ set(o_o[:n_o].tolist())
+                    rep.swap_blocks_outside_boundary += sum(1 for b in diff if abs(cs[b] - boundary) > SCORE_ATOL)
+                    rep.rank_swap_stops += 1
                     continue
                 p_at = own_rank.p_acc[i, hq, min(n_g, int(own_rank.n_selected[i, hq])) - 1]
                 assert abs(p_at - eps) <= PACC_ATOL, \
@@ -134,19 +199,22 @@ def check_decode_against_oracle(pb: po.Problem, gpu, eps: float, m: int, request
                     f"with P_acc {p_at} not at the boundary {eps}"
                 rep.stop_flips += 1
                 continue
-            sg, so = set(g_order[i, h, :n_g].tolist()), set(ora.order[i, h, :n_o].tolist())
+            sg, so = set(o_g[:n_g].tolist()), set(o_o[:n_o].tolist())
             if sg == so:
                 rep.set_equal += 1
                 e = float(rel_l2(g_out[i, hq], ora.out[i, hq]))
                 rep.worst_out = max(rep.worst_out, e)
                 assert e <= OUT_RTOL, f"output vs oracle: {e}"
+                ee = float(rel_max(g_out[i, hq], ora.out[i, hq]))
+                rep.worst_out_elem = max(rep.worst_out_elem, ee)
+                assert ee <= OUT_RTOL, f"output vs oracle, element-wise: {ee}"
                 me = abs(g_mass[i, hq] - ora.mass_est[i, hq])
                 rep.worst_mass = max(rep.worst_mass, me)
                 assert me <= 1e-4, f"mass estimate {g_mass[i, hq]} vs {ora.mass_est[i, hq]}"
             else:
-                boundary = ora.cs[i, h, ora.order[i, h, n_o - 1]]
+                boundary = cs[o_o[n_o - 1]]
                 for b in sg ^ so:
-                    assert abs(ora.cs[i, h, b] - boundary) <= SCORE_ATOL, \
+                    assert abs(cs[b] - boundary) <= SCORE_ATOL, \
                         f"block {b} differs away from the stopping boundary"
                 rep.set_tolerated += 1
         for h in range(H):

@@ -45,7 +45,8 @@ def test_empty_tiny_and_page_boundary_requests(psa, eps, m):
     assert psa.read_device_error(gpu._workspace) == 0
     rep = gc.check_decode_against_oracle(pb, gpu, eps, m)
     empty = [i for i, n in enumerate(LENGTHS) if n == 0]
-    assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads - len(empty) * pb.q.shape[1]
+    assert rep.empty == len(empty) * pb.q.shape[1]
+    rep.assert_accounted()
     for r in empty:
         assert not gpu.out[r].any() and not gpu.n_selected[r].any() and not gpu.mass_est[r].any()
         assert torch.isneginf(gpu.lse[r]).all() and not gpu.blocks_read[r].any()

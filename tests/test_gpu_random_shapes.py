@@ -33,12 +33,14 @@ def _dense_check(psa, li, pb, requests=None):
     np.testing.assert_allclose(lse.cpu().numpy(), wlse, rtol=0, atol=2e-3)
 
 
-def _run(psa, cfg, layer, eps, m, tun, scorer):
+def _run(psa, cfg, layer, eps, m, tun, scorer, max_rank_swaps=1):
+    """One shape through the checker.  A single shape may hold one rank-swap stop (the sweep's total is bounded
+    by its caller: one head in 200)."""
     li = generate_layer(cfg, layer=layer, device="cuda", poison_tail=True)
     out = gc.run_gpu_decode(li, eps, m, tuning=tun, scorer=scorer)
     pb = gc.to_problem(li)
     rep = gc.check_decode_against_oracle(pb, out, eps, m, scorer=scorer)
-    assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads
+    rep.assert_accounted(max_rank_swaps=max_rank_swaps)
     _dense_check(psa, li, pb)
     return rep
 
@@ -46,7 +48,7 @@ def _run(psa, cfg, layer, eps, m, tun, scorer):
 @pytest.mark.parametrize("seed", [101, 202])
 def test_random_shapes_against_the_oracle(psa, seed):
     rng = np.random.default_rng(seed)
-    flips = heads = 0
+    total = gc.ParityReport()
     for case in range(120):
         idx = int(rng.choice([1, 2, 3, 4, 5]))
         G, H = int(rng.choice([1, 2, 4, 8])), int(rng.choice([1, 2, 4, 8]))
@@ -68,21 +70,29 @@ def test_random_shapes_against_the_oracle(psa, seed):
         scorer = int(rng.choice([0, 0, 1]))
         print(f"case {case}: config {idx} {kw} layer {layer} eps {eps} m {m} "
               f"tuning {tun.chunk_blocks}/{tun.window_chunks}/{tun.spin_limit} scorer {scorer}", flush=True)
-        rep = _run(psa, cfg, layer, eps, m, tun, scorer)
-        flips += rep.stop_flips
-        heads += rep.heads
-    assert flips <= heads // 200
+        total.add(_run(psa, cfg, layer, eps, m, tun, scorer))
+    print(f"\n[random shapes, seed {seed}] {total}")
+    total.assert_accounted(max_stop_flips=total.heads // 200)      # and rank-swap stops: one head in 200 at most
 
 
 @pytest.mark.parametrize("kw,m", [(dict(batch=3, ctx=5011, num_q_heads=64, num_kv_heads=8, dtype="f16"), 1),
                                   (dict(batch=3, ctx=7181, num_q_heads=16, num_kv_heads=2, dtype="f16"), 2)])
 def test_near_tied_scores_at_the_stop(psa, kw, m):
-    rep = _run(psa, get_config(1).scaled(**kw), 0, 0.99, m, None, 0)
-    assert rep.set_tolerated >= 1
+    """Two shapes a sweep once caught: binary32 and binary64 scoring order two blocks about 2e-6 apart differently
+    right at a head's stop, which moves AS_min and the stop.  The checker must put exactly such heads into
+    rank_swap_stops (the stop reproduced by the oracle over the GPU's ranking, the swapped blocks within the score
+    error), and no other head of the shape.  (Whether binary32 really orders the pair the other way depends on the
+    summation order of the scoring kernel, so the count may be 0; the class itself is exercised with planted swaps
+    in test_parity_checker.py.)"""
+    rep = _run(psa, get_config(1).scaled(**kw), 0, 0.99, m, None, 0, max_rank_swaps=2)
+    print(f"\n[near-tied {kw} m={m}] {rep}")
+    assert rep.rank_swap_stops <= 2 and rep.worst_swap_gap <= 1e-5
+    assert rep.stop_flips == 0
 
 
 def test_odd_head_counts_and_large_batches_of_tiny_requests(psa):
     rng = np.random.default_rng(303)
+    total = gc.ParityReport()
     for case in range(60):
         idx = int(rng.choice([1, 2, 4, 5]))
         G, H = int(rng.choice([1, 2, 4, 8])), int(rng.choice([3, 5, 6, 7, 12, 16]))
@@ -105,5 +115,8 @@ def test_odd_head_counts_and_large_batches_of_tiny_requests(psa):
         reqs = None if batch <= 8 else sorted(rng.choice(batch, size=6, replace=False).tolist())
         pb = gc.to_problem(li)
         rep = gc.check_decode_against_oracle(pb, out, eps, m, requests=reqs, scorer=scorer)
-        assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads
+        rep.assert_accounted(max_rank_swaps=1)
+        total.add(rep)
         _dense_check(psa, li, pb, reqs)
+    print(f"\n[odd head counts] {total}")
+    total.assert_accounted(max_stop_flips=max(1, total.heads // 200))

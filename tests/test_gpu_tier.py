@@ -110,7 +110,7 @@ def test_cold_then_warm_single_layer(psa, slots_share):
                                want_traffic=True)
     torch.cuda.synchronize()
     rep = gc.check_decode_against_oracle(gc.to_problem(li), got, cfg.threshold, 1)
-    assert rep.set_equal + rep.set_tolerated + rep.stop_flips == rep.heads
+    rep.assert_accounted()
 
 
 def test_two_layers_share_a_small_pool_over_a_decode_loop(psa):
