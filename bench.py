@@ -60,6 +60,17 @@ class HipEvents:
         self.all = []
 
 
+def load_read_probe():
+    """bench_stream_read_probe of libbench_probe.so (bench_probe.hip, built by __graft_entry__.build())."""
+    path = os.path.join(ROOT, "libbench_probe.so")
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is missing: run `python __graft_entry__.py` to build it")
+    lib = C.CDLL(path)
+    lib.bench_stream_read_probe.restype = C.c_int
+    lib.bench_stream_read_probe.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    return lib.bench_stream_read_probe
+
+
 def read_measured_traffic(workload: str, kernel: str):
     """HBM bytes per launch of `kernel` on `workload` as measured with hardware counters (two
     rocprofv3 --pmc runs, scaled by a plain copy of known size) and recorded in the text summary
@@ -298,9 +309,10 @@ def main():
     probe = torch.empty(4 << 30, dtype=torch.uint8, device=dev).fill_(0x5A)
     sink = torch.zeros(1, dtype=torch.int64, device=dev)
     probe_ms = []
+    read_probe = load_read_probe()
     for rep in range(9):
         e0.record()
-        psa.stream_read_probe(probe, sink)
+        assert read_probe(probe.data_ptr(), probe.numel(), sink.data_ptr(), torch.cuda.current_stream().cuda_stream) == 0
         e1.record()
         torch.cuda.synchronize()
         if rep >= 2:
@@ -308,7 +320,7 @@ def main():
     ceiling_gbs = probe.numel() / (float(np.median(probe_ms)) * 1e-3) / 1e9
     read_ceiling = {"GBps": ceiling_gbs, "GBps_best": probe.numel() / (min(probe_ms) * 1e-3) / 1e9,
                     "frac_of_peak": ceiling_gbs / HBM_PEAK_GBS, "bytes": probe.numel(), "runs": len(probe_ms),
-                    "kernel": "psa_stream_read_probe (plain 16-byte loads, one pass)"}
+                    "kernel": "bench_stream_read_probe (plain 16-byte loads, one pass)"}
     del probe
     log(f"[bench] streaming-read ceiling {ceiling_gbs:.0f} GB/s")
 

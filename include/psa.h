@@ -53,7 +53,6 @@ enum {
     PSA_DEVERR_CTX_RANGE = 2     /* ctx_len < 0 or > 16*max_blocks_per_seq: clamped             */
 };
 
-/* Shapes and layout of ONE layer's paged KV cache (PagedAttention layout, Sec. 2.1 "KV Cache"). */
 /* How a block's criticality score is computed from its metadata (Algorithm 1, line 5: CS = q . B_meta).
  * Both read the same per-channel min/max metadata and take the maximum over the query heads that
  * share the KV head.
@@ -86,6 +85,7 @@ typedef struct {
     int64_t slice_base;         /* id of this descriptor's page 0, KV head 0                       */
 } psa_tier;
 
+/* Shapes and layout of ONE layer's paged KV cache (PagedAttention layout, Sec. 2.1 "KV Cache"). */
 typedef struct {
     int32_t batch;              /* decode requests, one query token each                          */
     int32_t num_q_heads;        /* Hq                                                             */
@@ -262,19 +262,6 @@ size_t psa_tier_update_workspace_bytes(const psa_kv_desc *desc);
 psa_status psa_tier_update(const psa_kv_desc *desc, const int32_t *order, const int32_t *blocks_read,
                            int64_t busy_first, int64_t busy_count, int32_t *stats_out, void *workspace,
                            size_t workspace_bytes, void *stream);
-
-/*
- * Measurement aid, not a step of the method: one plain kernel reads `bytes` (rounded down to a
- * multiple of 16) of device memory at `src` once, front to back, and keeps nothing.  Timed by the
- * caller over a buffer much larger than the last-level cache it gives the streaming-read rate the
- * memory system delivers in practice, the ceiling the decode path's rates are quoted against
- * beside the published peak.
- *   src   device pointer, 16-byte aligned; read only
- *   sink  device pointer to 8 writable bytes, 8-byte aligned, or NULL; practically never written
- *         (it only keeps the loads alive)
- * Errors: PSA_ERR_INVALID_ARG for a NULL or misaligned pointer; bytes == 0 is a no-op.
- */
-psa_status psa_stream_read_probe(const void *src, size_t bytes, void *sink, void *stream);
 
 /*
  * Copies the sticky device error word of a workspace to the host and clears nothing.

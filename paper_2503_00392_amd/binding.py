@@ -103,8 +103,6 @@ def load_library() -> C.CDLL:
         lib.psa_tier_update_workspace_bytes.argtypes = [C.POINTER(_KvDesc)]
         lib.psa_tier_update.restype = C.c_int
         lib.psa_tier_update.argtypes = [C.POINTER(_KvDesc), vp, vp, C.c_int64, C.c_int64, vp, vp, sz, vp]
-        lib.psa_stream_read_probe.restype = C.c_int
-        lib.psa_stream_read_probe.argtypes = [vp, sz, vp, vp]
         lib.psa_read_device_error.restype = C.c_int
         lib.psa_read_device_error.argtypes = [vp, C.POINTER(C.c_int32), vp]
         _lib = lib
@@ -369,14 +367,6 @@ def tier_update(kv: KvCache, order: torch.Tensor, blocks_read: torch.Tensor, bus
     _check(st, "psa_tier_update")
     stats._workspace = workspace
     return stats
-
-
-def stream_read_probe(src: torch.Tensor, sink=None, stream=None) -> None:
-    """Reads the whole of `src` (a contiguous device tensor) once with a plain kernel; for timing."""
-    assert src.is_contiguous()
-    st = load_library().psa_stream_read_probe(_ptr(src), src.numel() * src.element_size(),
-                                              _ptr(sink) if sink is not None else None, _stream(stream))
-    _check(st, "psa_stream_read_probe")
 
 
 def read_device_error(workspace: torch.Tensor, stream=None) -> int:

@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpsa.so")
 SOURCES = ["psa_api.hip", "psa_meta.hip", "psa_dense.hip", "psa_decode.hip", "psa_score.hip",
-           "psa_order.hip", "psa_select.hip", "psa_values.hip", "psa_append.hip", "psa_probe.hip", "psa_tier.hip"]
+           "psa_order.hip", "psa_select.hip", "psa_values.hip", "psa_append.hip", "psa_tier.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 VALU forms are kept out of the generated code

@@ -226,14 +226,6 @@ psa_status psa_tier_update(const psa_kv_desc *d, const int32_t *order, const int
     return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
 }
 
-psa_status psa_stream_read_probe(const void *src, size_t bytes, void *sink, void *stream) {
-    if (bytes == 0) return PSA_OK;
-    if (!src || (reinterpret_cast<uintptr_t>(src) & 15u) || (reinterpret_cast<uintptr_t>(sink) & 7u))
-        return PSA_ERR_INVALID_ARG;
-    hipError_t e = psa::launch_read_probe(src, bytes, sink, (hipStream_t)stream);
-    return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
-}
-
 psa_status psa_read_device_error(const void *workspace, int32_t *host_flags, void *stream) {
     if (!workspace || !host_flags) return PSA_ERR_INVALID_ARG;
     // word 1 of the workspace header holds the sticky bits

@@ -44,9 +44,6 @@ DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t) {
 
 struct WsLayout {
     size_t header, ctl, scores, order, ranked_page, agg, block_lse, logits, partial, value_items, total;
-#ifdef PSA_ENABLE_TRACE
-    size_t trace;
-#endif
 };
 
 static WsLayout layout(const psa_kv_desc *d, const DecodePlan &p) {
@@ -65,19 +62,11 @@ static WsLayout layout(const psa_kv_desc *d, const DecodePlan &p) {
     L.logits = at;      at = align_up(at + S * MB * kPage * G * 4, 256);
     L.partial = at;     at = align_up(at + S * p.max_chunks * G * kPartialStride * 4, 256);
     L.value_items = at; at = align_up(at + S * p.max_chunks * 4, 256);
-#ifdef PSA_ENABLE_TRACE
-    L.trace = at;       at = align_up(at + (size_t)(2 + kTraceRecords) * 32, 256);
-#endif
     L.total = at;
     return L;
 }
 
 size_t decode_workspace_bytes_plan(const psa_kv_desc *d, const DecodePlan &p) { return layout(d, p).total; }
-#ifdef PSA_ENABLE_TRACE
-extern "C" size_t psa_debug_trace_offset(const psa_kv_desc *d, const psa_tuning *t) {
-    return layout(d, make_plan(d, t)).trace;
-}
-#endif
 
 hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const DecodePlan &plan, void *wsp,
                          hipStream_t st) {
@@ -97,10 +86,6 @@ hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const Decode
     ws.value_items = reinterpret_cast<int32_t *>(base + L.value_items);
     ws.max_chunks = plan.max_chunks;
     ws.max_units = plan.max_chunks;
-#ifdef PSA_ENABLE_TRACE
-    ws.trace = reinterpret_cast<unsigned long long *>(base + L.trace);
-    (void)hipMemsetAsync(ws.trace, 0, (size_t)(2 + kTraceRecords) * 32, st);
-#endif
     const int G = d->num_q_heads / d->num_kv_heads;
     if (kv.batch == 0) return hipSuccess;
     hipEvent_t *ev = plan.events;

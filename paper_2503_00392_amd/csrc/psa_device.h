@@ -92,15 +92,7 @@ struct DecodeWs {
                             // each stream's fold when it closes the stream
     int32_t max_chunks;     // chunks per stream at most
     int32_t max_units;      // = max_chunks (stride of `partial`)
-#ifdef PSA_ENABLE_TRACE
-    unsigned long long *trace;   // [0] record count, then 4 words per record (tuning aid)
-#endif
 };
-#ifdef PSA_ENABLE_TRACE
-constexpr int kTracePerWave = 32;                      // records per workgroup
-constexpr int kTraceWgs = 32768;                       // workgroups that keep records
-constexpr int kTraceRecords = kTraceWgs * kTracePerWave;
-#endif
 constexpr int kPartialStride = 132;  // M, l, pad, pad, acc[128]
 constexpr int kMaxWindowChunks = 256; // chunks read beyond the fold's frontier, at most
 constexpr int kValueCount = 32;      // index of the value-item counter in the workspace header

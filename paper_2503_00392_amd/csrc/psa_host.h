@@ -77,7 +77,6 @@ hipError_t launch_tier_update(const psa_kv_desc *d, const int32_t *order, const 
                               long long busy_first, long long busy_count, int32_t *stats_out, void *workspace,
                               hipStream_t st);
 
-hipError_t launch_read_probe(const void *src, size_t bytes, void *sink, hipStream_t st);
 hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const DecodePlan &plan, void *ws,
                          hipStream_t st);
 

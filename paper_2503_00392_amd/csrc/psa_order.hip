@@ -29,13 +29,6 @@ namespace psa {
 
 constexpr int kBucketLimit = 192;
 
-#ifdef PSA_ENABLE_TRACE
-// Tuning aid (not built by default): phase timestamps of workgroup 0, 100 MHz.
-#define PSA_ORDER_STAMP(K)                                                                     \
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) ws.trace[8 + ((size_t)(kTraceWgs - 1) * kTracePerWave + (K)) * 4 + 2] = wall_clock64();
-#else
-#define PSA_ORDER_STAMP(K)
-#endif
 
 __device__ __forceinline__ unsigned long long shfl_xor_u64(unsigned long long v, int mask) {
     const int lo = __shfl_xor((int)(v & 0xffffffffull), mask);
@@ -131,8 +124,6 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
     // the scoring kernel clamps silently (it clears the error word); out-of-range inputs are reported here
     const int ctx = (tid == 0 && blockIdx.x == 0) ? ctx_clamped(kv, r, ws.header) : ctx_clamped_quiet(kv, r);
     const int N = (ctx + kPage - 1) / kPage;
-    PSA_ORDER_STAMP(0)
-
     // ---- reset of the progressive kernel's per-stream state ------------------------------------
     if (tid == 0 && part == 0) {
         StreamCtl *c = &ws.ctl[s];
@@ -186,8 +177,6 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
     const float smax = score_of_key(kmin), span = smax - score_of_key(kmax);
     const bool span_ok = span > 0.0f && span < INFINITY;       // false also for NaN: the fallback ranks then
     const float scale = span_ok ? (float)NB / span : 0.0f;
-    PSA_ORDER_STAMP(1)
-
     int bkt[8], arrival[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -201,8 +190,6 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         }
     }
     lds_barrier();
-
-    PSA_ORDER_STAMP(2)
     // exclusive scan of the bucket counts (8 buckets per thread) and the largest bucket
     uint32_t c8[8];
     {
@@ -235,7 +222,6 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         if (tid == 0) cnt[NB] = (uint32_t)N;
     }
     lds_barrier();
-    PSA_ORDER_STAMP(3)
     const uint32_t *base = cnt;                                               // base[b] .. base[b+1]: bucket b's slots
 
     int32_t *ord = ws.order + (size_t)s * kv.max_blocks;
@@ -267,7 +253,6 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
                 cmax = max(cmax, cn[j]);
             }
         }
-        PSA_ORDER_STAMP(4)
         // the 8 elements walk their buckets side by side, so their LDS reads overlap; the slot's block
         // index is needed only to break a tie
         for (uint32_t i = 0; i < cmax; ++i) {
@@ -284,7 +269,6 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
                 before[j] += (i < cn[j] && first) ? 1u : 0u;
             }
         }
-        PSA_ORDER_STAMP(5)
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int p = tid * 8 + j;
@@ -317,7 +301,6 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
     }
     if (oout && part == 0)
         for (int p = N + tid; p < kv.max_blocks; p += nthreads) oout[p] = -1;
-    PSA_ORDER_STAMP(6)
 }
 
 hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, const DecodePlan &plan, int budget_blocks,

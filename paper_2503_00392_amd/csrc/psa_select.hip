@@ -84,39 +84,6 @@ __device__ __forceinline__ unsigned long long shfl_u64(unsigned long long v, int
 }
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
-#ifdef PSA_ENABLE_TRACE
-// Tuning aid (not built by default): every workgroup keeps its own list of records (kind, stream,
-// index, begin, end; 100 MHz timestamps), so tracing adds no shared traffic.
-#define PSA_TRACE(KIND, S, IDX, T0)                                                            \
-    if (threadIdx.x == 0 && trace_n < kTracePerWave && blockIdx.x < kTraceWgs) {                                         \
-        unsigned long long *rec_ = ws.trace + 8 + ((size_t)blockIdx.x * kTracePerWave + trace_n) * 4; \
-        rec_[0] = ((unsigned long long)(KIND) << 56) | ((unsigned long long)(S) << 32) | (unsigned)(IDX); \
-        rec_[1] = (unsigned long long)blockIdx.x;                                              \
-        rec_[2] = (T0); rec_[3] = wall_clock64();                                              \
-        ++trace_n;                                                                             \
-    }
-#define PSA_NOW() wall_clock64()
-#define PSA_STAMP(K) if (threadIdx.x == 0) sh.stamp[K] = wall_clock64();
-#define PSA_FOLD_STAMP() if (threadIdx.x == 0 && *fold_n < 16) fold_t[(*fold_n)++] = wall_clock64();
-#define PSA_FOLD_ARGS , unsigned long long *fold_t, int *fold_n
-#define PSA_FOLD_PASS , sh.fold_stamp, &sh.fold_stamps
-#define PSA_TRACE_SPAN(KIND, S, IDX, T0, T1)                                                   \
-    if (threadIdx.x == 0 && trace_n < kTracePerWave && blockIdx.x < kTraceWgs) {                                         \
-        unsigned long long *rec_ = ws.trace + 8 + ((size_t)blockIdx.x * kTracePerWave + trace_n) * 4; \
-        rec_[0] = ((unsigned long long)(KIND) << 56) | ((unsigned long long)(S) << 32) | (unsigned)(IDX); \
-        rec_[1] = (unsigned long long)blockIdx.x;                                              \
-        rec_[2] = (T0); rec_[3] = (T1);                                                        \
-        ++trace_n;                                                                             \
-    }
-#else
-#define PSA_STAMP(K)
-#define PSA_FOLD_STAMP()
-#define PSA_FOLD_ARGS
-#define PSA_FOLD_PASS
-#define PSA_TRACE_SPAN(KIND, S, IDX, T0, T1)
-#define PSA_TRACE(KIND, S, IDX, T0)
-#define PSA_NOW() 0ull
-#endif
 
 constexpr int kBatch = 4;            // key slices a wave keeps in flight
 constexpr int kSelectThreads = 256;  // 4 waves; four such workgroups fit a CU (register budget)
@@ -152,11 +119,6 @@ struct SelectShared {
     int valid[kMaxChunkBlocks];
     int go;                                // after the wait for the window: 1 = read the chunk, 0 = the stream closed
     uint4 stage[kSelectThreads / 64][16 * 17];   // per wave: one key slice, rows padded to 272 bytes
-#ifdef PSA_ENABLE_TRACE
-    unsigned long long stamp[8];
-    unsigned long long fold_stamp[16];
-    int fold_stamps;
-#endif
 };
 
 // =================================================================================================
@@ -165,7 +127,7 @@ struct SelectShared {
 // Leaves either with the stream's key side closed, or with the mark on the first unpublished chunk.
 // =================================================================================================
 template <int G>
-__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU, int fr PSA_FOLD_ARGS) {
+__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU, int fr) {
     // fr: the chunk the mark was on, which is where the previous holder of the fold stopped
     const int lane = threadIdx.x & 63;
     StreamCtl *ctl = &ws.ctl[s];
@@ -193,7 +155,6 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
         v = (ci < ws.max_chunks) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
     }
     const int nch = uniform((int)(kp0 >> 32));
-    PSA_FOLD_STAMP()
     int fr_pub = fr;                           // frontier as the progress word shows it
     int walked = fr;
     bool finished = false;
@@ -253,7 +214,6 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
             walked = cidx + 1;
             if (__ballot(stop == ~0ull) == 0ull) finished = true;
         }
-        PSA_FOLD_STAMP()
         fr = walked;
         if (fr >= nch) finished = true;
         if (finished) break;
@@ -273,7 +233,6 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
             v = (ci < nch) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
         }
         stores_done();
-        PSA_FOLD_STAMP()
         if (!gap) continue;
         {
             const unsigned long long pub2 = __ballot(v < kAggArmed);
@@ -289,7 +248,6 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
                                                  __HIP_MEMORY_SCOPE_AGENT);
             seen = expected;
         }
-        PSA_FOLD_STAMP()
         if (uniform((int)(seen == kAggSentinel))) return;
         // published between the look and the mark: fetch the words again and carry on
         {
@@ -367,8 +325,6 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     for (int kk = 0; kk < 4; ++kk) qb[kk] = sh.qb[kk][lane];
     float *lg_out = ws.logits + row0 * (kPage * G);
     lds_barrier();
-    PSA_STAMP(0)
-
     // ---- keys: wave w takes blocks [16*it + 4*w, +4), each a 4 KiB slice read as four coalesced 1 KiB
     //      loads.  A operand of the product: row n = token n of the block, same channel assignment as
     //      the queries. ----------------------------------------------------------------------------
@@ -423,15 +379,12 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
             }
         }
     }
-    PSA_STAMP(1)
     lds_barrier();
-    PSA_STAMP(2)
     // the blocks' L_b, for the fold's block-by-block pass; complete before the chunk is published
     for (int idx = tid; idx < nblk * G; idx += kSelectThreads)
         st_relaxed(&ws.block_lse[row0 * G + idx], sh.Lb[idx / G][idx % G]);
     stores_done();
     lds_barrier();
-    PSA_STAMP(3)
     if (wave != 0) return;
 
     // ---- publish: the chunk's (log-sum-exp, minimum) of its blocks' L_b per head.  Lane = (slot, head):
@@ -460,12 +413,7 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     if (lane >= 1 && lane < G) st_relaxed(cw + lane, w);
     unsigned long long old = 0;
     if (lane == 0) old = __hip_atomic_exchange(cw, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    PSA_STAMP(4)
-#ifdef PSA_ENABLE_TRACE
-    if (threadIdx.x == 0) sh.fold_stamps = 0;
-#endif
-    if (uniform((int)(old == kAggArmed))) fold_stream<G>(kv, ws, s, eps, m, CB, c PSA_FOLD_PASS);
-    PSA_STAMP(5)
+    if (uniform((int)(old == kAggArmed))) fold_stream<G>(kv, ws, s, eps, m, CB, c);
 }
 
 // =================================================================================================
@@ -481,8 +429,6 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
     const int s = blockIdx.x % S, c = blockIdx.x / S;
     const int N = (stream_ctx(kv, s) + kPage - 1) / kPage;
     if (c * CB >= N) return;
-    [[maybe_unused]] int trace_n = 0;
-    [[maybe_unused]] const unsigned long long t_begin = PSA_NOW();
     load_queries<G>(sh, kv, q, s);
     stage_pages<G>(sh, kv, ws, CB, s, c);
     // Second tier: a chunk with slices that are not cached is read over the host link, where reading ahead
@@ -515,22 +461,9 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
         sh.go = go;
     }
     lds_barrier();
-    PSA_TRACE(4, s, c, t_begin);
     if (!sh.go) return;
     if (threadIdx.x == 0) atomicAdd(&ws.ctl[s].k_blocks, min(CB, N - c * CB));     // traffic accounting
-    [[maybe_unused]] const unsigned long long t0 = PSA_NOW();
     process_chunk<DT, G>(sh, kv, q, ws, eps, m, CB, s, c);
-    PSA_TRACE(1, s, c, t0);
-    PSA_TRACE_SPAN(10, s, c, t0, sh.stamp[0]);             // queries in registers
-    PSA_TRACE_SPAN(11, s, c, sh.stamp[0], sh.stamp[1]);    // keys loaded, logits computed (wave 0)
-    PSA_TRACE_SPAN(12, s, c, sh.stamp[1], sh.stamp[2]);    // the other waves
-    PSA_TRACE_SPAN(13, s, c, sh.stamp[2], sh.stamp[3]);    // stores complete
-    PSA_TRACE_SPAN(14, s, c, sh.stamp[3], sh.stamp[4]);    // published
-    PSA_TRACE_SPAN(15, s, c, sh.stamp[4], sh.stamp[5]);    // fold, if it was this chunk's turn
-#ifdef PSA_ENABLE_TRACE
-    if (threadIdx.x == 0)
-        for (int fj = 0; fj < sh.fold_stamps; ++fj) { PSA_TRACE_SPAN(20 + fj, s, c, sh.stamp[4], sh.fold_stamp[fj]); }
-#endif
 }
 
 template <int DT, int G>

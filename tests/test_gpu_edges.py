@@ -118,19 +118,24 @@ def test_inputs_only_the_device_can_see_are_wrong(psa):
     assert psa.read_device_error(again._workspace) == 0
 
 
-def test_stream_read_probe_sizes_and_alignment(psa):
-    """The measurement aid reads and keeps nothing: any size runs (empty, below one load, ragged, several
-    workgroups' worth), the source is unchanged, and a misaligned source is refused on the host."""
+def test_bench_read_probe_sizes_and_alignment(psa):
+    """The benchmark's measurement aid (bench_probe.hip) reads and keeps nothing: any size runs (empty, below one
+    load, ragged, several workgroups' worth), the source is unchanged, a misaligned source is refused on the host."""
+    import os
+    import sys
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import bench
+    probe = bench.load_read_probe()
     buf = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
     before = buf.clone()
     sink = torch.zeros(1, dtype=torch.int64, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
     for n in (0, 1, 4, 5, 1000, 2048 * 4 + 12, 1 << 20):
-        psa.stream_read_probe(buf[:n].contiguous() if n else buf[:0], sink)
-    psa.stream_read_probe(buf, None)
+        assert probe(buf.data_ptr(), n * 4, sink.data_ptr(), st) == 0
+    assert probe(buf.data_ptr(), buf.numel() * 4, None, st) == 0
     torch.cuda.synchronize()
     assert torch.equal(buf, before)
-    with pytest.raises(psa.PsaError):
-        psa.stream_read_probe(buf[1:], sink)        # 4 bytes past a 16-byte boundary
+    assert probe(buf.data_ptr() + 4, 4096, sink.data_ptr(), st) == 1        # 4 bytes past a 16-byte boundary
 
 
 @pytest.mark.parametrize("bad", ["nan", "inf", "huge"])

@@ -155,7 +155,8 @@ def test_degenerate_scores_rank_by_block_index(psa):
     for r in range(2):
         assert np.array_equal(order[r, :, :N[r]], np.tile(np.arange(N[r]), (cfg.num_kv_heads, 1)))
     rep = gc.check_decode_against_oracle(pb, gpu, 0.5, 1)
-    rep.assert_accounted(max_rank_swaps=0)
+    # every block weighs the same, so P_acc(n) = n/N lands exactly on the threshold: stop flips are the rule here
+    rep.assert_accounted(max_rank_swaps=0, max_stop_flips=rep.heads)
     assert rep.set_tolerated == 0
 
 
