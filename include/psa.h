@@ -205,6 +205,32 @@ psa_status psa_decode_attention(const psa_kv_desc *desc, const void *q, const vo
                                 void *stream);
 
 /*
+ * psa_decode_attention for callers that cannot allocate device memory and have no workspace to bring: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same results
+ * bit for bit as psa_decode_attention with the same arguments; the workspace is an array of
+ * PSA_STATIC_SCRATCH_BYTES of device memory inside the library itself (every GPU the library runs on holds
+ * its own copy until the process ends).  The call allocates nothing and frees nothing, on the host side of
+ * the runtime or the device side; the first call on a GPU looks the array's address up (make that call
+ * outside a graph capture).
+ *   Arguments as for psa_decode_attention (no scores_out, no traffic_out, no workspace), plus
+ *   device_error_out  device int32 or NULL: receives the sticky device error word of the call (an OR of
+ *                     PSA_DEVERR_* bits, 0 = none) -- there is no workspace pointer to hand to
+ *                     psa_read_device_error
+ * Errors: those of psa_decode_attention; PSA_ERR_WORKSPACE_TOO_SMALL if this descriptor and tuning need more
+ * than PSA_STATIC_SCRATCH_BYTES (psa_decode_workspace_bytes tells how much: about 43 MiB for 8 requests x 8
+ * KV heads x 32K tokens with 4 query heads per KV head); PSA_ERR_UNSUPPORTED with a second tier.
+ * All calls on one GPU share that GPU's array, whatever their streams: two calls whose kernels may overlap
+ * in time race and give wrong results.  Order them (one stream, or events).  Nothing needs clearing between
+ * calls: every call initialises what it reads.
+ */
+#define PSA_STATIC_SCRATCH_BYTES (64u << 20)
+psa_status psa_decode_attention_static(const psa_kv_desc *desc, const void *q, const void *meta,
+                                       float threshold, int32_t check_granularity, int32_t scorer, float *out,
+                                       int32_t *n_selected, float *mass_est, int32_t *blocks_read,
+                                       float *lse_out, int32_t *order_out, int32_t *device_error_out,
+                                       const psa_tuning *tuning, void *stream);
+
+/*
  * Fixed-budget control: what block-level dynamic sparse attention does without PSA (Sec. 1, Sec. 2.2
  * "KV Cache Selection": a fixed top-k, e.g. k = 64 or 128 blocks).  Same scoring and ranking as
  * psa_decode_attention; every query head then attends exactly the first min(k_blocks, N) ranked

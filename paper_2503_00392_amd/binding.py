@@ -88,6 +88,9 @@ def load_library() -> C.CDLL:
         lib.psa_decode_attention.restype = C.c_int
         lib.psa_decode_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, f32, i32, i32, vp, vp, vp, vp, vp,
                                              vp, vp, vp, C.POINTER(_Tuning), vp, sz, vp]
+        lib.psa_decode_attention_static.restype = C.c_int
+        lib.psa_decode_attention_static.argtypes = [C.POINTER(_KvDesc), vp, vp, f32, i32, i32, vp, vp, vp, vp, vp,
+                                                    vp, vp, C.POINTER(_Tuning), vp]
         lib.psa_append_kv.restype = C.c_int
         lib.psa_append_kv.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, vp, vp]
         lib.psa_topk_attention.restype = C.c_int
@@ -284,6 +287,25 @@ def decode_attention(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, threshold
         _ptr(o.scores), _ptr(o.traffic), C.byref(t) if t else None, _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "psa_decode_attention")
     o._workspace = workspace   # keeps the buffer alive until the caller has synchronised
+    return o
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def decode_attention_static(kv: KvCache, q: torch.Tensor, meta: torch.Tensor, threshold: float,
+                            check_granularity: int, outputs: DecodeOutput, *, device_error: torch.Tensor | None = None,
+                            tuning: Tuning | None = None, stream=None, scorer: int = SCORE_UPPER_BOUND) -> DecodeOutput:
+    """psa_decode_attention_static: the caller brings every output tensor (`outputs.scores` and
+    `outputs.traffic` are not written); nothing is allocated here or in the library."""
+    d = kv.desc()
+    t = tuning.c() if tuning else None
+    o = outputs
+    st = load_library().psa_decode_attention_static(
+        C.byref(d), _ptr(q), _ptr(meta), float(threshold), int(check_granularity), int(scorer), _ptr(o.out),
+        _ptr(o.n_selected), _ptr(o.mass_est), _ptr(o.blocks_read), _ptr(o.lse), _ptr(o.order), _ptr(device_error),
+        C.byref(t) if t else None, _stream(stream))
+    _check(st, "psa_decode_attention_static")
     return o
 
 

@@ -3,6 +3,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "psa_host.h"
 
 namespace {
@@ -174,6 +176,65 @@ psa_status psa_topk_attention(const psa_kv_desc *d, const void *q, const void *m
     if (k_blocks < 1) return PSA_ERR_INVALID_ARG;
     return decode_common(d, q, meta, 0.0f, k_blocks, k_blocks, scorer, out, n_selected, mass_est, blocks_read,
                          lse_out, order_out, scores_out, traffic_out, tuning, workspace, workspace_bytes, stream);
+}
+
+// ---- the entry point that allocates nothing ------------------------------------------------------------
+// Its workspace is this array: device memory that belongs to the loaded library, one copy per GPU, there
+// until the process ends.  In host code the array's NAME is only a handle for the runtime's symbol table,
+// not a device address: the address on the current GPU comes from hipGetSymbolAddress (once per device),
+// and only that pointer is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[PSA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];      // per device: where `scratch` lives there; NULL = not asked yet
+std::mutex g_scratch_mutex;
+
+// The current device's copy of `scratch`.
+psa_status static_scratch(void **ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PSA_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return PSA_ERR_LAUNCH;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return PSA_OK;
+}
+
+__global__ void copy_error_word_kernel(const int32_t *header, int32_t *dst) { *dst = header[1]; }
+}  // namespace
+
+psa_status psa_decode_attention_static(const psa_kv_desc *d, const void *q, const void *meta, float threshold,
+                                       int32_t check_granularity, int32_t scorer, float *out, int32_t *n_selected,
+                                       float *mass_est, int32_t *blocks_read, float *lse_out, int32_t *order_out,
+                                       int32_t *device_error_out, const psa_tuning *tuning, void *stream) {
+    // the size first: a shape that does not fit is refused before anything touches the GPU
+    psa_status st = check_desc(d, true, true);
+    if (st != PSA_OK) return st;
+    if (d->tier) return PSA_ERR_UNSUPPORTED;
+    if (d->max_blocks_per_seq > psa::kMaxBlocks) return PSA_ERR_UNSUPPORTED;
+    if (tuning) {
+        const int cb = tuning->chunk_blocks;
+        if (cb != 0 && (cb < 8 || cb > psa::kMaxChunkBlocks || cb % 4 != 0)) return PSA_ERR_INVALID_ARG;
+    }
+    if (psa::decode_workspace_bytes_plan(d, psa::make_plan(d, tuning)) > (size_t)PSA_STATIC_SCRATCH_BYTES)
+        return PSA_ERR_WORKSPACE_TOO_SMALL;
+    if (d->batch == 0) return PSA_OK;
+    void *ws = nullptr;
+    if ((st = static_scratch(&ws)) != PSA_OK) return st;
+    st = decode_common(d, q, meta, threshold, check_granularity, 0, scorer, out, n_selected, mass_est, blocks_read,
+                       lse_out, order_out, nullptr, nullptr, tuning, ws, (size_t)PSA_STATIC_SCRATCH_BYTES, stream);
+    if (st == PSA_OK && device_error_out) {
+        copy_error_word_kernel<<<1, 1, 0, (hipStream_t)stream>>>(static_cast<const int32_t *>(ws), device_error_out);
+        if (hipGetLastError() != hipSuccess) return PSA_ERR_LAUNCH;
+    }
+    return st;
 }
 
 psa_status psa_dense_attention(const psa_kv_desc *d, const void *q, float *out, float *lse,

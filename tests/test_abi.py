@@ -175,3 +175,18 @@ def test_binding_structs_have_the_layout_of_the_header(tmp_path):
         for fname, _ in ct._fields_:
             assert int(got[f"{cname}.{fname}"]) == getattr(ct, fname).offset, f"{cname}.{fname}"
 
+
+def test_static_entry_point_rejects_on_the_host_before_it_touches_a_gpu(lib):
+    """psa_decode_attention_static: what does not fit its array, a bad descriptor or a second tier come back as
+    codes with no device involved (this test runs without one)."""
+    def call(d, threshold=0.9, m=1):
+        return lib.psa_decode_attention_static(C.byref(d), 0x10, 0x20, threshold, m, 0, 0x30, 0x40, 0x50, None, None,
+                                               None, None, None, None)
+    big = _desc(batch=4, num_pages=4 * 8192, max_blocks_per_seq=8192)
+    assert lib.psa_decode_workspace_bytes(C.byref(big), None) > pb.STATIC_SCRATCH_BYTES
+    assert call(big) == 3
+    assert call(_desc(head_dim=64)) == 2
+    assert call(_desc(num_q_heads=30)) == 1
+    assert call(_desc(batch=0)) == 0
+    header = open(HEADER).read()
+    assert f"#define PSA_STATIC_SCRATCH_BYTES ({pb.STATIC_SCRATCH_BYTES >> 20}u << 20)" in header
