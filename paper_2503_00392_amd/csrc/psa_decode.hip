@@ -9,7 +9,7 @@ namespace psa {
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Compute units of the current device (256 on MI355X); read once.
-static int compute_units() {
+int compute_units() {
     static int cached = 0;
     if (cached == 0) {
         int dev = 0, n = 0;
@@ -96,7 +96,7 @@ hipError_t launch_decode(const psa_kv_desc *d, const DecodeArgs &a, const Decode
     if ((e = launch_order(kv, ws, G, plan, a.budget_blocks, a.order_out, st)) != hipSuccess) return e;
     if (d->tier && (e = launch_tier_resolve(kv, d->tier, ws.ranked_page, st)) != hipSuccess) return e;
     if (ev) (void)hipEventRecord(ev[2], st);
-    if ((e = launch_select(kv, d->dtype, G, a.q, ws, a.threshold, a.check_granularity, plan, st)) != hipSuccess)
+    if ((e = launch_select(kv, d->dtype, G, a.q, ws, a.threshold, a.check_granularity, a.budget_blocks, plan, st)) != hipSuccess)
         return e;
     if (ev) (void)hipEventRecord(ev[3], st);
     if ((e = launch_attend(kv, d->dtype, G, ws, plan, st)) != hipSuccess) return e;

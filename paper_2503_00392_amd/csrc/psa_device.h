@@ -86,7 +86,8 @@ struct DecodeWs {
     int32_t *ranked_page;   // [S][max_blocks]  physical page of each ranked block
     unsigned long long *agg;  // [S][max_chunks][G]  (L_chunk, Lmin_chunk) as two floats, or the NaN sentinel
     float *block_lse;       // [S][max_blocks][G]  log2 of each ranked block's AS (Algorithm 1 line 10)
-    float *logits;          // [S][max_blocks][G][16]  scaled logits (log2 units) by ranked block
+    float *logits;          // [S][max_blocks][G][16]  scaled logits (log2 units) by ranked block; position
+                            // 4*r + j of a (block, head) row holds token 4*j + r
     float *partial;         // [S][max_chunks][G][kPartialStride]
     int32_t *value_items;   // [S * max_chunks] value units to attend: stream * max_chunks + chunk, appended by
                             // each stream's fold when it closes the stream

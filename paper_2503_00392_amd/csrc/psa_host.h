@@ -52,6 +52,7 @@ struct DecodePlan {
     hipEvent_t *events;   // NULL or 6 events recorded between the kernels
 };
 DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t);
+int compute_units();      // of the current device (256 on MI355X); read once
 size_t decode_workspace_bytes_plan(const psa_kv_desc *d, const DecodePlan &p);
 struct DecodeArgs {
     const void *q, *meta;
@@ -86,7 +87,7 @@ hipError_t launch_score(const KvView &kv, int dtype, int G, int scorer, const vo
 hipError_t launch_order(const KvView &kv, const DecodeWs &ws, int G, const DecodePlan &plan, int budget_blocks,
                         int32_t *order_out, hipStream_t st);
 hipError_t launch_select(const KvView &kv, int dtype, int G, const void *q, const DecodeWs &ws, float eps,
-                         int m, const DecodePlan &plan, hipStream_t st);
+                         int m, int budget_blocks, const DecodePlan &plan, hipStream_t st);
 hipError_t launch_attend(const KvView &kv, int dtype, int G, const DecodeWs &ws, const DecodePlan &plan,
                          hipStream_t st);
 hipError_t launch_finalize(const KvView &kv, const DecodeWs &ws, int G, int VU, float *out,

@@ -4,7 +4,8 @@
 
 namespace psa {
 
-constexpr int kScoreBlocks = 64;   // blocks per workgroup: 16 per wave
+constexpr int kScoreBlocks = 64;   // blocks per workgroup and round: 16 per wave (the matrix version: per workgroup)
+constexpr int kMaxRounds = 4;      // rounds a workgroup of score_kernel makes at most
 
 // =================================================================================================
 // Scoring.  Upper bound (CENTER = 0):
@@ -12,71 +13,90 @@ constexpr int kScoreBlocks = 64;   // blocks per workgroup: 16 per wave
 //   with q+ = max(q,0), q- = min(q,0).
 // Cuboid centre (CENTER = 1): (1/sqrt d) q . (kmin + kmax)/2 = (1/(2 sqrt d)) (q . kmax + q . kmin).
 // Either way CS[b] = max over the heads g of the group.
-// grid (ceil(max_blocks/64), S), 256 threads.  A 16-lane row handles one block: lanes 0-7 take
-// 32 bytes each of the min row (against q-, or q), lanes 8-15 of the max row (against q+, or q).
+// grid (ceil(max_blocks / (64 rounds)), S), 256 threads; a workgroup covers 64*rounds consecutive blocks, wave w
+// the 16*rounds blocks from 16*rounds*w.  A 16-lane row handles one block per step: lane cl takes channels
+// 8cl..8cl+7 of the min row (against q-, or q) and of the max row (against q+, or q), so each row's two loads
+// are 256 contiguous bytes.  The wave fetches the pages of all its blocks with one load (lane = block) and
+// keeps the records of one round (16 blocks, 8 KiB) in flight while it computes the round before.
 // =================================================================================================
 template <int DT, int G, int CENTER>
 __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__restrict__ q,
                                                     const uint8_t *__restrict__ meta,
                                                     float *__restrict__ scores,
-                                                    float *__restrict__ scores_out, int32_t *header) {
+                                                    float *__restrict__ scores_out, int32_t *header, int rounds) {
     const int s = blockIdx.y, r = s / kv.num_kv_heads, h = s % kv.num_kv_heads;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, row = lane >> 4, cl = lane & 15;
-    const int is_max = cl >> 3, slot = cl & 7;
     // first kernel of a decode call: it clears the sticky error word and clamps silently; the
     // ranking kernel, which sees the same table entries and contexts, reports them
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 2) header[threadIdx.x] = 0;
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 2) header[kValueCount] = 0;   // value work list
     const int ctx = ctx_clamped_quiet(kv, r);
     const int N = (ctx + kPage - 1) / kPage;
-    const int base = blockIdx.x * kScoreBlocks + wave * 16;
+    const int base = (blockIdx.x * 4 + wave) * 16 * rounds;      // the wave's first block
     if (base >= N) return;
+    const int mine = min(16 * rounds, N - base);                 // blocks of this wave
 
-    // the lane's 16 channels of every query head, with the entries of the wrong sign zeroed
-    uint32_t qs[G][8];
+    // pages of the wave's blocks: lane = block
+    const int32_t *table = kv.block_table + (size_t)r * kv.max_blocks;
+    const int page_of_lane = clamp_page_quiet(table[base + min(lane, mine - 1)], kv.num_pages);
+
+    // the lane's 8 channels of every query head: the negative parts (for the minima) and the positive parts (for
+    // the maxima), or the whole of it twice for the centre
+    uint32_t qn[G][4], qp[G][4];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const uint8_t *qp = q + ((size_t)(r * kv.num_q_heads + h * G + g) * kHeadDim + slot * 16) * 2;
-        const uint4 a = ld16(qp), b = ld16(qp + 16);
-        const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        const uint4 a = ld16(q + ((size_t)(r * kv.num_q_heads + h * G + g) * kHeadDim + cl * 8) * 2);
+        const uint32_t w[4] = {a.x, a.y, a.z, a.w};
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t neg = ((w[j] >> 15) & 0x00010001u) * 0xFFFFu;
-            qs[g][j] = CENTER ? w[j] : (w[j] & (is_max ? ~neg : neg));
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t neg = ((w[j] >> 15) & 0x00010001u) * 0xFFFFu;   // 0xFFFF in each negative half
+            qn[g][j] = CENTER ? w[j] : (w[j] & neg);
+            qp[g][j] = CENTER ? w[j] : (w[j] & ~neg);
         }
     }
 
-    const int32_t *table = kv.block_table + (size_t)r * kv.max_blocks;
-    uint4 ma[4], mb[4];
+    // round rd: blocks base + 16 rd + 4 it + row, it = 0..3
+    uint4 mn[2][4], mx[2][4];
+    auto fetch = [&](int rd, uint4 (&lo)[4], uint4 (&hi)[4]) {
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int b = base + it * 4 + row;
-        if (b < N) {
-            const int page = clamp_page_quiet(table[b], kv.num_pages);
-            const uint8_t *mp = meta + ((size_t)page * kv.num_kv_heads + h) * kMetaBytes + is_max * 256 + slot * 32;
-            ma[it] = ld16(mp);
-            mb[it] = ld16(mp + 16);
-        } else {
-            ma[it] = make_uint4(0, 0, 0, 0);
-            mb[it] = make_uint4(0, 0, 0, 0);
+        for (int it = 0; it < 4; ++it) {
+            const int j = min(16 * rd + 4 * it + row, mine - 1);     // (clamped: the loads need no branch)
+            const int page = __shfl(page_of_lane, j);
+            const uint8_t *mp = meta + ((size_t)page * kv.num_kv_heads + h) * kMetaBytes + cl * 16;
+            lo[it] = ld16(mp);
+            hi[it] = ld16(mp + 256);
         }
-    }
+    };
+    auto reduce = [&](int rd, const uint4 (&lo)[4], const uint4 (&hi)[4]) {
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int b = base + it * 4 + row;
-        const uint32_t w[8] = {ma[it].x, ma[it].y, ma[it].z, ma[it].w, mb[it].x, mb[it].y, mb[it].z, mb[it].w};
-        float cs = -INFINITY;
+        for (int it = 0; it < 4; ++it) {
+            const int j = 16 * rd + 4 * it + row;
+            const uint32_t a[4] = {lo[it].x, lo[it].y, lo[it].z, lo[it].w};
+            const uint32_t b[4] = {hi[it].x, hi[it].y, hi[it].z, hi[it].w};
+            float cs = -INFINITY;
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float p = 0.0f;
+            for (int g = 0; g < G; ++g) {
+                float p = 0.0f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) p = dot2<DT>(w[j], qs[g][j], p);
-            p = row_sum16(p);
-            cs = fmaxf(cs, p * (CENTER ? 0.5f * kScale : kScale));
+                for (int x = 0; x < 4; ++x) p = dot2<DT>(a[x], qn[g][x], p);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) p = dot2<DT>(b[x], qp[g][x], p);
+                p = row_sum16(p);
+                cs = fmaxf(cs, p * (CENTER ? 0.5f * kScale : kScale));
+            }
+            if (cl == 0 && j < mine) {
+                scores[(size_t)s * kv.max_blocks + base + j] = cs;
+                if (scores_out) scores_out[(size_t)s * kv.max_blocks + base + j] = cs;
+            }
         }
-        if (cl == 0 && b < N) {
-            scores[(size_t)s * kv.max_blocks + b] = cs;
-            if (scores_out) scores_out[(size_t)s * kv.max_blocks + b] = cs;
+    };
+    const int nr = (mine + 15) / 16;
+    fetch(0, mn[0], mx[0]);
+#pragma unroll
+    for (int rd = 0; rd < kMaxRounds; ++rd) {
+        if (rd < nr) {
+            if (rd + 1 < nr) fetch(rd + 1, mn[(rd + 1) & 1], mx[(rd + 1) & 1]);
+            reduce(rd, mn[rd & 1], mx[rd & 1]);
         }
     }
 }
@@ -156,6 +176,10 @@ static hipError_t launch_score_t(const KvView &kv, int scorer, const void *q, co
                                  float *scores_out, hipStream_t st) {
     const int S = kv.batch * kv.num_kv_heads;
     const dim3 grid((kv.max_blocks + kScoreBlocks - 1) / kScoreBlocks, S);
+    // rounds per workgroup of score_kernel: as many (up to kMaxRounds) as still leave four workgroups per compute unit
+    long long per = ((long long)S * kv.max_blocks) / (4ll * compute_units() * kScoreBlocks);
+    const int rounds = per < 1 ? 1 : (per > kMaxRounds ? kMaxRounds : (int)per);
+    const dim3 grid_r((kv.max_blocks + kScoreBlocks * rounds - 1) / (kScoreBlocks * rounds), S);
     if constexpr (G >= 8) {
         if (scorer == 1)
             score_mfma_kernel<DT, G, 1><<<grid, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
@@ -165,11 +189,11 @@ static hipError_t launch_score_t(const KvView &kv, int scorer, const void *q, co
                                                               scores_out, ws.header);
     } else {
         if (scorer == 1)
-            score_kernel<DT, G, 1><<<grid, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
-                                                         scores_out, ws.header);
+            score_kernel<DT, G, 1><<<grid_r, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
+                                                           scores_out, ws.header, rounds);
         else
-            score_kernel<DT, G, 0><<<grid, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
-                                                         scores_out, ws.header);
+            score_kernel<DT, G, 0><<<grid_r, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
+                                                           scores_out, ws.header, rounds);
     }
     return hipGetLastError();
 }

@@ -121,13 +121,44 @@ struct SelectShared {
     uint4 stage[kSelectThreads / 64][16 * 17];   // per wave: one key slice, rows padded to 272 bytes
 };
 
+// How far a stream can still go, in chunks, given what the fold knows after n blocks.  AS_acc only grows and
+// AS_min only shrinks as more blocks are folded, so for any n* >= n
+//     P_acc(n*) >= AS_acc(n) / (AS_acc(n) + AS_min(n) (N - n*)),
+// and the right-hand side exceeds eps as soon as N - n* < (AS_acc(n) / AS_min(n)) (1 - eps) / eps: the head stops at
+// the first tested position from there on, whatever the blocks in between hold.  Lane g < G carries head g
+// (a stopped head needs its stop, lanes >= G nothing); the result, the largest need of the group plus one chunk
+// to spare against rounding, is the same in every lane.  Keys beyond it are never worth reading.
+template <int G>
+__device__ __forceinline__ int stop_bound(float Lacc, float Lmin, unsigned long long stop, int n, int N, int m, int KU,
+                                          float odds) {
+    const int lane = threadIdx.x & 63;
+    int need = 0;
+    if (lane < G) {
+        if (stop != ~0ull) {
+            need = (int)(stop >> 32);
+        } else {
+            // blocks that may be left over when the test first passes: fewer than ratio * odds (taken a little
+            // low, and one lower still: the bound must hold in binary32)
+            const float room = exp2_fast(Lacc - Lmin) * odds * 0.999f - 1.0f;
+            int nstar = room >= (float)N ? 0 : N - (int)fmaxf(room, 0.0f);     // (NaN compares false: N, no bound)
+            nstar = max(nstar, n + 1);
+            nstar = (int)min((long long)N, ((long long)nstar + m - 1) / m * m);   // the next tested position
+            need = nstar;
+        }
+    }
+#pragma unroll
+    for (int d = 1; d < 8; d <<= 1) need = max(need, __shfl_xor(need, d));
+    need = uniform(__shfl(need, 0));
+    return (need + KU - 1) / KU + 1;
+}
+
 // =================================================================================================
 // The fold (Algorithm 1 lines 12-18 in rank order).  Called by wave 0 of the workgroup that
 // published over the fold mark.  Lane g < G carries head g: (L_acc, L_min) over the folded chunks and the head's stop.
 // Leaves either with the stream's key side closed, or with the mark on the first unpublished chunk.
 // =================================================================================================
 template <int G>
-__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU, int fr) {
+__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU, int budget, int fr) {
     // fr: the chunk the mark was on, which is where the previous holder of the fold stopped
     const int lane = threadIdx.x & 63;
     StreamCtl *ctl = &ws.ctl[s];
@@ -154,7 +185,11 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
         const int ci = fr + lane / G;
         v = (ci < ws.max_chunks) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
     }
-    const int nch = uniform((int)(kp0 >> 32));
+    (void)kp0;
+    // chunks that may ever be folded: all of them, or those a fixed budget of blocks covers (the limit in the
+    // progress word is for the readers of keys and may be tighter: see stop_bound)
+    const int nch = ((budget > 0 ? min(N, budget) : N) + KU - 1) / KU;
+    const float odds = eps > 0.0f ? (1.0f - eps) / eps : INFINITY;      // (1 - eps) / eps of the stop test
     int fr_pub = fr;                           // frontier as the progress word shows it
     int walked = fr;
     bool finished = false;
@@ -221,8 +256,11 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
         fr_pub = walked;
         // the frontier (it opens the window for waiting workgroups), the state if the fold may have to be
         // handed over, and the next chunk words -- one round trip for all of it
-        if (lane == 0 && moved)
-            st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)nch << 32) | (unsigned)walked);
+        if (moved) {
+            const int lim = min(nch, stop_bound<G>(Lacc, Lmin, stop, walked * KU, N, m, KU, odds));
+            if (lane == 0)
+                st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)lim << 32) | (unsigned)walked);
+        }
         if (gap && lane < G) {
             st_relaxed(&ctl->Lacc[lane], Lacc);
             st_relaxed(&ctl->Lmin[lane], Lmin);
@@ -309,7 +347,7 @@ __device__ __forceinline__ void load_queries(SelectShared<G> &sh, const KvView &
 // =================================================================================================
 template <int DT, int G>
 __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8_t *__restrict__ q,
-                              const DecodeWs &ws, float eps, int m, int CB, int s, int c) {
+                              const DecodeWs &ws, float eps, int m, int CB, int budget, int s, int c) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = s % kv.num_kv_heads;
     const int ctx = stream_ctx(kv, s);
@@ -320,6 +358,10 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     // (the chunk's pages and valid-token counts are in LDS already: stage_pages)
     // B operand of the QK^T product (see load_queries): the same for every chunk of the stream
     const int n = lane & 15, kq = lane >> 4;
+    // Row r of the A operand stands for token 4*(r%4) + r/4, so that lane (kq, n) ends up with head n's logits of
+    // tokens kq, 4+kq, 8+kq, 12+kq: the value pass wants the four tokens whose value rows ITS lane (kq, *) loads,
+    // and finds them as the 16 bytes at [block][head][4 kq] of the stored logits.
+    const int arow = 4 * (n & 3) + (n >> 2);
     uint4 qb[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) qb[kk] = sh.qb[kk][lane];
@@ -354,16 +396,16 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
                 uint4 a[4];
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) a[kk] = stg[n * 17 + kk * 4 + kq];
+                for (int kk = 0; kk < 4; ++kk) a[kk] = stg[arow * 17 + kk * 4 + kq];
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
                 __builtin_amdgcn_wave_barrier();
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) acc = mfma_16x16x32<DT>(a[kk], qb[kk], acc);
-                // the lane now holds head n's logits of tokens 4*kq .. 4*kq+3
+                // the lane now holds head n's logits of tokens kq, 4+kq, 8+kq, 12+kq
                 const int valid = sh.valid[i];
                 float sc[4];
 #pragma unroll
-                for (int x = 0; x < 4; ++x) sc[x] = (4 * kq + x < valid) ? acc[x] * kScaleLog2 : -INFINITY;
+                for (int x = 0; x < 4; ++x) sc[x] = (4 * x + kq < valid) ? acc[x] * kScaleLog2 : -INFINITY;
                 if (n < G)
                     *reinterpret_cast<float4 *>(lg_out + ((size_t)i * G + n) * kPage + 4 * kq) =
                         make_float4(sc[0], sc[1], sc[2], sc[3]);
@@ -413,7 +455,7 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     if (lane >= 1 && lane < G) st_relaxed(cw + lane, w);
     unsigned long long old = 0;
     if (lane == 0) old = __hip_atomic_exchange(cw, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (uniform((int)(old == kAggArmed))) fold_stream<G>(kv, ws, s, eps, m, CB, c);
+    if (uniform((int)(old == kAggArmed))) fold_stream<G>(kv, ws, s, eps, m, CB, budget, c);
 }
 
 // =================================================================================================
@@ -421,7 +463,7 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
 // =================================================================================================
 template <int DT, int G>
 __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, const uint8_t *__restrict__ q,
-                                                                DecodeWs ws, float eps, int m, int CB,
+                                                                DecodeWs ws, float eps, int m, int CB, int budget,
                                                                 int window, int spin_limit,
                                                                 const int32_t *depth_hint) {
     __shared__ SelectShared<G> sh;
@@ -463,22 +505,22 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
     lds_barrier();
     if (!sh.go) return;
     if (threadIdx.x == 0) atomicAdd(&ws.ctl[s].k_blocks, min(CB, N - c * CB));     // traffic accounting
-    process_chunk<DT, G>(sh, kv, q, ws, eps, m, CB, s, c);
+    process_chunk<DT, G>(sh, kv, q, ws, eps, m, CB, budget, s, c);
 }
 
 template <int DT, int G>
 static hipError_t launch_select_t(const KvView &kv, const void *q, const DecodeWs &ws, float eps, int m,
-                                  const DecodePlan &plan, hipStream_t st) {
+                                  int budget, const DecodePlan &plan, hipStream_t st) {
     const unsigned grid = (unsigned)(kv.batch * kv.num_kv_heads) * (unsigned)plan.max_chunks;
     select_kernel<DT, G><<<grid, kSelectThreads, 0, st>>>(kv, (const uint8_t *)q, ws, eps, m, plan.chunk_blocks,
-                                               plan.window_chunks, plan.spin_limit, plan.depth_hint);
+                                               budget, plan.window_chunks, plan.spin_limit, plan.depth_hint);
     return hipGetLastError();
 }
 
 hipError_t launch_select(const KvView &kv, int dtype, int G, const void *q, const DecodeWs &ws, float eps,
-                         int m, const DecodePlan &plan, hipStream_t st) {
+                         int m, int budget, const DecodePlan &plan, hipStream_t st) {
 #define PSA_CASE(DT, GG) \
-    if (dtype == DT && G == GG) return launch_select_t<DT, GG>(kv, q, ws, eps, m, plan, st);
+    if (dtype == DT && G == GG) return launch_select_t<DT, GG>(kv, q, ws, eps, m, budget, plan, st);
     PSA_CASE(0, 1) PSA_CASE(0, 2) PSA_CASE(0, 4) PSA_CASE(0, 8)
     PSA_CASE(1, 1) PSA_CASE(1, 2) PSA_CASE(1, 4) PSA_CASE(1, 8)
 #undef PSA_CASE

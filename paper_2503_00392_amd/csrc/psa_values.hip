@@ -6,8 +6,8 @@
 // slices of the selected blocks -- every workgroup independent, no waiting, and only blocks
 // actually selected are read.
 //   attend_kernel    per value unit (chunk, stream) on the work list the selection kernel wrote:
-//                    p = exp(logit - chunk max), partial numerator sum_t p_t v_t per head (on the matrix
-//                    cores, the weights as a sum of two 16-bit halves), exp-sum and reference maximum
+//                    p = exp(logit - reference), partial numerator sum_t p_t v_t per head (on the
+//                    matrix cores, the weights as a sum of two 16-bit halves) and exp-sum
 //   finalize_kernel  merges a head's chunks (the online-softmax merge of line 11, all at once):
 //                    out_g = sum over the chunks of the head's own prefix of the partial numerators,
 //                    over the sum of the partial exp-sums, both rescaled to one reference maximum
@@ -16,31 +16,38 @@
 
 namespace psa {
 
-constexpr int kBatch = 4;   // slices a wave keeps in flight
-
-// CBMAX: blocks per value unit at most (32 for the default chunk size and below, else 64): it sizes the LDS
-// arrays, and with them how many workgroups fit a CU.
-template <int G, int CBMAX>
-struct AttendShared {
-    float p[CBMAX][kPage][G];              // logits, then softmax numerators
-    float st_acc[4][G][kHeadDim];          // per-wave partial numerators
-    float red[256];
-    int page[CBMAX];
-    int valid[CBMAX];
-    int cnt[G];
-    float Mref[G];
-    float lsum[G];
-};
-
 // Stop of head g of a stream: (n, P_acc) as the selection kernel left it, n = N when it never stopped.
 __device__ __forceinline__ int head_stop(const StreamCtl *ctl, int g, int N) {
     const unsigned long long st = ctl->stop[g];
     return (st != ~0ull && (int)(st >> 32) <= N) ? (int)(st >> 32) : N;
 }
 
-// One value unit: chunk c of stream s.  Called by all 256 threads of a workgroup.
-template <int DT, int G, int CBMAX>
-__device__ void attend_unit(AttendShared<G, CBMAX> &sh, const KvView &kv, const DecodeWs &ws, int CB, int s, int c) {
+// =================================================================================================
+// One workgroup per entry of the work list the selection kernel left (value unit = chunk c of stream s);
+// the grid is sized for the most there can be, and a workgroup beyond the list's end returns after one
+// load.  256 threads.  The four waves stream independently: wave w takes blocks w, w+4, ... of the unit,
+// two value slices (8 KiB) in flight at a time, and nothing is shared until the final merge.
+//   weights   p = exp(logit - L), L = per head the largest log-sum-exp of a block the head uses (the selection
+//             kernel left one per block): a reference every wave knows beforehand, so nothing is rescaled
+//             on the way and the four waves' sums simply add up.  (p <= 1, and the largest weight is at least
+//             1/16: the weights keep their precision as 16-bit halves.)
+//   numerator D[head][channel] += P[head][token] V[token][channel]: eight 16x16x16 products per block (one
+//             per channel of the lane's eight) with the weights split into hi + lo 16-bit halves.  The k
+//             index of both operands is the token: lane (rg, *) holds the value rows rg, 4+rg, 8+rg, 12+rg
+//             -- the rows its four loads fetched -- and the selection kernel stored the logits so that the
+//             16 bytes at [block][head][4 rg] are those same four tokens: one load, no transposition.
+//             A: row = head lane%16 (zero beyond G).  D: lane (rg, cl) gets heads 4rg..4rg+3 of channels
+//             8cl..8cl+7.
+// Output per unit and head: (L, sum of p, numerator[128]) for the final merge.
+// =================================================================================================
+template <int DT, int G>
+__global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int CB) {
+    __shared__ float st_acc[4][G][kHeadDim];
+    __shared__ float st_l[4][G];
+    __shared__ float st_ref[G];
+    if ((int)blockIdx.x >= ws.header[kValueCount]) return;
+    const int item = ws.value_items[blockIdx.x];
+    const int s = item / ws.max_chunks, c = item % ws.max_chunks;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, rg = lane >> 4, cl = lane & 15;
     const int h = s % kv.num_kv_heads;
     int ctx = kv.ctx_lens[s / kv.num_kv_heads];
@@ -50,96 +57,71 @@ __device__ void attend_unit(AttendShared<G, CBMAX> &sh, const KvView &kv, const 
     if (start >= N) return;
     const int nblk = min(CB, N - start);
     const StreamCtl *ctl = &ws.ctl[s];
-    int cnt[G], maxcnt = 0;
+    // blocks of this chunk each head uses: those before its stop
+    int maxcnt = 0, mycnt = 0;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        cnt[g] = min(nblk, max(0, head_stop(ctl, g, N) - start));
-        maxcnt = max(maxcnt, cnt[g]);
+        const int cg = min(nblk, max(0, head_stop(ctl, g, N) - start));
+        maxcnt = max(maxcnt, cg);
+        if (g == cl) mycnt = cg;
     }
     if (maxcnt == 0) return;    // no head of the group reaches this chunk
-
-    if (tid < maxcnt) {
-        const size_t at = (size_t)s * kv.max_blocks + start + tid;
-        sh.page[tid] = ws.ranked_page[at];
-        sh.valid[tid] = min(kPage, ctx - ws.order[at] * kPage);
-    }
-    lds_barrier();
-    // first batch of value slices, issued before the softmax bookkeeping so that they overlap it
-    Slice v[kBatch];
+    const size_t row0 = (size_t)s * kv.max_blocks + start;
+    // the wave's blocks are wave, wave + 4, ...: lane j fetches the page and the logical index of the j-th
+    const int jmax = (maxcnt - wave + 3) / 4;           // how many of them there are (may be <= 0)
+    int pg = 0, od = 0;
+    if (lane < jmax) { pg = ws.ranked_page[row0 + wave + 4 * lane]; od = ws.order[row0 + wave + 4 * lane]; }
+    // Reference exponent per head: the largest block log-sum-exp among the blocks the head uses (log2 units; the
+    // selection kernel left one per block and head).  Lane = (block, head) pairs, 64 / G blocks per load, then a
+    // butterfly over the lanes of a head: every lane l ends with the reference of head l % G, so lane (rg, cl < G)
+    // holds head cl's.  Every wave computes the same bits.
+    float Lc = -INFINITY;
+    {
+        const float *bl = ws.block_lse + row0 * G;
+        const int g = lane % G;
+        int cg = 0;
 #pragma unroll
-    for (int u = 0; u < kBatch; ++u) {
-        const int i = wave * kBatch + u;
-        if (i < maxcnt) {
-            v[u] = load_slice(value_slice(kv, sh.page[i], h), lane);
+        for (int x = 0; x < G; ++x) cg = (x == g) ? min(nblk, max(0, head_stop(ctl, x, N) - start)) : cg;
+        for (int i = lane / G; i < maxcnt; i += 64 / G) {
+            const float v = bl[(size_t)i * G + g];
+            if (i < cg) Lc = fmaxf(Lc, v);
         }
+#pragma unroll
+        for (int d = G; d < 64; d <<= 1) Lc = fmaxf(Lc, __shfl_xor(Lc, d));
     }
-    // logits of the chunk (contiguous in the workspace as [block][head][token]) -> LDS as
-    // [block][token][head], with each head's maximum over the blocks it uses
-    const float *lg = ws.logits + ((size_t)s * kv.max_blocks + start) * (kPage * G);
-    const int total = maxcnt * kPage * G;
-    float mx = -INFINITY;                       // thread-local, for head g = (tid / 16) % G
-    for (int idx = tid; idx < total; idx += 256) {
-        const int t = idx % kPage, g = (idx / kPage) % G, i = idx / (kPage * G);
-        const float x = lg[idx];
-        sh.p[i][t][g] = x;
-        if (i < cnt[g]) mx = fmaxf(mx, x);
-    }
-    // thread tid holds head (tid / 16) % G: reduce each 16-lane row, then the 16/G rows of a head
-    mx = row_max16(mx);
-    if (cl == 0) sh.red[tid >> 4] = mx;
-    lds_barrier();
-    if (tid < G) {
-        float M = -INFINITY;
-        for (int j = tid; j < 16; j += G) M = fmaxf(M, sh.red[j]);
-        sh.Mref[tid] = M;
-    }
-    lds_barrier();
-    float sum = 0.0f;
-    for (int idx = tid; idx < total; idx += 256) {
-        const int t = idx % kPage, g = (idx / kPage) % G, i = idx / (kPage * G);
-        float *p = &sh.p[i][t][g];
-        const float e = (i < cnt[g]) ? exp2_fast(*p - sh.Mref[g]) : 0.0f;   // masked tokens hold -inf
-        *p = e;
-        sum += e;
-    }
-    sum = row_sum16(sum);
-    if (cl == 0) sh.red[16 + (tid >> 4)] = sum;
-    lds_barrier();
-    if (tid < G) {
-        float l = 0.0f;
-        for (int j = tid; j < 16; j += G) l += sh.red[16 + j];
-        sh.lsum[tid] = l;
-    }
+    const float *lg = ws.logits + row0 * (kPage * G) + (size_t)(cl < G ? cl : 0) * kPage + 4 * rg;
 
-    // Numerators on the matrix cores: per block D[head][channel] += P[head][token] V[token][channel] as eight
-    // 16x16x16 products (one per channel of the lane's eight) with the softmax weights split into two
-    // 16-bit halves (hi + lo keeps fp32 accuracy; the values are 16-bit already).  The k index of both
-    // operands is the token: lane (rg, *) holds tokens rg, 4+rg, 8+rg, 12+rg -- exactly the rows its four
-    // loads fetched -- so the B operand is four 16-bit picks from registers, no transposition.  A: row =
-    // head lane%16 (zero beyond G).  D: lane (rg, cl) gets heads 4rg..4rg+3 of channel 8cl + tile.
     f32x4_t acc[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t) acc[t] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
-    for (int i0 = wave * kBatch; i0 < maxcnt; i0 += 4 * kBatch) {
-        if (i0 != wave * kBatch) {
+    float l = 0.0f;
+    for (int j0 = 0; j0 < jmax; j0 += 2) {
+        Slice v[2];
+        float4 x[2];
+        int valid[2], blk[2];
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                if (i0 + u < maxcnt) {
-                    v[u] = load_slice(value_slice(kv, sh.page[i0 + u], h), lane);
-                }
-            }
+        for (int u = 0; u < 2; ++u) {              // (index clamped, loads made anyway: no branch around a load)
+            const int j = min(j0 + u, jmax - 1);
+            blk[u] = wave + 4 * j;
+            v[u] = load_slice(value_slice(kv, __shfl(pg, j), h), lane);
+            x[u] = *reinterpret_cast<const float4 *>(lg + (size_t)blk[u] * (kPage * G));
+            valid[u] = min(kPage, ctx - __shfl(od, j) * kPage);
         }
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            const int i = i0 + u;
-            if (i < maxcnt) {
-                if (sh.valid[i] < kPage) zero_invalid_rows(v[u], rg, sh.valid[i]);
+        for (int u = 0; u < 2; ++u) {
+            if (j0 + u < jmax) {
+                if (valid[u] < kPage) zero_invalid_rows(v[u], rg, valid[u]);
+                // tokens beyond `valid` hold -inf logits; blocks beyond the head's stop, and heads beyond the
+                // group, weigh nothing
+                const bool on = cl < G && blk[u] < mycnt;
+                float pw[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
                 uint32_t hi[4], lo[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const float pj = cl < G ? sh.p[i][4 * j + rg][cl] : 0.0f;
-                    split16<DT>(pj, hi[j], lo[j]);
+                    pw[j] = on ? exp2_fast(pw[j] - Lc) : 0.0f;      // (a head that uses no block of the unit is never `on`)
+                    split16<DT>(pw[j], hi[j], lo[j]);
                 }
+                l += (pw[0] + pw[1]) + (pw[2] + pw[3]);
                 const uint2 a_hi = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
                 const uint2 a_lo = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
 #pragma unroll
@@ -154,32 +136,30 @@ __device__ void attend_unit(AttendShared<G, CBMAX> &sh, const KvView &kv, const 
             }
         }
     }
+    // the exp-sum over the four row groups, then the four waves through LDS (one reference: plain sums)
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int g = 4 * rg + r;
         if (g < G) {
 #pragma unroll
-            for (int t = 0; t < 8; ++t) sh.st_acc[wave][g][cl * 8 + t] = acc[t][r];
+            for (int t = 0; t < 8; ++t) st_acc[wave][g][cl * 8 + t] = acc[t][r];
         }
     }
-    lds_barrier();
+    if (rg == 0 && cl < G) st_l[wave][cl] = l;
+    if (wave == 0 && rg == 0 && cl < G) st_ref[cl] = Lc;
+    __syncthreads();
     float *dst = ws.partial + ((size_t)s * ws.max_units + c) * G * kPartialStride;
     for (int idx = tid; idx < G * kHeadDim; idx += 256) {
         const int g = idx / kHeadDim, ch = idx % kHeadDim;
         dst[g * kPartialStride + 4 + ch] =
-            (sh.st_acc[0][g][ch] + sh.st_acc[1][g][ch]) + (sh.st_acc[2][g][ch] + sh.st_acc[3][g][ch]);
-        if (ch == 0) { dst[g * kPartialStride] = sh.Mref[g]; dst[g * kPartialStride + 1] = sh.lsum[g]; }
+            (st_acc[0][g][ch] + st_acc[1][g][ch]) + (st_acc[2][g][ch] + st_acc[3][g][ch]);
+        if (ch == 0) {
+            dst[g * kPartialStride] = st_ref[g];
+            dst[g * kPartialStride + 1] = (st_l[0][g] + st_l[1][g]) + (st_l[2][g] + st_l[3][g]);
+        }
     }
-}
-
-// One workgroup per entry of the work list the selection kernel left; the grid is sized for the most
-// there can be, and a workgroup beyond the list's end returns after one load.
-template <int DT, int G, int CBMAX>
-__global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int CB) {
-    __shared__ AttendShared<G, CBMAX> sh;
-    if ((int)blockIdx.x >= ws.header[kValueCount]) return;
-    const int item = ws.value_items[blockIdx.x];
-    attend_unit<DT, G, CBMAX>(sh, kv, ws, CB, item / ws.max_chunks, item % ws.max_chunks);
 }
 
 constexpr int kUnitLanes = 16;   // value units merged side by side by one workgroup
@@ -285,10 +265,7 @@ __global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, i
 template <int DT, int G>
 static hipError_t launch_attend_t(const KvView &kv, const DecodeWs &ws, const DecodePlan &plan, hipStream_t st) {
     const unsigned grid = (unsigned)(kv.batch * kv.num_kv_heads) * (unsigned)plan.max_chunks;
-    if (plan.chunk_blocks <= 32)
-        attend_kernel<DT, G, 32><<<grid, 256, 0, st>>>(kv, ws, plan.chunk_blocks);
-    else
-        attend_kernel<DT, G, kMaxChunkBlocks><<<grid, 256, 0, st>>>(kv, ws, plan.chunk_blocks);
+    attend_kernel<DT, G><<<grid, 256, 0, st>>>(kv, ws, plan.chunk_blocks);
     return hipGetLastError();
 }
 
