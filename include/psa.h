@@ -50,7 +50,9 @@ typedef enum { PSA_F16 = 0, PSA_BF16 = 1 } psa_dtype;
 /* Bits of the sticky device error word (psa_read_device_error). */
 enum {
     PSA_DEVERR_PAGE_RANGE = 1,   /* block-table entry outside [0, num_pages): page 0 was used   */
-    PSA_DEVERR_CTX_RANGE = 2     /* ctx_len < 0 or > 16*max_blocks_per_seq: clamped             */
+    PSA_DEVERR_CTX_RANGE = 2,    /* ctx_len < 0 or > 16*max_blocks_per_seq: clamped             */
+    PSA_DEVERR_STALLED = 4       /* the stop rule of a (request, KV head) gave up waiting for keys (seconds):
+                                    its query heads' results are not valid.  Not expected to happen           */
 };
 
 /* How a block's criticality score is computed from its metadata (Algorithm 1, line 5: CS = q . B_meta).

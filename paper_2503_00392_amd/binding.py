@@ -17,7 +17,7 @@ _LIB_PATH = os.path.join(_HERE, "libpsa.so")
 
 PSA_F16, PSA_BF16 = 0, 1
 PSA_OK = 0
-DEVERR_PAGE_RANGE, DEVERR_CTX_RANGE = 1, 2
+DEVERR_PAGE_RANGE, DEVERR_CTX_RANGE, DEVERR_STALLED = 1, 2, 4
 
 
 class PsaError(RuntimeError):

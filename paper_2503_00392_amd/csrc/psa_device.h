@@ -59,7 +59,7 @@ __device__ __forceinline__ const uint8_t *value_slice(const KvView &kv, int loc,
 // stop rule, and in which values are read.
 //
 // Per-stream control block of the progressive kernel: three 128-byte lines, so that the progress word
-// that waiting workgroups poll, the traffic counter and the fold's own state never share a cache line
+// that waiting workgroups poll, the traffic counter and the heads' stops never share a cache line
 // (accesses to one line are served one after the other).
 struct alignas(128) StreamCtl {
     // line 0: progress, written by the folding wave only, as ONE 64-bit store; polled by workgroups that
@@ -71,10 +71,9 @@ struct alignas(128) StreamCtl {
     // line 1: counters
     int32_t k_blocks;   // key slices loaded (traffic accounting)
     int32_t pad1[31];
-    // line 2: fold state, owned by the folding wave
-    float Lacc[8];               // per head: log2 of AS_acc over the folded chunks
-    float Lmin[8];               // per head: log2 of AS_min over the folded chunks
+    // line 2: the fold's result, written when it closes the stream
     unsigned long long stop[8];  // per head: (n << 32) | float bits of P_acc at the stop; ~0 = not stopped
+    int32_t pad2[16];
 };
 
 struct DecodeWs {
@@ -84,7 +83,7 @@ struct DecodeWs {
     float *scores;          // [S][max_blocks]
     int32_t *order;         // [S][max_blocks]  ranked logical blocks
     int32_t *ranked_page;   // [S][max_blocks]  physical page of each ranked block
-    unsigned long long *agg;  // [S][max_chunks][G]  (L_chunk, Lmin_chunk) as two floats, or the NaN sentinel
+    unsigned long long *agg;  // [S][max_chunks][G]  (L_chunk, Lmin_chunk) as two floats, or kAggSentinel
     float *block_lse;       // [S][max_blocks][G]  log2 of each ranked block's AS (Algorithm 1 line 10)
     float *logits;          // [S][max_blocks][G][16]  scaled logits (log2 units) by ranked block; position
                             // 4*r + j of a (block, head) row holds token 4*j + r
@@ -98,10 +97,8 @@ constexpr int kPartialStride = 132;  // M, l, pad, pad, acc[128]
 constexpr int kMaxWindowChunks = 256; // chunks read beyond the fold's frontier, at most
 constexpr int kValueCount = 32;      // index of the value-item counter in the workspace header
 // A chunk word holds (L_chunk, Lmin_chunk) as two floats once the chunk is published.  Before that
-// it holds one of two NaN patterns no computation produces: "not published", or -- word 0 only --
-// "not published, and the fold stopped here": whoever publishes over that one carries on folding.
+// it holds a NaN pattern no publisher writes: "not published".
 constexpr unsigned long long kAggSentinel = 0xFFFFFFFFFFFFFFFFull;
-constexpr unsigned long long kAggArmed = 0xFFFFFFFFFFFFFFFEull;
 
 __device__ __forceinline__ void set_error(int32_t *header, int bit) { atomicOr(&header[1], bit); }
 

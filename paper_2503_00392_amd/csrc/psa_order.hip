@@ -132,12 +132,11 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         const unsigned nch = (unsigned)((nlim + KU - 1) / KU);
         c->k_blocks = 0;
         c->key_progress = (unsigned long long)nch << 32;                                  // frontier 0
-        for (int g = 0; g < 8; ++g) { c->Lacc[g] = -INFINITY; c->Lmin[g] = INFINITY; c->stop[g] = ~0ull; }
+        for (int g = 0; g < 8; ++g) c->stop[g] = ~0ull;
     }
     if (part == 0) {
         unsigned long long *a = ws.agg + (size_t)s * ws.max_chunks * G;
-        // chunk 0 starts out as the place where the fold waits: its publisher starts folding
-        for (int i = tid; i < ws.max_chunks * G; i += nthreads) a[i] = (i == 0) ? kAggArmed : kAggSentinel;
+        for (int i = tid; i < ws.max_chunks * G; i += nthreads) a[i] = kAggSentinel;      // nothing published yet
     }
 
     // LDS carve-up of the bucket path: 10*Np bytes + scratch

@@ -102,6 +102,95 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
 }
 
 // =================================================================================================
+// The same scoring, page by page instead of stream by stream, for KV-head counts that divide 16.  The metadata of
+// a page is [KV head][min | max], 512 bytes per head, so the KV heads of one page are contiguous (4 KiB with eight):
+// a workgroup that scores ALL heads of its blocks reads whole pages' metadata at a time, where the stream-by-stream
+// kernel picks one isolated 512-byte record out of every page.
+// grid (ceil(max_blocks / nb), batch), 256 threads; a workgroup covers nb consecutive blocks (nb <= 64, a multiple
+// of 64/H) of one request.  The 16 rows of the workgroup (4 waves x 4 rows of 16 lanes) form a (16/H blocks) x
+// (H heads) tile per step: row rho takes head rho % H of block step * 16/H + rho / H; four steps are a round, and
+// a round's records stay in flight while the round before is computed.
+// =================================================================================================
+template <int DT, int G, int CENTER>
+__global__ __launch_bounds__(256) void score_pages_kernel(KvView kv, const uint8_t *__restrict__ q,
+                                                          const uint8_t *__restrict__ meta,
+                                                          float *__restrict__ scores,
+                                                          float *__restrict__ scores_out, int32_t *header, int nb) {
+    const int r = blockIdx.y, H = kv.num_kv_heads;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, row = lane >> 4, cl = lane & 15;
+    const int rho = wave * 4 + row, h = rho % H, sub = rho / H, BS = 16 / H;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 2) header[threadIdx.x] = 0;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 2) header[kValueCount] = 0;   // value work list
+    const int ctx = ctx_clamped_quiet(kv, r);
+    const int N = (ctx + kPage - 1) / kPage;
+    const int base = blockIdx.x * nb;
+    if (base >= N) return;
+    const int mine = min(nb, N - base);                 // blocks of this workgroup
+    const int32_t *table = kv.block_table + (size_t)r * kv.max_blocks;
+    const int page_of_lane = clamp_page_quiet(table[base + min(lane, mine - 1)], kv.num_pages);   // lane = block
+    const int s = r * H + h;
+
+    uint32_t qn[G][4], qp[G][4];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const uint4 a = ld16(q + ((size_t)(r * kv.num_q_heads + h * G + g) * kHeadDim + cl * 8) * 2);
+        const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t neg = ((w[j] >> 15) & 0x00010001u) * 0xFFFFu;   // 0xFFFF in each negative half
+            qn[g][j] = CENTER ? w[j] : (w[j] & neg);
+            qp[g][j] = CENTER ? w[j] : (w[j] & ~neg);
+        }
+    }
+
+    uint4 mn[2][4], mx[2][4];
+    auto fetch = [&](int rd, uint4 (&lo)[4], uint4 (&hi)[4]) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int j = min((4 * rd + it) * BS + sub, mine - 1);     // (clamped: the loads need no branch)
+            const int page = __shfl(page_of_lane, j);
+            const uint8_t *mp = meta + ((size_t)page * H + h) * kMetaBytes + cl * 16;
+            lo[it] = ld16(mp);
+            hi[it] = ld16(mp + 256);
+        }
+    };
+    auto reduce = [&](int rd, const uint4 (&lo)[4], const uint4 (&hi)[4]) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int j = (4 * rd + it) * BS + sub;
+            const uint32_t a[4] = {lo[it].x, lo[it].y, lo[it].z, lo[it].w};
+            const uint32_t b[4] = {hi[it].x, hi[it].y, hi[it].z, hi[it].w};
+            float cs = -INFINITY;
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                float p = 0.0f;
+#pragma unroll
+                for (int x = 0; x < 4; ++x) p = dot2<DT>(a[x], qn[g][x], p);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) p = dot2<DT>(b[x], qp[g][x], p);
+                p = row_sum16(p);
+                cs = fmaxf(cs, p * (CENTER ? 0.5f * kScale : kScale));
+            }
+            if (cl == 0 && j < mine) {
+                scores[(size_t)s * kv.max_blocks + base + j] = cs;
+                if (scores_out) scores_out[(size_t)s * kv.max_blocks + base + j] = cs;
+            }
+        }
+    };
+    const int nr = (mine + 4 * BS - 1) / (4 * BS);       // rounds: at most 64 / (4 BS) = 16
+    fetch(0, mn[0], mx[0]);
+#pragma nounroll
+    for (int rd = 0; rd < nr; rd += 2) {
+        if (rd + 1 < nr) fetch(rd + 1, mn[1], mx[1]);
+        reduce(rd, mn[0], mx[0]);
+        if (rd + 1 < nr) {
+            if (rd + 2 < nr) fetch(rd + 2, mn[0], mx[0]);
+            reduce(rd + 1, mn[1], mx[1]);
+        }
+    }
+}
+
+// =================================================================================================
 // Scoring on the matrix cores (used at G = 8, where the version above is bound by its arithmetic; at G <= 4
 // it is the faster one, its loads being fully coalesced).  Upper bound (CENTER = 0):
 //   UB[g][b] = (1/sqrt d) sum_c max(q_c kmin_c, q_c kmax_c) = (1/sqrt d) (q- . kmin + q+ . kmax)
@@ -187,6 +276,20 @@ static hipError_t launch_score_t(const KvView &kv, int scorer, const void *q, co
         else
             score_mfma_kernel<DT, G, 0><<<grid, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
                                                               scores_out, ws.header);
+    } else if (kv.num_kv_heads > 1 && 16 % kv.num_kv_heads == 0) {
+        // all KV heads of a page together; blocks per workgroup: as many (up to 64) as still leave four
+        // workgroups per compute unit, in whole rounds of four steps
+        const int round_blocks = 4 * (16 / kv.num_kv_heads);
+        long long want = ((long long)kv.batch * kv.max_blocks) / (4ll * compute_units());
+        int nb = (int)(want / round_blocks) * round_blocks;
+        nb = nb < round_blocks ? round_blocks : (nb > 64 ? 64 : nb);
+        const dim3 grid_p((kv.max_blocks + nb - 1) / nb, kv.batch);
+        if (scorer == 1)
+            score_pages_kernel<DT, G, 1><<<grid_p, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
+                                                                 scores_out, ws.header, nb);
+        else
+            score_pages_kernel<DT, G, 0><<<grid_p, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
+                                                                 scores_out, ws.header, nb);
     } else {
         if (scorer == 1)
             score_kernel<DT, G, 1><<<grid_r, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,

@@ -9,11 +9,12 @@
 // fastest: the hardware hands workgroups out in that order, so each stream's chunks start in rank
 // order, interleaved over the streams, and a compute unit takes the next one the moment a slot is free
 // (four fit).  A workgroup
-//   1. returns at once if its chunk lies beyond the stream's blocks or the stream is closed;
+//   1. returns at once if its chunk lies beyond the stream's blocks or beyond the limit the fold has set
+//      (the stream is closed, or cannot go that far any more);
 //   2. fetches the chunk's page numbers and waits (napping about a microsecond between looks at one
 //      progress word, a bounded number of times) until the chunk is inside the read-ahead window --
 //      chunks read beyond the fold's frontier are at most max(window, frontier/4), 256 at most, which
-//      bounds the keys read beyond the stop -- or the stream closes before it (with a second tier, a
+//      bounds the keys read beyond the stop -- or the limit falls below it (with a second tier, a
 //      chunk that has slices in host memory waits until the fold is one chunk away, unless it lies
 //      inside the depth hint: the host link is too slow to read ahead over it);
 //   3. reads the chunk's key slices (each wave keeps 4 slices = 16 KiB in flight, loaded as coalesced
@@ -22,24 +23,23 @@
 //      cores (heads beyond G are zero columns), stores them for the value pass, and reduces each
 //      block's log-sum-exp L_b (= log AS of line 10);
 //   4. publishes the chunk's (log-sum-exp, minimum) of L_b per head as one 64-bit word per head.
-// The wait of step 2 is a courtesy, not a dependency: no workgroup needs another one to proceed
-// (when the polls run out it simply reads its chunk), so the grid drains whatever order it runs in.
+// The wait of step 2 is a courtesy, not a dependency: no chunk workgroup needs anything to proceed
+// (when the looks run out it simply reads its chunk), so the grid drains whatever order it runs in.
 // THE FOLD applies lines 12-17 strictly in rank order: AS_acc, AS_min, N_left and P_acc at the end
 // of each published chunk after the frontier and, in the first chunk where P_acc exceeds the
-// threshold, with a prefix scan over the chunk's blocks to find the head's exact stop.  It is a
-// token: exactly one wave at a time folds.  When it reaches a chunk that is not yet published it
-// marks that chunk's word "the fold waits here" and returns; the workgroup that later publishes
-// over the mark (an atomic exchange tells it) picks the fold up from the state left in the control
-// block.  So nobody polls for the fold and nothing is locked.  Once every head has stopped (or the
-// blocks ran out) the fold closes the stream: the chunks beyond what it used are never read.
+// threshold, with a prefix scan over the chunk's blocks to find the head's exact stop.  One wave per
+// stream does it, in workgroups of its own at the head of the grid (so they start first): it looks at the
+// words of the next chunks, folds what is published, moves the frontier, tells the readers how far the
+// stream can still go (stop_bound), and looks again.  Once every head has stopped (or the blocks ran
+// out) it closes the stream -- the chunks beyond what it used are never read -- and puts the stream's
+// value units on the work list of the value pass.
 //
 // Communication between workgroups: every shared word is read and written with relaxed agent-scope
 // atomics (coherent accesses); a writer waits for its data stores to complete before it stores the
-// word that announces them (chunk word 0, the progress word, the fold mark), and a reader looks at
-// the announcing word before it issues the loads that depend on it.  Accesses to one cache line are
-// served one at a time (tens of nanoseconds each), which is why one thread per workgroup touches the
-// stream's control block and the fold hand-over goes through the chunks' own words.  The logits
-// are plain stores: their reader is the next kernel.
+// word that announces them (the chunk words, the progress word), and a reader looks at the announcing
+// word before it issues the loads that depend on it.  Accesses to one cache line are served one at a
+// time (tens of nanoseconds each), which is why one thread per workgroup touches the stream's control
+// block.  The logits are plain stores: their reader is the next kernel.
 //
 // The fold is one scan in rank order and every reduction has a fixed shape, so results are bitwise
 // reproducible although the scheduling is dynamic.
@@ -153,13 +153,18 @@ __device__ __forceinline__ int stop_bound(float Lacc, float Lmin, unsigned long 
 }
 
 // =================================================================================================
-// The fold (Algorithm 1 lines 12-18 in rank order).  Called by wave 0 of the workgroup that
-// published over the fold mark.  Lane g < G carries head g: (L_acc, L_min) over the folded chunks and the head's stop.
-// Leaves either with the stream's key side closed, or with the mark on the first unpublished chunk.
+// The fold (Algorithm 1 lines 12-18 in rank order): one wave per stream, from the kernel's first moment until
+// the stream closes.  Lane g < G carries head g: (L_acc, L_min) over the folded chunks and the head's stop.
+// The wave looks at the words of the next chunks (one load covers 64 / G of them), folds those that are
+// published, moves the frontier, and looks again; with nothing new it naps a fraction of a microsecond first.
+// It waits for nothing but chunks whose workgroups are in this kernel's grid and never wait for anything
+// themselves beyond a bounded number of looks, so it always ends; a count of looks bounds it all the same
+// (kFoldPatience: seconds), after which the stream is closed as it stands and PSA_DEVERR_STALLED is raised.
 // =================================================================================================
+constexpr int kFoldPatience = 1 << 22;
+
 template <int G>
-__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU, int budget, int fr) {
-    // fr: the chunk the mark was on, which is where the previous holder of the fold stopped
+__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU, int budget) {
     const int lane = threadIdx.x & 63;
     StreamCtl *ctl = &ws.ctl[s];
     const int ctx = stream_ctx(kv, s);
@@ -167,37 +172,32 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
     constexpr int CPR = 64 / G;                // chunks per load round: lane = (chunk j, head)
     const unsigned long long *agg = ws.agg + (size_t)s * ws.max_chunks * G;
     const int hg = lane < G ? lane : 0;
-    // One round trip for everything the fold starts from: the chunk limit (all chunks unless the ranking
-    // kernel set a budget), the state the previous holder left, and the words of the next 4*CPR chunks
-    // (words of chunks that will never be published hold the "not published" pattern).
-    const unsigned long long kp0 = ld_relaxed(&ctl->key_progress);
-    float Lacc = -INFINITY, Lmin = INFINITY;
-    unsigned long long stop = 0ull;            // lanes >= G count as stopped
-    if (lane < G) {
-        Lacc = ld_relaxed(&ctl->Lacc[lane]);
-        Lmin = ld_relaxed(&ctl->Lmin[lane]);
-        stop = ld_relaxed(&ctl->stop[lane]);
-    }
-    // (The fold runs rarely and on one wave, so its instructions are usually not in the instruction
-    // cache: the loops below are deliberately not unrolled -- compact code beats straight-line code here.)
-    unsigned long long v;
-    {
-        const int ci = fr + lane / G;
-        v = (ci < ws.max_chunks) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
-    }
-    (void)kp0;
     // chunks that may ever be folded: all of them, or those a fixed budget of blocks covers (the limit in the
     // progress word is for the readers of keys and may be tighter: see stop_bound)
     const int nch = ((budget > 0 ? min(N, budget) : N) + KU - 1) / KU;
+    if (nch == 0) return;                      // an empty request: the ranking kernel left it closed
     const float odds = eps > 0.0f ? (1.0f - eps) / eps : INFINITY;      // (1 - eps) / eps of the stop test
-    int fr_pub = fr;                           // frontier as the progress word shows it
-    int walked = fr;
+    float Lacc = -INFINITY, Lmin = INFINITY;
+    unsigned long long stop = lane < G ? ~0ull : 0ull;                  // lanes >= G count as stopped
+    int fr = 0, walked = 0, looks = 0;
     bool finished = false;
-    while (true) {
+    while (!finished) {
         // v: the words of chunks fr .. fr+CPR-1; k = how many leading ones are completely published
-        const unsigned long long pub = __ballot(v < kAggArmed);
+        unsigned long long v;
+        {
+            const int ci = fr + lane / G;
+            v = (ci < nch) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
+        }
+        const unsigned long long pub = __ballot(v != kAggSentinel);
         const int k = ((pub == ~0ull) ? 64 : (__ffsll((long long)~pub) - 1)) / G;
-        const bool gap = k < CPR;
+        if (k == 0) {
+            if (++looks > kFoldPatience) {
+                if (lane == 0) set_error(ws.header, PSA_DEVERR_STALLED);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(8);
+            continue;
+        }
 #pragma nounroll
         for (int j = 0; j < k && !finished; ++j) {
             const unsigned long long a = shfl_u64(v, j * G + hg);
@@ -252,46 +252,10 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
         fr = walked;
         if (fr >= nch) finished = true;
         if (finished) break;
-        const bool moved = walked != fr_pub;
-        fr_pub = walked;
-        // the frontier (it opens the window for waiting workgroups), the state if the fold may have to be
-        // handed over, and the next chunk words -- one round trip for all of it
-        if (moved) {
-            const int lim = min(nch, stop_bound<G>(Lacc, Lmin, stop, walked * KU, N, m, KU, odds));
-            if (lane == 0)
-                st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)lim << 32) | (unsigned)walked);
-        }
-        if (gap && lane < G) {
-            st_relaxed(&ctl->Lacc[lane], Lacc);
-            st_relaxed(&ctl->Lmin[lane], Lmin);
-            st_relaxed(&ctl->stop[lane], stop);
-        }
-        {
-            const int ci = fr + lane / G;
-            v = (ci < nch) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
-        }
-        stores_done();
-        if (!gap) continue;
-        {
-            const unsigned long long pub2 = __ballot(v < kAggArmed);
-            const int ones2 = (pub2 == ~0ull) ? 64 : (__ffsll((long long)~pub2) - 1);
-            if (ones2 >= G) continue;          // chunk fr was published meanwhile: carry on folding
-        }
-        // chunk fr is not published: mark it (the state is in place); whoever publishes it carries on
-        unsigned long long seen = 0;
-        if (lane == 0) {
-            unsigned long long expected = kAggSentinel;
-            __hip_atomic_compare_exchange_strong(const_cast<unsigned long long *>(&agg[(size_t)fr * G]), &expected,
-                                                 kAggArmed, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT);
-            seen = expected;
-        }
-        if (uniform((int)(seen == kAggSentinel))) return;
-        // published between the look and the mark: fetch the words again and carry on
-        {
-            const int ci = fr + lane / G;
-            v = (ci < nch) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
-        }
+        // the frontier opens the window for waiting workgroups; the limit tells them how far the stream can still go
+        const int lim = min(nch, stop_bound<G>(Lacc, Lmin, stop, walked * KU, N, m, KU, odds));
+        if (lane == 0)
+            st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)lim << 32) | (unsigned)walked);
     }
     // every head has stopped, or the blocks ran out: close the key side (limit = frontier)
     if (lane < G) st_relaxed(&ctl->stop[lane], stop);
@@ -448,18 +412,15 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
         }
     }
     unsigned long long w = pack2(aggL, aggMin);
-    if (w >= kAggArmed) w = kAggArmed - 1;     // a NaN that happens to look like one of the marks
-    unsigned long long *cw = &ws.agg[((size_t)s * ws.max_chunks + c) * G];
-    // The G words need no order among themselves: the fold takes a chunk only when it sees all of
-    // them, and a chunk it finds half published it simply looks at again.
-    if (lane >= 1 && lane < G) st_relaxed(cw + lane, w);
-    unsigned long long old = 0;
-    if (lane == 0) old = __hip_atomic_exchange(cw, w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (uniform((int)(old == kAggArmed))) fold_stream<G>(kv, ws, s, eps, m, CB, budget, c);
+    if (w == kAggSentinel) w = kAggSentinel - 1;     // a NaN pair that happens to look like "not published"
+    // The G words need no order among themselves: the fold takes a chunk only when it sees all of them.
+    if (lane < G) st_relaxed(&ws.agg[((size_t)s * ws.max_chunks + c) * G + lane], w);
 }
 
 // =================================================================================================
-// grid = S * max_chunks workgroups, streams fastest; 256 threads.
+// grid = folders + S * max_chunks workgroups of 256 threads.  The first `folders` = ceil(S / 4) workgroups are the
+// folds, one wave per stream (they start first and stay until their streams close); then one workgroup per
+// (chunk, stream), streams fastest.
 // =================================================================================================
 template <int DT, int G>
 __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, const uint8_t *__restrict__ q,
@@ -468,7 +429,13 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
                                                                 const int32_t *depth_hint) {
     __shared__ SelectShared<G> sh;
     const int S = kv.batch * kv.num_kv_heads;
-    const int s = blockIdx.x % S, c = blockIdx.x / S;
+    const int folders = (S + 3) / 4;
+    if ((int)blockIdx.x < folders) {
+        const int fs = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
+        if (fs < S) fold_stream<G>(kv, ws, fs, eps, m, CB, budget);
+        return;
+    }
+    const int s = ((int)blockIdx.x - folders) % S, c = ((int)blockIdx.x - folders) / S;
     const int N = (stream_ctx(kv, s) + kPage - 1) / kPage;
     if (c * CB >= N) return;
     load_queries<G>(sh, kv, q, s);
@@ -511,7 +478,8 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
 template <int DT, int G>
 static hipError_t launch_select_t(const KvView &kv, const void *q, const DecodeWs &ws, float eps, int m,
                                   int budget, const DecodePlan &plan, hipStream_t st) {
-    const unsigned grid = (unsigned)(kv.batch * kv.num_kv_heads) * (unsigned)plan.max_chunks;
+    const unsigned S = (unsigned)(kv.batch * kv.num_kv_heads);
+    const unsigned grid = (S + 3) / 4 + S * (unsigned)plan.max_chunks;
     select_kernel<DT, G><<<grid, kSelectThreads, 0, st>>>(kv, (const uint8_t *)q, ws, eps, m, plan.chunk_blocks,
                                                budget, plan.window_chunks, plan.spin_limit, plan.depth_hint);
     return hipGetLastError();
