@@ -71,19 +71,43 @@ def load_read_probe():
     return lib.bench_stream_read_probe
 
 
+KERNEL_SOURCES = {"select_kernel": ["psa_select.hip", "psa_device.h"], "attend_kernel": ["psa_values.hip", "psa_attend.h", "psa_device.h"],
+                  "score_kernel": ["psa_score.hip", "psa_device.h"]}
+
+
+def kernel_source_hash(kernel: str) -> str:
+    """sha256 (first 16 hex digits) over the source files a kernel is built from."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES.get(kernel, []):
+        with open(os.path.join(ROOT, "paper_2503_00392_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def read_measured_traffic(workload: str, kernel: str):
     """HBM bytes per launch of `kernel` on `workload` as measured with hardware counters (two
     rocprofv3 --pmc runs, scaled by a plain copy of known size) and recorded in the text summary
-    profiles/hbm_traffic_<workload>.md as a line `traffic_bytes_per_launch <kernel> = <number>`;
-    None if there is no such record."""
+    profiles/hbm_traffic_<workload>.md as a line `traffic_bytes_per_launch <kernel> = <number>`, next to a line
+    `traffic_source_hash <kernel> = <hash>` of the kernel's sources at the time.  Returns (bytes, stamp): bytes is
+    None if there is no such record or the kernel's sources have changed since it was taken (a stale number
+    is worse than none)."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.md")
     if not os.path.exists(path):
-        return None
+        return None, None
+    value = stamp = None
     for line in open(path):
         parts = line.replace("`", "").split()
-        if len(parts) >= 4 and parts[0] == "traffic_bytes_per_launch" and parts[1] == kernel and parts[2] == "=":
-            return float(parts[3])
-    return None
+        if len(parts) >= 4 and parts[1] == kernel and parts[2] == "=":
+            if parts[0] == "traffic_bytes_per_launch":
+                value = float(parts[3])
+            elif parts[0] == "traffic_source_hash":
+                stamp = parts[3]
+    now = kernel_source_hash(kernel)
+    if value is None or stamp != now:
+        return None, {"measured_at_source_hash": stamp, "current_source_hash": now,
+                      "note": "no counter measurement for the kernel as it is built now"}
+    return value, {"measured_at_source_hash": stamp, "current_source_hash": now}
 
 
 def host_tier_leg(psa, args, cfg, layers, metas, eps, m, tuning_kw, dev):
@@ -203,6 +227,73 @@ def host_tier_leg(psa, args, cfg, layers, metas, eps, m, tuning_kw, dev):
                     "place by the attention kernels (misses) plus slices copied into slots"}
 
 
+def other_workload(psa, idx, eps, m, steps, dev):
+    """One of the other workloads at its full shape: PSA and the dense control on the same inputs, every step
+    timed on its own with device events (inputs that would fit the last-level cache twice over are evicted
+    between steps by a 1 GiB write, which is not timed)."""
+    import numpy as np
+    import torch
+    from workloads import generate_layer, get_config
+    cfg = get_config(idx)
+    B, Hq, H = cfg.batch, cfg.num_q_heads, cfg.num_kv_heads
+    li = generate_layer(cfg, device=dev)
+    kv = psa.KvCache(li.k_pool, li.v_pool, li.block_table, li.ctx_lens, Hq)
+    meta = psa.build_block_metadata(kv, page_fill=li.page_fill)
+    nblk = (li.ctx_lens.cpu().numpy().astype(np.int64) + 15) // 16
+    last_pages = torch.stack([li.block_table[r, max(int(nblk[r]) - 1, 0)] for r in range(B)]).contiguous()
+    ws = torch.empty(psa.decode_workspace_bytes(kv), dtype=torch.uint8, device=dev)
+    out = psa.DecodeOutput(torch.empty((B, Hq, 128), dtype=torch.float32, device=dev),
+                           torch.empty((B, Hq), dtype=torch.int32, device=dev),
+                           torch.empty((B, Hq), dtype=torch.float32, device=dev),
+                           torch.empty((B, H), dtype=torch.int32, device=dev),
+                           torch.empty((B, Hq), dtype=torch.float32, device=dev), None, None,
+                           torch.empty((B, H, 2), dtype=torch.int32, device=dev))
+    dws = torch.empty(psa.dense_workspace_bytes(kv), dtype=torch.uint8, device=dev)
+    dout = torch.empty((B, Hq, 128), dtype=torch.float32, device=dev)
+    dlse = torch.empty((B, Hq), dtype=torch.float32, device=dev)
+    working_set = kv.k_pool.numel() * 2 * 2 + meta.numel() * 2
+    flush = torch.empty(1 << 30, dtype=torch.uint8, device=dev) if working_set < (512 << 20) else None
+
+    def psa_step():
+        psa.build_block_metadata(kv, meta, page_fill=li.page_fill, page_list=last_pages)
+        psa.decode_attention(kv, li.q, meta, eps, m, workspace=ws, outputs=out)
+
+    def dense_step():
+        psa.dense_attention(kv, li.q, workspace=dws, out=dout, lse=dlse)
+
+    def timed(fn):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        for k in range(steps):
+            if flush is not None:
+                flush.fill_(k & 0xFF)
+            ev[k][0].record()
+            fn()
+            ev[k][1].record()
+        torch.cuda.synchronize()
+        return float(np.median([a.elapsed_time(b) for a, b in ev]))
+
+    psa_ms, dense_ms = timed(psa_step), timed(dense_step)
+    assert psa.read_device_error(ws) == 0
+    read = out.blocks_read.cpu().numpy().astype(np.int64)
+    Ntot = np.repeat(nblk[:, None], H, 1)
+    alg = int((read * 8192 + Ntot * 516).sum() + B * Hq * 256)
+    dense_bytes = int((Ntot * 8196).sum() + B * Hq * 256)
+    true_mass = torch.exp(out.lse - dlse)
+    live = torch.isfinite(dlse)
+    return {"workload": cfg.name, "threshold": eps, "check_granularity": m, "kv_dtype": cfg.dtype,
+            "query_heads": B * Hq, "psa_ms_per_step": psa_ms, "dense_ms_per_step": dense_ms,
+            "psa_query_heads_per_s": B * Hq / (psa_ms * 1e-3), "psa_speedup": dense_ms / psa_ms,
+            "kv_reduction_vs_dense": float((Ntot * 8192).sum() / (Ntot * 512 + read * 8192).sum()),
+            "mean_selected_fraction": float((read / np.maximum(Ntot, 1)).mean()),
+            "algorithmic_bytes_per_step": alg, "hbm_frac": alg / (psa_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "dense_hbm_frac": dense_bytes / (dense_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "true_mass_mean": float(true_mass[live].mean()) if bool(live.any()) else 1.0,
+            "timing": "median of the steps, each timed on its own" + (", inputs evicted from the cache between steps" if flush is not None else "")}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -229,6 +320,8 @@ def main():
                          "the GPU); 0 = skip")
     ap.add_argument("--host-tier-layers", type=str, default="2,3,4,5")
     ap.add_argument("--slot-share", type=float, default=0.19, help="slots of the pool / slices of the tiered layers")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the leg that runs the other four workloads (PSA and dense, a few steps each)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -542,7 +635,7 @@ def main():
         assert psa.read_device_error(ws) == 0
 
     # ---- the oracle on the host cores, bounded sample ----------------------------------------------------
-    cpu = None
+    cpu = parity = None
     if not args.no_cpu_baseline:
         sys.path.insert(0, os.path.join(ROOT, "tests"))
         import gpu_common as gc
@@ -553,6 +646,7 @@ def main():
             sample = list(range(L))          # the whole step: about 10-20 s of oracle time for config 3
         reqs = list(range(B))
         t_cpu, heads = 0.0, 0
+        same_n = out_ok = 0
         for l in sample:
             pb = gc.to_problem(layers[l])
             sub = po.Problem(pb.q[reqs], pb.k_pool, pb.v_pool, pb.block_table[reqs], pb.ctx_lens[reqs], pb.dtype)
@@ -562,9 +656,22 @@ def main():
             t_cpu += time.perf_counter() - t1
             heads += len(reqs) * Hq
             g_n = outs[l].n_selected.cpu().numpy()[reqs]
+            eq = g_n == res.n_selected
+            same_n += int(eq.sum())
+            # where both took the same number of blocks the outputs must agree (heads that stop elsewhere are the
+            # near-boundary classes the parity tests examine block by block)
+            err = gc.rel_l2(outs[l].out.cpu().numpy().astype(np.float64)[reqs], res.out)
+            out_ok += int((err[eq] <= gc.OUT_RTOL).sum())
             log(f"[bench] oracle layer {l}: {len(reqs) * Hq} heads, n_selected equal on "
-                f"{(g_n == res.n_selected).mean() * 100:.1f}% of heads, cumulative {t_cpu:.1f}s")
+                f"{eq.mean() * 100:.1f}% of heads, cumulative {t_cpu:.1f}s")
             del pb, sub
+        parity = {"heads": heads, "n_selected_equal": same_n, "frac": same_n / max(heads, 1),
+                  "outputs_within_tolerance_where_equal": out_ok, "tolerance": gc.OUT_RTOL,
+                  "ok": bool(same_n >= 0.99 * heads and out_ok >= 0.995 * same_n),
+                  "what": "the timed step's results against the oracle on the cpu_baseline sample: heads that stop at "
+                          "the same block count, and how many of those have outputs within the tolerance (the rest are "
+                          "heads whose last blocks tie in score, which the element-by-element rule of "
+                          "tests/gpu_common.py examines block by block); fails below 99 % / 99.5 %"}
         cpu = {"value": heads / t_cpu, "unit": "query-heads/s", "cores": po.num_threads(), "kind": "oracle",
                "sample": f"config {cfg.index}, layers {sample}, requests {reqs}, all {Hq} query heads, "
                          f"scoring+ranking+progressive loop in fp64 ({t_cpu:.1f}s of CPU time)"}
@@ -643,23 +750,41 @@ def main():
                               "blocks_read_per_stream_mean_last_step": float(np.mean(read))}
         log(f"[bench] decode loop: {loop}")
 
-    traffic = read_measured_traffic(cfg.name, dom)
+    # ---- the other workloads, each at its full shape (beside the headline's inputs: 288 GB hold both) -----
+    others = None
+    if not args.no_other_configs:
+        others = []
+        for idx, th in ((1, None), (2, None), (4, None), (5, 0.95), (5, 0.99)):
+            if idx == cfg.index:
+                continue
+            try:
+                rec = other_workload(psa, idx, get_config(idx).threshold if th is None else th, m, max(args.steps, 10), dev)
+            except Exception as exc:
+                rec = {"workload": get_config(idx).name, "error": f"{type(exc).__name__}: {exc}"}
+            log(f"[bench] other workload: {rec}")
+            others.append(rec)
+            torch.cuda.empty_cache()
+
+    traffic, traffic_stamp = read_measured_traffic(cfg.name, dom)
 
     result = {
         "metric": "psa_decode_query_heads_per_s", "value": value, "unit": "query-heads/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "ms_per_step_median": float(np.median(step_ms)), "ms_per_step_min": float(np.min(step_ms)), "timing": timing,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": cfg.dtype, "accumulate": "f32", "contraction": f"{cfg.dtype} x {cfg.dtype} -> f32 on the matrix cores",
+        "data": "synthetic",
         "config": {"workload": cfg.name, "layers": L, "batch": B, "num_q_heads": Hq, "num_kv_heads": H,
                    "ctx": cfg.ctx, "kv_dtype": cfg.dtype, "threshold": eps, "check_granularity": m,
                    "scorer": ["upper_bound", "cuboid_center"][args.scorer],
                    "chunk_blocks": args.chunk_blocks or 32, "parallelism": "1 GPU"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_measured_at": traffic_stamp,
                      "frac_of_read_ceiling": dom_gbs / ceiling_gbs,
                      "avg_launch_ms": kern_ms[dom], "algorithmic_bytes_per_launch": kern_bytes[dom]},
         "cpu_baseline": cpu,
+        "parity": parity,
         "read_ceiling": read_ceiling,
         "whole_path": {"algorithmic_bytes_per_step": alg_bytes, "GBps": eff_gbs, "hbm_frac": eff_gbs / HBM_PEAK_GBS,
                        "frac_of_read_ceiling": eff_gbs / ceiling_gbs,
@@ -676,6 +801,7 @@ def main():
         "topk_control": topk,
         "scorer_comparison": scorers,
         "host_tier": tier_leg,
+        "other_configs": others,
         "metadata_bulk_build": {"ms": meta_ms, "GBps": meta_bytes / (meta_ms * 1e-3) / 1e9},
     }
     for n in ("select", "attend"):
@@ -683,6 +809,9 @@ def main():
     log("[bench] per-layer selected fraction: " +
         " ".join(f"{x:.3f}" for x in (blocks_read / np.maximum(N_total, 1)).mean((1, 2))))
     print(json.dumps(result), flush=True)
+    if parity is not None and not parity["ok"]:
+        log(f"[bench] PARITY FAILED against the oracle: {parity}")
+        sys.exit(3)
 
 
 if __name__ == "__main__":
