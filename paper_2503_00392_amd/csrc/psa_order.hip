@@ -6,9 +6,11 @@
 //      smaller key is a larger score) and the workgroup reduces their minimum and maximum;
 //   2. bucket = floor((largest score - score) * scale) is monotone in the score, so bucket order is
 //      rank order; an LDS counter per bucket and a workgroup scan give each bucket its output range;
-//   3. an element's final rank is its bucket's base plus the number of elements of the same bucket
-//      that precede it under (key, index) -- counted exactly, so the result does not depend on the
-//      order in which the LDS atomics arrived.
+//   3. the elements are laid out bucket by bucket ("slots"); an element's final rank is its bucket's base
+//      plus the number of elements of the same bucket that precede it under (key, index) -- counted
+//      exactly, so the result does not depend on the order in which the LDS atomics arrived.  The
+//      counting goes slot by slot, every thread of the workgroup taking its share, so that neighbouring
+//      lanes look at the same bucket.
 // There are as many buckets as element slots, so a bucket holds about one element.  If one bucket
 // holds more than kBucketLimit elements
 // (near-identical scores) the quadratic in-bucket count would be slow, and the workgroup falls back
@@ -108,18 +110,18 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
     const int part = blockIdx.x, nparts = gridDim.x;
     const int tid = threadIdx.x, nthreads = blockDim.x, lane = tid & 63, wave = tid >> 6;
     const int nwaves = nthreads >> 6;
-    // everything this thread needs from memory, requested at once and before anything
-    // else: its 8 scores and table entries
+    // what this thread needs from memory, requested before anything else: its 8 scores (two 16-byte loads
+    // where the row's length allows)
     const float *sc = ws.scores + (size_t)s * kv.max_blocks;
     const int32_t *table = kv.block_table + (size_t)r * kv.max_blocks;
     float scv[8];
-    int pg[8];
+    if ((kv.max_blocks & 7) == 0 && kv.max_blocks >= 8) {
+        const float4 *v4 = reinterpret_cast<const float4 *>(sc + min(tid * 8, kv.max_blocks - 8));   // (clamped: no branch)
+        const float4 a = v4[0], b = v4[1];
+        scv[0] = a.x; scv[1] = a.y; scv[2] = a.z; scv[3] = a.w; scv[4] = b.x; scv[5] = b.y; scv[6] = b.z; scv[7] = b.w;
+    } else {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int p = tid * 8 + j;
-        const int pc = min(p, max(kv.max_blocks - 1, 0));   // clamped into the row, so that the loads need no branch
-        scv[j] = sc[pc];
-        pg[j] = table[pc];
+        for (int j = 0; j < 8; ++j) scv[j] = sc[min(tid * 8 + j, max(kv.max_blocks - 1, 0))];
     }
     // the scoring kernel clamps silently (it clears the error word); out-of-range inputs are reported here
     const int ctx = (tid == 0 && blockIdx.x == 0) ? ctx_clamped(kv, r, ws.header) : ctx_clamped_quiet(kv, r);
@@ -228,54 +230,63 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
     int32_t *oout = order_out ? order_out + (size_t)s * kv.max_blocks : nullptr;
 
     if (max_bucket <= (uint32_t)kBucketLimit && !force_bitonic) {
-        uint32_t b0[8], cn[8], before[8], cmax = 0;
-        // every workgroup of the stream builds the whole slot table (arrival order may differ between
-        // them; the exact count below does not depend on it) ...
+        // every workgroup of the stream builds the whole slot table: the elements of a bucket side by side, in
+        // arrival order (which may differ between the workgroups; the exact count below does not depend on it) ...
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            b0[j] = base[bkt[j]];
-            cn[j] = 0;
-            before[j] = 0;
             if (tid * 8 + j < N) {
-                slot[b0[j] + arrival[j]] = (uint16_t)(tid * 8 + j);
-                skey[b0[j] + arrival[j]] = key[j];
+                const uint32_t at = base[bkt[j]] + arrival[j];
+                slot[at] = (uint16_t)(tid * 8 + j);
+                skey[at] = key[j];
             }
         }
         lds_barrier();
-        // ... and ranks its own share of the elements
-        const int per = (nthreads + nparts - 1) / nparts;
-        const bool mine_part = tid >= part * per && tid < (part + 1) * per;
-        if (mine_part) {
+        // ... and ranks its own share of the SLOTS, all threads taking part: thread t takes slots first + t,
+        // first + t + nthreads, ...  Neighbouring lanes hold neighbouring slots, that is the same bucket or the
+        // next, so a wave's reads of the bucket's members are mostly the same addresses.  The final rank of a
+        // slot's element is its bucket's base plus the number of the bucket's members that precede it under
+        // (key, block index).
+        const int share = (N + nparts - 1) / nparts, first = part * share;
+        const int mine = max(0, min(share, N - first));
+        for (int q0 = 0; q0 < mine; q0 += 2 * nthreads) {         // two slots per thread and turn
+            uint32_t mk[2], me[2], b0[2], cn[2], before[2], cmax = 0;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                cn[j] = tid * 8 + j < N ? base[bkt[j] + 1] - b0[j] : 0u;
-                cmax = max(cmax, cn[j]);
+            for (int j = 0; j < 2; ++j) {
+                const int q = q0 + tid + j * nthreads;
+                mk[j] = 0; me[j] = 0; b0[j] = 0; cn[j] = 0; before[j] = 0;
+                if (q < mine) {
+                    mk[j] = skey[first + q];
+                    me[j] = slot[first + q];
+                    const float fb = (smax - score_of_key(mk[j])) * scale;     // the bucket, exactly as it was computed above
+                    int b = fb >= (float)(NB - 1) ? NB - 1 : (int)fb;
+                    b = b < 0 ? 0 : b;
+                    b0[j] = base[b];
+                    cn[j] = base[b + 1] - b0[j];
+                    cmax = max(cmax, cn[j]);
+                }
             }
-        }
-        // the 8 elements walk their buckets side by side, so their LDS reads overlap; the slot's block
-        // index is needed only to break a tie
-        for (uint32_t i = 0; i < cmax; ++i) {
-            uint32_t ko[8], so[8];
+            for (uint32_t i = 0; i < cmax; ++i) {
+                uint32_t ko[2], so[2];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {              // reads past a bucket's end stay inside the table
-                const uint32_t at = min(b0[j] + i, (uint32_t)(Np - 1));
-                ko[j] = skey[at];
-                so[j] = slot[at];
+                for (int j = 0; j < 2; ++j) {              // reads past a bucket's end stay inside the table
+                    const uint32_t at = min(b0[j] + i, (uint32_t)(Np - 1));
+                    ko[j] = skey[at];
+                    so[j] = slot[at];
+                }
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const bool precedes = ko[j] < mk[j] || (ko[j] == mk[j] && so[j] < me[j]);
+                    before[j] += (i < cn[j] && precedes) ? 1u : 0u;
+                }
             }
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const bool first = ko[j] < key[j] || (ko[j] == key[j] && so[j] < (uint32_t)(tid * 8 + j));
-                before[j] += (i < cn[j] && first) ? 1u : 0u;
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int p = tid * 8 + j;
-            if (p < N && mine_part) {
-                const uint32_t rank = b0[j] + before[j];
-                ord[rank] = p;
-                rpage[rank] = clamp_page(pg[j], kv.num_pages, ws.header);
-                if (oout) oout[rank] = p;
+            for (int j = 0; j < 2; ++j) {
+                if (q0 + tid + j * nthreads < mine) {
+                    const uint32_t rank = b0[j] + before[j];
+                    ord[rank] = (int)me[j];
+                    rpage[rank] = clamp_page(table[me[j]], kv.num_pages, ws.header);
+                    if (oout) oout[rank] = (int)me[j];
+                }
             }
         }
     } else if (part == 0) {     // (uniform over the workgroup) the fallback is one workgroup's work
