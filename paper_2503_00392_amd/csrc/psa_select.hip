@@ -159,9 +159,13 @@ __device__ __forceinline__ int stop_bound(float Lacc, float Lmin, unsigned long 
 // published, moves the frontier, and looks again; with nothing new it naps a fraction of a microsecond first.
 // It waits for nothing but chunks whose workgroups are in this kernel's grid and never wait for anything
 // themselves beyond a bounded number of looks, so it always ends; a count of looks bounds it all the same
-// (kFoldPatience: seconds), after which the stream is closed as it stands and PSA_DEVERR_STALLED is raised.
+// (kFoldPatience: about half a second), after which the stream is closed as it stands and PSA_DEVERR_STALLED is
+// raised.  With more streams than folding waves (4 * kMaxFoldGroups) a wave folds several streams, one after
+// the other.
 // =================================================================================================
-constexpr int kFoldPatience = 1 << 22;
+constexpr int kFoldPatience = 1 << 19;
+constexpr int kMaxFoldGroups = 128;            // workgroups of four folding waves at most: they must leave the
+                                               // compute units room for the chunks they wait for
 
 template <int G>
 __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU, int budget) {
@@ -418,9 +422,9 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
 }
 
 // =================================================================================================
-// grid = folders + S * max_chunks workgroups of 256 threads.  The first `folders` = ceil(S / 4) workgroups are the
-// folds, one wave per stream (they start first and stay until their streams close); then one workgroup per
-// (chunk, stream), streams fastest.
+// grid = folders + S * max_chunks workgroups of 256 threads.  The first `folders` = min(ceil(S / 4), kMaxFoldGroups)
+// workgroups are the folds, one wave per stream (they start first and stay until their streams close); then one
+// workgroup per (chunk, stream), streams fastest.
 // =================================================================================================
 template <int DT, int G>
 __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, const uint8_t *__restrict__ q,
@@ -429,10 +433,10 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
                                                                 const int32_t *depth_hint) {
     __shared__ SelectShared<G> sh;
     const int S = kv.batch * kv.num_kv_heads;
-    const int folders = (S + 3) / 4;
+    const int folders = min((S + 3) / 4, kMaxFoldGroups);
     if ((int)blockIdx.x < folders) {
-        const int fs = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
-        if (fs < S) fold_stream<G>(kv, ws, fs, eps, m, CB, budget);
+        for (int fs = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6); fs < S; fs += 4 * folders)
+            fold_stream<G>(kv, ws, fs, eps, m, CB, budget);
         return;
     }
     const int s = ((int)blockIdx.x - folders) % S, c = ((int)blockIdx.x - folders) / S;
@@ -479,7 +483,8 @@ template <int DT, int G>
 static hipError_t launch_select_t(const KvView &kv, const void *q, const DecodeWs &ws, float eps, int m,
                                   int budget, const DecodePlan &plan, hipStream_t st) {
     const unsigned S = (unsigned)(kv.batch * kv.num_kv_heads);
-    const unsigned grid = (S + 3) / 4 + S * (unsigned)plan.max_chunks;
+    const unsigned folders = (S + 3) / 4 < (unsigned)kMaxFoldGroups ? (S + 3) / 4 : (unsigned)kMaxFoldGroups;
+    const unsigned grid = folders + S * (unsigned)plan.max_chunks;
     select_kernel<DT, G><<<grid, kSelectThreads, 0, st>>>(kv, (const uint8_t *)q, ws, eps, m, plan.chunk_blocks,
                                                budget, plan.window_chunks, plan.spin_limit, plan.depth_hint);
     return hipGetLastError();
