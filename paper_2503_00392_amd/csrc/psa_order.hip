@@ -246,8 +246,21 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         // next, so a wave's reads of the bucket's members are mostly the same addresses.  The final rank of a
         // slot's element is its bucket's base plus the number of the bucket's members that precede it under
         // (key, block index).
-        const int share = (N + nparts - 1) / nparts, first = part * share;
-        const int mine = max(0, min(share, N - first));
+        // A workgroup's share is a run of whole buckets (the workgroups of a stream agree on the buckets' ranges,
+        // not on the arrangement inside a bucket): from the first bucket that starts at or after part * N / nparts
+        // to the first one that starts at or after (part + 1) * N / nparts.
+        auto bucket_from = [&](int target) {           // smallest b with base[b] >= target (base[NB] = N >= target)
+            int lo = 0, hi = NB;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if ((int)base[mid] >= target) hi = mid; else lo = mid + 1;
+            }
+            return lo;
+        };
+        const int share = (N + nparts - 1) / nparts;
+        const int first = (int)base[bucket_from(min(part * share, N))];
+        const int last = part == nparts - 1 ? N : (int)base[bucket_from(min((part + 1) * share, N))];
+        const int mine = last - first;
         for (int q0 = 0; q0 < mine; q0 += 2 * nthreads) {         // two slots per thread and turn
             uint32_t mk[2], me[2], b0[2], cn[2], before[2], cmax = 0;
 #pragma unroll

@@ -173,7 +173,6 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
     StreamCtl *ctl = &ws.ctl[s];
     const int ctx = stream_ctx(kv, s);
     const int N = (ctx + kPage - 1) / kPage;
-    constexpr int CPR = 64 / G;                // chunks per load round: lane = (chunk j, head)
     const unsigned long long *agg = ws.agg + (size_t)s * ws.max_chunks * G;
     const int hg = lane < G ? lane : 0;
     // chunks that may ever be folded: all of them, or those a fixed budget of blocks covers (the limit in the
@@ -288,7 +287,10 @@ __device__ __forceinline__ void stage_pages(SelectShared<G> &sh, const KvView &k
     const int nblk = min(CB, N - c * CB);
     const size_t row0 = (size_t)s * kv.max_blocks + c * CB;
     if (tid < nblk) {
-        sh.page[tid] = ws.ranked_page[row0 + tid];
+        const int page = ws.ranked_page[row0 + tid];
+        // (the ranking kernel wrote a page of the pool, or with a second tier possibly ~slot; anything else
+        // is taken for page 0 rather than for an address)
+        sh.page[tid] = (kv.slot_pool != nullptr && page < 0) ? page : clamp_page_quiet(page, kv.num_pages);
         sh.valid[tid] = min(kPage, ctx - ws.order[row0 + tid] * kPage);
     }
 }

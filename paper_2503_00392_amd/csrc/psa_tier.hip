@@ -8,10 +8,9 @@
 // Replacement is least-recently-used at the granularity of one update (Sec. 3.4): every update has a time
 // stamp; the slices an attention call used get it; the misses, ordered by (stream, rank), take the
 // candidate slots ordered by (age, slot index), oldest first.  The first order comes from prefix sums, the
-// second from sorting 64-bit keys with the device radix sort of rocPRIM -- the one library routine in this
-// file; bookkeeping, not attention.
-#include <rocprim/device/device_radix_sort.hpp>
-
+// second from a stable counting sort of the slots by their 17-bit age key, done here in two passes (8 and 9
+// bits): per-tile digit counts, one scan over the (digit, tile) table, a scatter that keeps slot order inside
+// a digit.
 #include "psa_host.h"
 
 namespace psa {
@@ -20,7 +19,7 @@ constexpr int kTierThreads = 256;
 constexpr unsigned long long kNoKey = ~0ull;
 constexpr uint32_t kMaxAge = 65535;      // updates after which a slot is as old as it gets
 // words of the state header
-constexpr int kClock = 0, kMisses = 1, kPlaced = 2, kHits = 3, kEvicted = 4;
+constexpr int kClock = 0, kMisses = 1, kHits = 3, kEvicted = 4;
 
 static size_t tier_align(size_t v) { return (v + 255) / 256 * 256; }
 
@@ -185,6 +184,85 @@ __global__ __launch_bounds__(kTierThreads) void tier_candidates_kernel(TierView 
     }
 }
 
+// ---- stable sort of the candidate keys by bits [SHIFT, SHIFT + BITS) -------------------------------------------
+// One pass of a least-significant-digit radix sort: tiles of 256 consecutive keys (one per thread); within a
+// tile a key's rank among the keys with its digit comes from ballots (the lanes of a wave that share the digit)
+// plus the counts of the waves before; `counts` is laid out [digit][tile], so that one exclusive scan over the
+// whole table gives every (digit, tile) its first output position and equal digits keep their input order.
+constexpr int kSortTile = kTierThreads;
+
+template <int SHIFT, int BITS>
+__device__ __forceinline__ void tile_ranks(const unsigned long long *__restrict__ keys, int n, uint16_t (*wave_hist)[1 << BITS],
+                                           unsigned long long &key, int &digit, int &rank, bool &live) {
+    constexpr int BINS = 1 << BITS;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = blockIdx.x * kSortTile + tid;
+    live = i < n;
+    key = live ? keys[i] : 0ull;
+    digit = (int)((key >> SHIFT) & (unsigned long long)(BINS - 1));
+    for (int b = tid; b < (kTierThreads / 64) * BINS; b += kTierThreads) (&wave_hist[0][0])[b] = 0;
+    __syncthreads();
+    unsigned long long peers = __ballot(live);
+#pragma unroll
+    for (int b = 0; b < BITS; ++b) {
+        const bool bit = (digit >> b) & 1;
+        const unsigned long long bal = __ballot(bit);
+        peers &= bit ? bal : ~bal;
+    }
+    const int in_wave = __popcll(peers & ((1ull << lane) - 1ull));
+    if (live && in_wave == 0) wave_hist[wave][digit] = (uint16_t)__popcll(peers);
+    __syncthreads();
+    rank = in_wave;
+    for (int w = 0; w < wave; ++w) rank += wave_hist[w][digit];
+}
+
+template <int SHIFT, int BITS>
+__global__ __launch_bounds__(kTierThreads) void sort_count_kernel(const unsigned long long *__restrict__ keys, int n,
+                                                                  uint32_t *__restrict__ counts, int tiles) {
+    constexpr int BINS = 1 << BITS;
+    __shared__ uint16_t wave_hist[kTierThreads / 64][BINS];
+    unsigned long long key; int digit, rank; bool live;
+    tile_ranks<SHIFT, BITS>(keys, n, wave_hist, key, digit, rank, live);
+    for (int b = threadIdx.x; b < BINS; b += kTierThreads) {
+        uint32_t c = 0;
+#pragma unroll
+        for (int w = 0; w < kTierThreads / 64; ++w) c += wave_hist[w][b];
+        counts[(size_t)b * tiles + blockIdx.x] = c;
+    }
+}
+
+// Exclusive prefix sum over `total` counters in place, one workgroup of 1024 threads: each thread sums a
+// contiguous span, the spans' sums are scanned across the workgroup, each thread then rewrites its span.
+__global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *__restrict__ counts, int total) {
+    __shared__ uint32_t wave_sum[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int span = (total + 1023) / 1024, lo = min(tid * span, total), hi = min(lo + span, total);
+    uint32_t mine = 0;
+    for (int i = lo; i < hi; ++i) mine += counts[i];
+    uint32_t incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t o = (uint32_t)__shfl_up((int)incl, d);
+        if (lane >= d) incl += o;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    uint32_t run = incl - mine;
+    for (int w = 0; w < wave; ++w) run += wave_sum[w];
+    for (int i = lo; i < hi; ++i) { const uint32_t c = counts[i]; counts[i] = run; run += c; }
+}
+
+template <int SHIFT, int BITS>
+__global__ __launch_bounds__(kTierThreads) void sort_scatter_kernel(const unsigned long long *__restrict__ keys, int n,
+                                                                    const uint32_t *__restrict__ counts, int tiles,
+                                                                    unsigned long long *__restrict__ out) {
+    constexpr int BINS = 1 << BITS;
+    __shared__ uint16_t wave_hist[kTierThreads / 64][BINS];
+    unsigned long long key; int digit, rank; bool live;
+    tile_ranks<SHIFT, BITS>(keys, n, wave_hist, key, digit, rank, live);
+    if (live) out[counts[(size_t)digit * tiles + blockIdx.x] + rank] = key;
+}
+
 // The j-th miss takes the j-th candidate slot: the slice is copied from host memory (two 4 KiB slices, one
 // 16-byte load per thread each) and the tables are brought up to date.  Workgroups stride over the pairs.
 __global__ __launch_bounds__(kTierThreads) void tier_promote_kernel(KvView kv, TierView t,
@@ -254,25 +332,24 @@ hipError_t launch_tier_resolve(const KvView &kv, const psa_tier *tier, int32_t *
 }
 
 struct TierScratch {
-    size_t miss_ids, miss_count, miss_offset, cand_in, cand_out, temp, temp_bytes, total;
+    size_t miss_ids, miss_count, miss_offset, cand_in, cand_out, counts, total;
+    int tiles;
 };
+constexpr int kSortBitsLow = 8, kSortBitsHigh = 9;       // the 17 bits of the age key, low digit first
 
 static TierScratch tier_scratch(const psa_kv_desc *d) {
     const size_t S = (size_t)d->batch * d->num_kv_heads;
     const size_t cap = S * d->max_blocks_per_seq;
     const size_t slots = (size_t)d->tier->num_slots;
-    size_t tb = 0;
-    unsigned long long *none = nullptr;
-    (void)rocprim::radix_sort_keys(nullptr, tb, none, none, slots, 32, 49, (hipStream_t)0);
     TierScratch L;
+    L.tiles = (int)((slots + kSortTile - 1) / kSortTile);
     size_t at = 0;
     L.miss_ids = at;    at = tier_align(at + cap * 4);
     L.miss_count = at;  at = tier_align(at + S * 4);
     L.miss_offset = at; at = tier_align(at + (S + 1) * 4);
     L.cand_in = at;     at = tier_align(at + slots * 8);
     L.cand_out = at;    at = tier_align(at + slots * 8);
-    L.temp = at;        L.temp_bytes = tb;
-    at = tier_align(at + L.temp_bytes);
+    L.counts = at;      at = tier_align(at + ((size_t)1 << kSortBitsHigh) * L.tiles * 4);
     L.total = at;
     return L;
 }
@@ -300,13 +377,19 @@ hipError_t launch_tier_update(const psa_kv_desc *d, const int32_t *order, const 
     const int cgrid = (t.num_slots + kTierThreads - 1) / kTierThreads;
     tier_candidates_kernel<<<cgrid < 2048 ? cgrid : 2048, kTierThreads, 0, st>>>(t, busy_first, busy_count, cand_in);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    // candidates by bits 32..48 (the sort is stable: equal ages stay in slot order)
-    size_t tb = L.temp_bytes;
-    if ((e = rocprim::radix_sort_keys(base + L.temp, tb, cand_in, cand_out, (size_t)t.num_slots, 32, 49, st)) != hipSuccess)
-        return e;
-    tier_promote_kernel<<<2048, kTierThreads, 0, st>>>(kv, t, miss_ids, miss_offset, S, cand_out);
+    // candidates by bits 32..48, low digit first (each pass is stable: equal ages stay in slot order)
+    auto *counts = reinterpret_cast<uint32_t *>(base + L.counts);
+    const int n = t.num_slots, tiles = L.tiles;
+    sort_count_kernel<32, kSortBitsLow><<<tiles, kTierThreads, 0, st>>>(cand_in, n, counts, tiles);
+    sort_scan_kernel<<<1, 1024, 0, st>>>(counts, (1 << kSortBitsLow) * tiles);
+    sort_scatter_kernel<32, kSortBitsLow><<<tiles, kTierThreads, 0, st>>>(cand_in, n, counts, tiles, cand_out);
+    sort_count_kernel<32 + kSortBitsLow, kSortBitsHigh><<<tiles, kTierThreads, 0, st>>>(cand_out, n, counts, tiles);
+    sort_scan_kernel<<<1, 1024, 0, st>>>(counts, (1 << kSortBitsHigh) * tiles);
+    sort_scatter_kernel<32 + kSortBitsLow, kSortBitsHigh><<<tiles, kTierThreads, 0, st>>>(cand_out, n, counts, tiles, cand_in);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    tier_finish_kernel<<<1, 64, 0, st>>>(t, cand_out, stats_out);
+    tier_promote_kernel<<<2048, kTierThreads, 0, st>>>(kv, t, miss_ids, miss_offset, S, cand_in);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    tier_finish_kernel<<<1, 64, 0, st>>>(t, cand_in, stats_out);
     return hipGetLastError();
 }
 

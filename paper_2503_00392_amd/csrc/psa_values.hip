@@ -70,7 +70,11 @@ __global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int
     // the wave's blocks are wave, wave + 4, ...: lane j fetches the page and the logical index of the j-th
     const int jmax = (maxcnt - wave + 3) / 4;           // how many of them there are (may be <= 0)
     int pg = 0, od = 0;
-    if (lane < jmax) { pg = ws.ranked_page[row0 + wave + 4 * lane]; od = ws.order[row0 + wave + 4 * lane]; }
+    if (lane < jmax) {
+        pg = ws.ranked_page[row0 + wave + 4 * lane];
+        if (!(kv.slot_pool != nullptr && pg < 0)) pg = clamp_page_quiet(pg, kv.num_pages);   // (a page of the pool, or ~slot)
+        od = ws.order[row0 + wave + 4 * lane];
+    }
     // Reference exponent per head: the largest block log-sum-exp among the blocks the head uses (log2 units; the
     // selection kernel left one per block and head).  Lane = (block, head) pairs, 64 / G blocks per load, then a
     // butterfly over the lanes of a head: every lane l ends with the reference of head l % G, so lane (rg, cl < G)

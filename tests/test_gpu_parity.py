@@ -29,6 +29,8 @@ CASES = {
     "c2_small_kvhead_fracs": (_small(2, batch=2, ctx=4096), {}),
     "c3_small_bf16_random_table": (_small(3, batch=2, ctx=8192, layers=1), {"layer": 5}),
     "c3_dense_layer": (_small(3, batch=1, ctx=4096, layers=1), {"layer": 0}),
+    # long enough (2500 blocks, 16 streams) for the ranking to be shared by several workgroups per stream
+    "c2_ranking_in_parts": (_small(2, batch=2, ctx=40000), {}),
     "c4_ragged_g8": (_small(4, batch=6, ctx=6000, ctx_min=100), {}),
     "c5_uniform": (_small(5, batch=2, ctx=4096), {}),
     "mha_g1": (_small(1, num_q_heads=8, num_kv_heads=8, ctx=2000), {}),
