@@ -216,11 +216,28 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         if (w < wave) wave_off += scratch[32 + w];
         max_bucket = max(max_bucket, scratch[48 + w]);
     }
+    // A workgroup's share of the ranking work is a run of whole buckets (the workgroups of a stream agree on the
+    // buckets' ranges, not on the arrangement inside a bucket): share p starts with the first bucket that begins at
+    // or after slot p * N / nparts.  Whoever holds the bucket that slot falls into notes where the next one begins.
+    const int share = (N + nparts - 1) / nparts;
+    if (tid < 8) scratch[64 + tid] = 0u;               // (share 0 starts at slot 0; nparts <= 4)
     {
         const uint32_t t0 = wave_off + incl - mine;
         *reinterpret_cast<uint4 *>(cnt + tid * 8) = make_uint4(t0 + e8[0], t0 + e8[1], t0 + e8[2], t0 + e8[3]);
         *reinterpret_cast<uint4 *>(cnt + tid * 8 + 4) = make_uint4(t0 + e8[4], t0 + e8[5], t0 + e8[6], t0 + e8[7]);
         if (tid == 0) cnt[NB] = (uint32_t)N;
+    }
+    lds_barrier();
+    {
+        const uint32_t t0 = wave_off + incl - mine;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t lo = t0 + e8[j], hi = lo + c8[j];          // bucket's slots [lo, hi)
+            for (int p = 1; p < nparts; ++p) {
+                const uint32_t target = (uint32_t)min(p * share, N);
+                if (lo < target && target <= hi) scratch[64 + p] = hi;
+            }
+        }
     }
     lds_barrier();
     const uint32_t *base = cnt;                                               // base[b] .. base[b+1]: bucket b's slots
@@ -246,20 +263,8 @@ __global__ __launch_bounds__(1024) void order_kernel(KvView kv, DecodeWs ws, int
         // next, so a wave's reads of the bucket's members are mostly the same addresses.  The final rank of a
         // slot's element is its bucket's base plus the number of the bucket's members that precede it under
         // (key, block index).
-        // A workgroup's share is a run of whole buckets (the workgroups of a stream agree on the buckets' ranges,
-        // not on the arrangement inside a bucket): from the first bucket that starts at or after part * N / nparts
-        // to the first one that starts at or after (part + 1) * N / nparts.
-        auto bucket_from = [&](int target) {           // smallest b with base[b] >= target (base[NB] = N >= target)
-            int lo = 0, hi = NB;
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if ((int)base[mid] >= target) hi = mid; else lo = mid + 1;
-            }
-            return lo;
-        };
-        const int share = (N + nparts - 1) / nparts;
-        const int first = (int)base[bucket_from(min(part * share, N))];
-        const int last = part == nparts - 1 ? N : (int)base[bucket_from(min((part + 1) * share, N))];
+        const int first = (int)scratch[64 + part];
+        const int last = part == nparts - 1 ? N : (int)scratch[64 + part + 1];
         const int mine = last - first;
         for (int q0 = 0; q0 < mine; q0 += 2 * nthreads) {         // two slots per thread and turn
             uint32_t mk[2], me[2], b0[2], cn[2], before[2], cmax = 0;

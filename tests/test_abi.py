@@ -182,7 +182,7 @@ def test_static_entry_point_rejects_on_the_host_before_it_touches_a_gpu(lib):
     def call(d, threshold=0.9, m=1):
         return lib.psa_decode_attention_static(C.byref(d), 0x10, 0x20, threshold, m, 0, 0x30, 0x40, 0x50, None, None,
                                                None, None, None, None)
-    big = _desc(batch=4, num_pages=4 * 8192, max_blocks_per_seq=8192)
+    big = _desc(batch=8, num_pages=8 * 8192, max_blocks_per_seq=8192)
     assert lib.psa_decode_workspace_bytes(C.byref(big), None) > pb.STATIC_SCRATCH_BYTES
     assert call(big) == 3
     assert call(_desc(head_dim=64)) == 2

@@ -77,7 +77,7 @@ def test_static_scratch_reports_device_side_errors(psa):
 
 
 def test_a_shape_beyond_the_static_scratch_is_refused(psa):
-    cfg = get_config(3).scaled(layers=1)
+    cfg = get_config(3).scaled(layers=1, batch=8)        # eight requests of 128K tokens: about 117 MiB of workspace
     B, MB = cfg.batch, cfg.ctx // 16
     # a descriptor only: nothing this large is allocated, the call must return before it looks at any buffer
     tiny = torch.zeros((1, cfg.num_kv_heads, 16, 128), dtype=torch.bfloat16, device="cuda")
