@@ -79,11 +79,12 @@ typedef enum { PSA_SCORE_UPPER_BOUND = 0, PSA_SCORE_CUBOID_CENTER = 1 } psa_scor
  *   slot_pool  device, num_slots * 8192 bytes, 16-byte aligned: slot s holds a key slice at s * 8192 and a
  *              value slice at s * 8192 + 4096, each [page_size][head_dim]
  */
+#define PSA_TIER_MAX_SLOTS (1 << 26)   /* 512 GiB of slots: more than any GPU holds */
 typedef struct {
     void *state;
     void *slot_pool;
     int64_t total_slices;       /* 1 .. 2^31 - 1                                                   */
-    int64_t num_slots;          /* 1 .. 2^31 - 1                                                   */
+    int64_t num_slots;          /* 1 .. PSA_TIER_MAX_SLOTS                                         */
     int64_t slice_base;         /* id of this descriptor's page 0, KV head 0                       */
 } psa_tier;
 

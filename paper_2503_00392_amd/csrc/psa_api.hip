@@ -39,7 +39,7 @@ psa_status check_tier(const psa_kv_desc *d, psa_kv_desc *out) {
     if (!t || !t->state || !t->slot_pool) return PSA_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(t->state) & 255u) || (reinterpret_cast<uintptr_t>(t->slot_pool) & 15u))
         return PSA_ERR_INVALID_ARG;
-    if (t->total_slices < 1 || t->total_slices > INT32_MAX || t->num_slots < 1 || t->num_slots > INT32_MAX)
+    if (t->total_slices < 1 || t->total_slices > INT32_MAX || t->num_slots < 1 || t->num_slots > PSA_TIER_MAX_SLOTS)
         return PSA_ERR_INVALID_ARG;
     if (d->num_pages < 1) return PSA_ERR_INVALID_ARG;
     if (t->slice_base < 0 || t->slice_base + (long long)d->num_pages * d->num_kv_heads > t->total_slices)
@@ -254,7 +254,7 @@ psa_status psa_dense_attention(const psa_kv_desc *d, const void *q, float *out, 
 }
 
 size_t psa_tier_state_bytes(int64_t total_slices, int64_t num_slots) {
-    if (total_slices < 1 || total_slices > INT32_MAX || num_slots < 1 || num_slots > INT32_MAX) return 0;
+    if (total_slices < 1 || total_slices > INT32_MAX || num_slots < 1 || num_slots > PSA_TIER_MAX_SLOTS) return 0;
     return psa::tier_state_bytes(total_slices, num_slots);
 }
 

@@ -312,8 +312,8 @@ __device__ __forceinline__ void load_queries(SelectShared<G> &sh, const KvView &
 }
 
 // =================================================================================================
-// Key work of one workgroup: chunk c of stream s.  Ends with the chunk published; wave 0 carries
-// the fold on if it was waiting for this chunk.
+// Key work of one workgroup: chunk c of stream s.  Ends with the chunk published (wave 0 stores the chunk's
+// words, which the stream's folding wave is looking at).
 // =================================================================================================
 template <int DT, int G>
 __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8_t *__restrict__ q,

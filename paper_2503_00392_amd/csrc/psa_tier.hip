@@ -231,25 +231,71 @@ __global__ __launch_bounds__(kTierThreads) void sort_count_kernel(const unsigned
     }
 }
 
-// Exclusive prefix sum over `total` counters in place, one workgroup of 1024 threads: each thread sums a
-// contiguous span, the spans' sums are scanned across the workgroup, each thread then rewrites its span.
-__global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *__restrict__ counts, int total) {
-    __shared__ uint32_t wave_sum[16];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int span = (total + 1023) / 1024, lo = min(tid * span, total), hi = min(lo + span, total);
+// Exclusive prefix sum over `total` counters in place, in two launches: every workgroup owns a span of
+// kScanSpan consecutive counters (16 per thread).  First the spans' sums; then every workgroup adds up the sums of
+// the spans before its own (a few hundred numbers at most per million slots) and rewrites its span.  (One
+// workgroup walking the whole table -- 512 counters per tile of 256 slots -- took a millisecond per pass.)
+constexpr int kScanPerThread = 16;
+constexpr int kScanSpan = kTierThreads * kScanPerThread;
+
+// Sum of v over the workgroup, the same in every thread.  `part` holds one word per wave.
+__device__ __forceinline__ uint32_t group_sum(uint32_t v, uint32_t *part) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += (uint32_t)__shfl_xor((int)v, d);
+    __syncthreads();                       // (the previous use of `part` is over)
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint32_t all = 0;
+#pragma unroll
+    for (int w = 0; w < kTierThreads / 64; ++w) all += part[w];
+    return all;
+}
+
+__global__ __launch_bounds__(kTierThreads) void sort_scan_sums_kernel(const uint32_t *__restrict__ counts, int total,
+                                                                      uint32_t *__restrict__ span_sums) {
+    __shared__ uint32_t part[kTierThreads / 64];
+    const int base = blockIdx.x * kScanSpan;
     uint32_t mine = 0;
-    for (int i = lo; i < hi; ++i) mine += counts[i];
+#pragma unroll
+    for (int k = 0; k < kScanPerThread; ++k) {
+        const int i = base + k * kTierThreads + (int)threadIdx.x;
+        mine += i < total ? counts[i] : 0u;
+    }
+    const uint32_t all = group_sum(mine, part);
+    if (threadIdx.x == 0) span_sums[blockIdx.x] = all;
+}
+
+__global__ __launch_bounds__(kTierThreads) void sort_scan_apply_kernel(uint32_t *__restrict__ counts, int total,
+                                                                       const uint32_t *__restrict__ span_sums) {
+    __shared__ uint32_t part[kTierThreads / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t before = 0;
+    for (int i = tid; i < (int)blockIdx.x; i += kTierThreads) before += span_sums[i];
+    before = group_sum(before, part);
+    // thread t owns counters first .. first + 15 of the span
+    const int first = blockIdx.x * kScanSpan + tid * kScanPerThread;
+    uint32_t c[kScanPerThread], mine = 0;
+#pragma unroll
+    for (int k = 0; k < kScanPerThread; ++k) {
+        c[k] = first + k < total ? counts[first + k] : 0u;
+        mine += c[k];
+    }
     uint32_t incl = mine;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
         const uint32_t o = (uint32_t)__shfl_up((int)incl, d);
         if (lane >= d) incl += o;
     }
-    if (lane == 63) wave_sum[wave] = incl;
     __syncthreads();
-    uint32_t run = incl - mine;
-    for (int w = 0; w < wave; ++w) run += wave_sum[w];
-    for (int i = lo; i < hi; ++i) { const uint32_t c = counts[i]; counts[i] = run; run += c; }
+    if (lane == 63) part[wave] = incl;
+    __syncthreads();
+    uint32_t run = before + incl - mine;
+    for (int w = 0; w < wave; ++w) run += part[w];
+#pragma unroll
+    for (int k = 0; k < kScanPerThread; ++k) {
+        if (first + k < total) counts[first + k] = run;
+        run += c[k];
+    }
 }
 
 template <int SHIFT, int BITS>
@@ -332,7 +378,7 @@ hipError_t launch_tier_resolve(const KvView &kv, const psa_tier *tier, int32_t *
 }
 
 struct TierScratch {
-    size_t miss_ids, miss_count, miss_offset, cand_in, cand_out, counts, total;
+    size_t miss_ids, miss_count, miss_offset, cand_in, cand_out, counts, span_sums, total;
     int tiles;
 };
 constexpr int kSortBitsLow = 8, kSortBitsHigh = 9;       // the 17 bits of the age key, low digit first
@@ -349,7 +395,9 @@ static TierScratch tier_scratch(const psa_kv_desc *d) {
     L.miss_offset = at; at = tier_align(at + (S + 1) * 4);
     L.cand_in = at;     at = tier_align(at + slots * 8);
     L.cand_out = at;    at = tier_align(at + slots * 8);
-    L.counts = at;      at = tier_align(at + ((size_t)1 << kSortBitsHigh) * L.tiles * 4);
+    const size_t counters = ((size_t)1 << kSortBitsHigh) * L.tiles;
+    L.counts = at;      at = tier_align(at + counters * 4);
+    L.span_sums = at;   at = tier_align(at + (counters + kScanSpan - 1) / kScanSpan * 4);
     L.total = at;
     return L;
 }
@@ -380,11 +428,16 @@ hipError_t launch_tier_update(const psa_kv_desc *d, const int32_t *order, const 
     // candidates by bits 32..48, low digit first (each pass is stable: equal ages stay in slot order)
     auto *counts = reinterpret_cast<uint32_t *>(base + L.counts);
     const int n = t.num_slots, tiles = L.tiles;
+    auto *span_sums = reinterpret_cast<uint32_t *>(base + L.span_sums);
+    const int total_low = (1 << kSortBitsLow) * tiles, total_high = (1 << kSortBitsHigh) * tiles;
+    const int spans_low = (total_low + kScanSpan - 1) / kScanSpan, spans_high = (total_high + kScanSpan - 1) / kScanSpan;
     sort_count_kernel<32, kSortBitsLow><<<tiles, kTierThreads, 0, st>>>(cand_in, n, counts, tiles);
-    sort_scan_kernel<<<1, 1024, 0, st>>>(counts, (1 << kSortBitsLow) * tiles);
+    sort_scan_sums_kernel<<<spans_low, kTierThreads, 0, st>>>(counts, total_low, span_sums);
+    sort_scan_apply_kernel<<<spans_low, kTierThreads, 0, st>>>(counts, total_low, span_sums);
     sort_scatter_kernel<32, kSortBitsLow><<<tiles, kTierThreads, 0, st>>>(cand_in, n, counts, tiles, cand_out);
     sort_count_kernel<32 + kSortBitsLow, kSortBitsHigh><<<tiles, kTierThreads, 0, st>>>(cand_out, n, counts, tiles);
-    sort_scan_kernel<<<1, 1024, 0, st>>>(counts, (1 << kSortBitsHigh) * tiles);
+    sort_scan_sums_kernel<<<spans_high, kTierThreads, 0, st>>>(counts, total_high, span_sums);
+    sort_scan_apply_kernel<<<spans_high, kTierThreads, 0, st>>>(counts, total_high, span_sums);
     sort_scatter_kernel<32 + kSortBitsLow, kSortBitsHigh><<<tiles, kTierThreads, 0, st>>>(cand_out, n, counts, tiles, cand_in);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     tier_promote_kernel<<<2048, kTierThreads, 0, st>>>(kv, t, miss_ids, miss_offset, S, cand_in);
