@@ -806,6 +806,8 @@ def main():
     }
     for n in ("select", "attend"):
         log(f"[bench] per-layer {n} ms: " + " ".join(f"{x:.3f}" for x in per_layer[n]))
+    log("[bench] per-layer blocks read, min/mean/max over the (request, KV head) pairs: " +
+        " ".join(f"{int(x.min())}/{int(x.mean())}/{int(x.max())}" for x in blocks_read.reshape(L, -1)))
     log("[bench] per-layer selected fraction: " +
         " ".join(f"{x:.3f}" for x in (blocks_read / np.maximum(N_total, 1)).mean((1, 2))))
     print(json.dumps(result), flush=True)

@@ -52,7 +52,7 @@ static WsLayout layout(const psa_kv_desc *d, const DecodePlan &p) {
     const size_t MB = (size_t)d->max_blocks_per_seq;
     WsLayout L;
     size_t at = 0;
-    L.header = at;      at = align_up(at + 256, 256);
+    L.header = at;      at = align_up(at + 512, 256);
     L.ctl = at;         at = align_up(at + S * sizeof(StreamCtl), 256);
     L.scores = at;      at = align_up(at + S * MB * 4, 256);
     L.order = at;       at = align_up(at + S * MB * 4, 256);

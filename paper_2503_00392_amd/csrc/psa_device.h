@@ -64,9 +64,12 @@ __device__ __forceinline__ const uint8_t *value_slice(const KvView &kv, int loc,
 struct alignas(128) StreamCtl {
     // line 0: progress, written by the folding wave only, as ONE 64-bit store; polled by workgroups that
     // wait for the read-ahead window
-    unsigned long long key_progress;    // low: frontier = key chunks folded into the stop rule so far;
-                                        // high: k_limit = key chunks worth reading (all of them, or what a
-                                        // block budget covers, until the fold has finished; then what it used)
+    unsigned long long key_progress;    // bits 0-15: frontier = key chunks folded into the stop rule so far;
+                                        // bits 16-31: the read-ahead window the fold grants beyond the frontier,
+                                        // in chunks (0 = the launch's default);
+                                        // high word: k_limit = key chunks worth reading (all of them, or what a
+                                        // block budget covers, or what the stop rule can still reach; once the
+                                        // fold has finished, what it used)
     int32_t pad0[30];
     // line 1: counters
     int32_t k_blocks;   // key slices loaded (traffic accounting)
@@ -77,8 +80,9 @@ struct alignas(128) StreamCtl {
 };
 
 struct DecodeWs {
-    int32_t *header;        // [64]: word 1 = sticky error bits; word kValueCount (a cache line of its own) =
-                            // number of entries of value_items
+    int32_t *header;        // [128]: word 1 = sticky error bits; word kValueCount (a cache line of its own) =
+                            // number of entries of value_items; word kClosedStreams (again its own line) =
+                            // streams whose stop rule has finished
     StreamCtl *ctl;         // [S]
     float *scores;          // [S][max_blocks]
     int32_t *order;         // [S][max_blocks]  ranked logical blocks
@@ -96,6 +100,7 @@ struct DecodeWs {
 constexpr int kPartialStride = 132;  // M, l, pad, pad, acc[128]
 constexpr int kMaxWindowChunks = 256; // chunks read beyond the fold's frontier, at most
 constexpr int kValueCount = 32;      // index of the value-item counter in the workspace header
+constexpr int kClosedStreams = 64;   // index of the closed-stream counter in the workspace header
 // A chunk word holds (L_chunk, Lmin_chunk) as two floats once the chunk is published.  Before that
 // it holds a NaN pattern no publisher writes: "not published".
 constexpr unsigned long long kAggSentinel = 0xFFFFFFFFFFFFFFFFull;

@@ -30,6 +30,7 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
     // ranking kernel, which sees the same table entries and contexts, reports them
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 2) header[threadIdx.x] = 0;
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 2) header[kValueCount] = 0;   // value work list
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 3) header[kClosedStreams] = 0;
     const int ctx = ctx_clamped_quiet(kv, r);
     const int N = (ctx + kPage - 1) / kPage;
     const int base = (blockIdx.x * 4 + wave) * 16 * rounds;      // the wave's first block
@@ -121,6 +122,7 @@ __global__ __launch_bounds__(256) void score_pages_kernel(KvView kv, const uint8
     const int rho = wave * 4 + row, h = rho % H, sub = rho / H, BS = 16 / H;
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 2) header[threadIdx.x] = 0;
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 2) header[kValueCount] = 0;   // value work list
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 3) header[kClosedStreams] = 0;
     const int ctx = ctx_clamped_quiet(kv, r);
     const int N = (ctx + kPage - 1) / kPage;
     const int base = blockIdx.x * nb;
@@ -214,6 +216,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(KvView kv, const uint8_
     // ranking kernel, which sees the same table entries and contexts, reports them
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 2) header[threadIdx.x] = 0;
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 2) header[kValueCount] = 0;   // value work list
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 3) header[kClosedStreams] = 0;
     const int ctx = ctx_clamped_quiet(kv, r);
     const int N = (ctx + kPage - 1) / kPage;
     const int base = blockIdx.x * kScoreBlocks + wave * 16;

@@ -118,6 +118,7 @@ struct SelectShared {
     int page[kMaxChunkBlocks];
     int valid[kMaxChunkBlocks];
     int go;                                // after the wait for the window: 1 = read the chunk, 0 = the stream closed
+    unsigned long long kp0;                // the stream's progress word as the workgroup first saw it
     uint4 stage[kSelectThreads / 64][16 * 17];   // per wave: one key slice, rows padded to 272 bytes
 };
 
@@ -152,12 +153,32 @@ __device__ __forceinline__ int stop_bound(float Lacc, float Lmin, unsigned long 
     return (need + KU - 1) / KU + 1;
 }
 
+// The progress word of a stream that is still open (see StreamCtl).
+__device__ __forceinline__ unsigned long long progress_word(int lim, int grant, int walked) {
+    return ((unsigned long long)(unsigned)lim << 32) | ((unsigned)grant << 16) | (unsigned)walked;
+}
+// The read-ahead window of a stream when `closed` of the S streams have finished: the launch's total of chunks in
+// flight (window per stream x S) shared by the streams still open.
+__device__ __forceinline__ int granted(int window, int S, int closed) {
+    return min(kMaxWindowChunks, (int)(((long long)window * S) / max(1, S - closed)));
+}
+
 // =================================================================================================
 // The fold (Algorithm 1 lines 12-18 in rank order): one wave per stream, from the kernel's first moment until
-// the stream closes.  Lane g < G carries head g: (L_acc, L_min) over the folded chunks and the head's stop.
-// The wave looks at the words of the next chunks (one load covers 64 / G of them), folds those that are
-// published, moves the frontier, and looks again; with nothing new it naps a fraction of a microsecond first.
-// It waits for nothing but chunks whose workgroups are in this kernel's grid and never wait for anything
+// the stream closes.
+//
+// Chunks are folded a GROUP at a time: 64 / G consecutive chunks, aligned, lane = (chunk of the group, head).  One
+// load fetches the group's words; a prefix scan over the chunks (steps of G lanes) gives every head's AS_acc and
+// AS_min after every chunk of the group at once -- combined with the state carried into the group -- hence P_acc at
+// every chunk's end.  The chunks in which an open head passes the threshold are then visited in order (there are at
+// most G stops per stream) for the head's exact stop, with a second prefix scan over that chunk's blocks.  A
+// sequential walk, chunk by chunk on G lanes, cost a deep stream 0.3 us per chunk -- more than reading the chunk
+// costs the rest of the machine.
+// The expression that gives the state after a chunk is fixed by the chunk's place in its group (the scan's tree over
+// the group's earlier chunks, then the carry), whatever part of the group was published when the wave looked: the
+// fold is reproducible bit for bit although its timing is not.
+//
+// The wave waits for nothing but chunks whose workgroups are in this kernel's grid and never wait for anything
 // themselves beyond a bounded number of looks, so it always ends; a count of looks bounds it all the same
 // (kFoldPatience: about half a second), after which the stream is closed as it stands and PSA_DEVERR_STALLED is
 // raised.  With more streams than folding waves (4 * kMaxFoldGroups) a wave folds several streams, one after
@@ -168,60 +189,81 @@ constexpr int kMaxFoldGroups = 128;            // workgroups of four folding wav
                                                // compute units room for the chunks they wait for
 
 template <int G>
-__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU, int budget) {
-    const int lane = threadIdx.x & 63;
+__device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float eps, int m, int KU, int budget,
+                            int window) {
+    constexpr int CPG = 64 / G;                // chunks per group
+    const int lane = threadIdx.x & 63, g = lane % G, jl = lane / G;     // my head, my chunk of the group
     StreamCtl *ctl = &ws.ctl[s];
     const int ctx = stream_ctx(kv, s);
     const int N = (ctx + kPage - 1) / kPage;
     const unsigned long long *agg = ws.agg + (size_t)s * ws.max_chunks * G;
-    const int hg = lane < G ? lane : 0;
     // chunks that may ever be folded: all of them, or those a fixed budget of blocks covers (the limit in the
     // progress word is for the readers of keys and may be tighter: see stop_bound)
     const int nch = ((budget > 0 ? min(N, budget) : N) + KU - 1) / KU;
-    if (nch == 0) return;                      // an empty request: the ranking kernel left it closed
+    if (nch == 0) {                            // an empty request: the ranking kernel left it closed
+        if (lane == 0) atomicAdd(&ws.header[kClosedStreams], 1);
+        return;
+    }
+    const int S = kv.batch * kv.num_kv_heads;
     const float odds = eps > 0.0f ? (1.0f - eps) / eps : INFINITY;      // (1 - eps) / eps of the stop test
-    float Lacc = -INFINITY, Lmin = INFINITY;
-    unsigned long long stop = lane < G ? ~0ull : 0ull;                  // lanes >= G count as stopped
-    int fr = 0, walked = 0, looks = 0;
+    const unsigned long long head_lanes = (~0ull / ((1ull << G) - 1ull)) << g;   // the lanes of my head
+    float Cacc = -INFINITY, Cmin = INFINITY;   // my head's (L_acc, L_min) at the start of the group
+    unsigned long long stop = ~0ull;           // my head's stop (n << 32 | P_acc bits), ~0 = still open
+    int base = 0, walked = 0;                  // the group's first chunk; chunks folded so far
+    int closed = 0, lim_now = nch;             // streams seen closed at the last look; the limit last published
+    int looks = 0;
     bool finished = false;
     while (!finished) {
-        // v: the words of chunks fr .. fr+CPR-1; k = how many leading ones are completely published
-        unsigned long long v;
-        {
-            const int ci = fr + lane / G;
-            v = (ci < nch) ? ld_relaxed(&agg[(size_t)ci * G + lane % G]) : kAggSentinel;
-        }
+        // the group's words, and (in flight at the same time) how many streams have closed
+        const int ci = base + jl;
+        const unsigned long long v = (ci < nch) ? ld_relaxed(&agg[(size_t)ci * G + g]) : kAggSentinel;
+        const int closed_now = uniform(ld_relaxed(&ws.header[kClosedStreams]));
         const unsigned long long pub = __ballot(v != kAggSentinel);
-        const int k = ((pub == ~0ull) ? 64 : (__ffsll((long long)~pub) - 1)) / G;
-        if (k == 0) {
+        const int k = ((pub == ~0ull) ? 64 : (__ffsll((long long)~pub) - 1)) / G;     // leading published chunks
+        if (base + k <= walked) {
+            // Nothing new.  While the wait lasts, tell the readers if other streams have closed meanwhile, which
+            // widens this one's window.
             if (++looks > kFoldPatience) {
                 if (lane == 0) set_error(ws.header, PSA_DEVERR_STALLED);
                 break;
             }
+            if (closed_now != closed && walked > 0) {
+                closed = closed_now;
+                if (lane == 0) st_relaxed(&ctl->key_progress, progress_word(lim_now, granted(window, S, closed), walked));
+            }
             __builtin_amdgcn_s_sleep(8);
             continue;
         }
-#pragma nounroll
-        for (int j = 0; j < k && !finished; ++j) {
-            const unsigned long long a = shfl_u64(v, j * G + hg);
-            const float L2 = lse2(Lacc, __uint_as_float((uint32_t)(a & 0xffffffffull)));
-            const float M2 = fminf(Lmin, __uint_as_float((uint32_t)(a >> 32)));
-            const int cidx = fr + j;
-            const int b0 = cidx * KU, n_end = min(b0 + KU, N);
-            // a stop inside this chunk needs a position where the rule is tested (line 17 is reached
-            // every m blocks and at the last block) and, P_acc being non-decreasing, a pass at its end
-            const bool tested = (n_end / m) * m > b0 || n_end == N;
-            const bool scan = stop == ~0ull && tested && p_acc(L2, M2, N - n_end) > eps;
-            if (__ballot(scan) != 0ull) {
-                // Some head may stop in this chunk.  Its blocks' L_b are fetched 64 at a time, lane = (block,
-                // head); a prefix scan over the blocks of each head (steps of G lanes) gives AS_acc and AS_min
-                // after every block, hence P_acc at every position; the first position that passes is the stop.
-                // (A fixed scan shape: reproducible.  It is not the left fold bit for bit, which only matters
-                // where P_acc is within rounding of the threshold.)
-                const float *lb = ws.block_lse + ((size_t)s * kv.max_blocks + b0) * G;
-                const int cnt = (n_end - b0) * G;
-                const unsigned long long head_lanes = (~0ull / ((1ull << G) - 1ull)) << hg;   // lanes of my head
-                float cl = __shfl(Lacc, lane % G), cm = __shfl(Lmin, lane % G);              // carried in
+        closed = closed_now;
+        // (L_acc, L_min) of my head after my chunk: scan over the group's chunks, then the carry
+        float L = __uint_as_float((uint32_t)(v & 0xffffffffull)), M = __uint_as_float((uint32_t)(v >> 32));
+#pragma unroll
+        for (int d = G; d < 64; d <<= 1) {
+            const float ol = __shfl_up(L, d), om = __shfl_up(M, d);
+            if (lane >= d) { L = lse2(ol, L); M = fminf(om, M); }
+        }
+        L = lse2(Cacc, L);
+        M = fminf(Cmin, M);
+        const int b0 = ci * KU, n_end = min(b0 + KU, N);
+        // a stop inside a chunk needs a position where the rule is tested (line 17 is reached every m blocks and
+        // at the last block) and, P_acc being non-decreasing, a pass at the chunk's end
+        const bool passes = ((n_end / m) * m > b0 || n_end == N) && p_acc(L, M, N - n_end) > eps;
+        int j = walked - base;                 // the next chunk of the group to fold
+        while (j < k) {
+            const unsigned long long cand = __ballot(jl >= j && jl < k && stop == ~0ull && passes);
+            if (cand == 0ull) { j = k; break; }
+            const int js = (__ffsll((long long)cand) - 1) / G;          // the first chunk in which an open head passes
+            const bool scan = (cand >> (js * G + g)) & 1ull;            // does mine?
+            {
+                // That chunk's blocks' L_b are fetched 64 at a time, lane = (block, head); a prefix scan over the
+                // blocks of each head (steps of G lanes), on top of the state after the chunk before, gives AS_acc
+                // and AS_min after every block, hence P_acc at every position; the first tested position that
+                // passes is the stop.
+                const int cb0 = (base + js) * KU, cn_end = min(cb0 + KU, N);
+                const float *lb = ws.block_lse + ((size_t)s * kv.max_blocks + cb0) * G;
+                const int cnt = (cn_end - cb0) * G;
+                float cl = js == 0 ? Cacc : __shfl(L, (js - 1) * G + g);
+                float cm = js == 0 ? Cmin : __shfl(M, (js - 1) * G + g);
                 bool found = false;
 #pragma nounroll
                 for (int x0 = 0; x0 < cnt; x0 += 64) {
@@ -234,46 +276,53 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
                         if (lane >= d) { pl = lse2(ol, pl); pm = fminf(om, pm); }
                     }
                     const float fl = lse2(cl, pl), fm = fminf(cm, pm);
-                    const int nn = b0 + (x0 + lane) / G + 1;
+                    const int nn = cb0 + (x0 + lane) / G + 1;
                     const float P = p_acc(fl, fm, N - nn);
                     const unsigned long long hits = __ballot(valid && (nn % m == 0 || nn == N) && P > eps) & head_lanes;
                     const int src = hits ? (__ffsll((long long)hits) - 1) : 0;
                     const float Pf = __shfl(P, src);
                     if (scan && !found && hits) {
-                        stop = ((unsigned long long)(b0 + (x0 + src) / G + 1) << 32) | __float_as_uint(Pf);
+                        stop = ((unsigned long long)(cb0 + (x0 + src) / G + 1) << 32) | __float_as_uint(Pf);
                         found = true;
                     }
-                    const int last = (min(64, cnt - x0) / G - 1) * G + lane % G;   // my head's last block of this group
+                    const int last = (min(64, cnt - x0) / G - 1) * G + g;   // my head's last block of this batch
                     cl = __shfl(fl, last);
                     cm = __shfl(fm, last);
                 }
             }
-            if (stop == ~0ull || scan) { Lacc = L2; Lmin = M2; }
-            walked = cidx + 1;
-            if (__ballot(stop == ~0ull) == 0ull) finished = true;
+            j = js + 1;
+            if (__ballot(stop == ~0ull) == 0ull) { finished = true; break; }
         }
-        fr = walked;
-        if (fr >= nch) finished = true;
+        walked = base + j;
+        if (walked >= nch) finished = true;
         if (finished) break;
-        // the frontier opens the window for waiting workgroups; the limit tells them how far the stream can still go
-        const int lim = min(nch, stop_bound<G>(Lacc, Lmin, stop, walked * KU, N, m, KU, odds));
-        if (lane == 0)
-            st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)lim << 32) | (unsigned)walked);
+        // my head's state at the frontier (for stop_bound), and the carry once the whole group is folded
+        const float Lw = j == 0 ? Cacc : __shfl(L, (j - 1) * G + g), Mw = j == 0 ? Cmin : __shfl(M, (j - 1) * G + g);
+        if (j == CPG) { Cacc = Lw; Cmin = Mw; base += CPG; }
+        // The frontier opens the window for waiting workgroups; the limit tells them how far the stream can still go.
+        // The window: the launch's total of chunks in flight is shared by the streams still open, so the last,
+        // deepest streams are read as wide as the whole batch was (a window sized for all streams leaves the
+        // machine idle once most of them have closed).
+        const int lim = min(nch, stop_bound<G>(Lw, Mw, stop, walked * KU, N, m, KU, odds));
+        lim_now = lim;
+        if (lane == 0) st_relaxed(&ctl->key_progress, progress_word(lim, granted(window, S, closed), walked));
     }
     // every head has stopped, or the blocks ran out: close the key side (limit = frontier)
     if (lane < G) st_relaxed(&ctl->stop[lane], stop);
-    if (lane == 0)
+    if (lane == 0) {
         st_relaxed(&ctl->key_progress, ((unsigned long long)(unsigned)walked << 32) | (unsigned)walked);
+        atomicAdd(&ws.header[kClosedStreams], 1);
+    }
     // the stream's value units (the chunks up to its slowest head's stop) go onto the work list of the
     // value pass, which therefore starts no workgroup for a chunk nobody selected
     int nmax = (lane < G) ? ((stop == ~0ull) ? N : (int)(stop >> 32)) : 0;
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) nmax = max(nmax, __shfl_xor(nmax, d));
     const int units = (nmax + KU - 1) / KU;
-    int base = 0;
-    if (lane == 0) base = atomicAdd(&ws.header[kValueCount], units);
-    base = uniform(base);
-    for (int i = lane; i < units; i += 64) ws.value_items[base + i] = s * ws.max_chunks + i;
+    int base_item = 0;
+    if (lane == 0) base_item = atomicAdd(&ws.header[kValueCount], units);
+    base_item = uniform(base_item);
+    for (int i = lane; i < units; i += 64) ws.value_items[base_item + i] = s * ws.max_chunks + i;
 }
 
 // Physical page and valid-token count of each ranked block of chunk c of stream s -> LDS.  Issued before
@@ -438,19 +487,32 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
     const int folders = min((S + 3) / 4, kMaxFoldGroups);
     if ((int)blockIdx.x < folders) {
         for (int fs = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6); fs < S; fs += 4 * folders)
-            fold_stream<G>(kv, ws, fs, eps, m, CB, budget);
+            fold_stream<G>(kv, ws, fs, eps, m, CB, budget, window > 0 ? window : 1);
         return;
     }
-    const int s = ((int)blockIdx.x - folders) % S, c = ((int)blockIdx.x - folders) / S;
+    // Workgroups go to the chip's eight partitions by index, round robin.  With the streams in the same order in
+    // every batch of S workgroups, and S a multiple of eight, all chunks of a stream would land on one partition:
+    // the last, deepest streams would then be read by an eighth of the machine.  So the streams' order rotates by
+    // one from chunk to chunk (when S is even; an odd S rotates by itself).
+    const int c = ((int)blockIdx.x - folders) / S;
+    const int s = (((int)blockIdx.x - folders) % S + ((S & 1) ? 0 : c)) % S;
+    // One round trip for everything a workgroup needs to know first: the stream's progress word (asked for before
+    // anything else), its length, its queries, its chunk's pages.  Most workgroups of a launch belong to chunks
+    // beyond their stream's stop and leave right here; the faster they do, the sooner the slots they hold go to
+    // chunks that matter.
+    unsigned long long kp_first = 0;
+    if (threadIdx.x == 0) kp_first = ld_relaxed(&ws.ctl[s].key_progress);
     const int N = (stream_ctx(kv, s) + kPage - 1) / kPage;
     if (c * CB >= N) return;
     load_queries<G>(sh, kv, q, s);
     stage_pages<G>(sh, kv, ws, CB, s, c);
+    if (threadIdx.x == 0) sh.kp0 = kp_first;
+    lds_barrier();
+    if (c >= (int)(sh.kp0 >> 32)) return;          // closed, out of reach, or beyond a block budget
     // Second tier: a chunk with slices that are not cached is read over the host link, where reading ahead
     // of the stop costs far more than waiting does: such a chunk is read when it is expected to be needed
     // (inside the hint) or when the fold is about to reach it.
     const bool tiered = kv.slot_pool != nullptr;
-    if (tiered) lds_barrier();
     if (threadIdx.x == 0) {
         bool from_host = false;
         if (tiered)
@@ -460,15 +522,15 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
         const int hinted = hinted_chunks(depth_hint, s, N, CB);
         int go = 1;
         for (int tries = 0;; ++tries) {
-            const unsigned long long kp = ld_relaxed(&ws.ctl[s].key_progress);
-            const int fr = (int)(kp & 0xffffffffull), lim = (int)(kp >> 32);
+            const unsigned long long kp = tries == 0 ? sh.kp0 : ld_relaxed(&ws.ctl[s].key_progress);
+            const int fr = (int)(kp & 0xffffull), grant = (int)((kp >> 16) & 0xffffull), lim = (int)(kp >> 32);
+            const int win = max(window_of(window, fr), grant);      // (the fold grants more once streams have closed)
             if (c >= lim) { go = 0; break; }       // closed, or a block budget ends before this chunk
             // with a hint: everything up to it plus a margin (a sixteenth and two chunks: the depth of a
             // decode step differs a little from the previous step's) at once; past that, a window that
             // starts at 8 chunks and doubles with the distance the hint fell short by
             const int padded = hinted + (hinted >> 4) + 2;
-            int reach = hinted > 0 ? max(padded, fr + min(max(8, 2 * (fr - hinted)), window_of(window, fr)))
-                                   : fr + window_of(window, fr);
+            int reach = hinted > 0 ? max(padded, fr + min(max(8, 2 * (fr - hinted)), win)) : fr + win;
             if (from_host) reach = min(reach, max(hinted, fr + 2));
             if (c < reach || tries >= spin_limit) break;
             nap(tries);
