@@ -28,10 +28,11 @@ DecodePlan make_plan(const psa_kv_desc *d, const psa_tuning *t) {
     if (t && t->window_chunks > 0) {
         p.window_chunks = t->window_chunks;
     } else {
-        // about 128 MiB of key slices in flight over all streams (four 4-wave workgroups per CU, one 128 KiB
-        // chunk each, on 256 CUs), 2 to 32 chunks per stream
-        const long long per_stream = (128ll << 20) / ((long long)(S > 0 ? S : 1) * p.chunk_blocks * kSliceBytes);
-        p.window_chunks = per_stream < 2 ? 2 : (per_stream > 32 ? 32 : (int)per_stream);
+        // about 96 MiB of key slices inside the streams' windows together (the chip holds 1024 workgroups of this
+        // kernel, one 128 KiB chunk each; three quarters of that measured best: the fold widens the windows of the
+        // streams that stay open longest), 2 to 24 chunks per stream
+        const long long per_stream = (96ll << 20) / ((long long)(S > 0 ? S : 1) * p.chunk_blocks * kSliceBytes);
+        p.window_chunks = per_stream < 2 ? 2 : (per_stream > 24 ? 24 : (int)per_stream);
     }
     p.spin_limit = (t && t->spin_limit > 0) ? t->spin_limit : (1 << 14);
     p.max_chunks = (d->max_blocks_per_seq + p.chunk_blocks - 1) / p.chunk_blocks;
