@@ -158,10 +158,15 @@ def host_tier_leg(psa, args, cfg, layers, metas, eps, m, tuning_kw, dev):
     main_s, side_s = torch.cuda.current_stream(), torch.cuda.Stream()
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
-    def run(caches, overlap, with_tier, use_hint=True):
+    # staging buffers (the attention kernels leave the slices they read over the host link there, so that the update
+    # need not fetch them again): consecutive calls alternate between two, each with room for a cold layer's misses
+    staging = [psa.Tier.staging_buffer(1 << 16, device=dev) for _ in range(2)]
+
+    def run(caches, overlap, with_tier, use_hint=True, staged=True):
         outs = new_outs()
         hint = [torch.zeros((B, H), dtype=torch.int32, device=dev) for _ in range(Lt)]
-        stats = torch.zeros((n_steps, Lt, 4), dtype=torch.int32, device=dev)
+        stats = torch.zeros((n_steps, Lt, 5), dtype=torch.int32, device=dev)
+        calls = 0
         marks = [ev() for _ in range(n_steps + 1)]
         done = [None] * Lt                      # event: the last update of layer j has finished
         decoded = [ev() for _ in range(Lt)]
@@ -173,6 +178,9 @@ def host_tier_leg(psa, args, cfg, layers, metas, eps, m, tuning_kw, dev):
                     main_s.wait_event(done[(j - 2) % Lt])     # the update that ran beside layer j-1 may have evicted anything else
                 # the depth hint of a step is what the same layer read in the step before (a copy: the call rewrites it)
                 tn = psa.Tuning(depth_hint=hint[j], **tuning_kw) if (use_hint and t > 0) else tun
+                if with_tier:
+                    caches[j].staging = staging[calls % 2] if staged else None
+                    calls += 1
                 psa.decode_attention(caches[j], qs[t][j], metas[ids[j]], eps, m, workspace=ws, outputs=outs[j], tuning=tn)
                 if use_hint:
                     hint[j].copy_(outs[j].blocks_read)
@@ -203,7 +211,10 @@ def host_tier_leg(psa, args, cfg, layers, metas, eps, m, tuning_kw, dev):
     ovl_ms, ovl_stats, ovl_read, ovl_out = run(hosts, True, True)
     psa.tier_init(tier)
     noh_ms, noh_stats, _, noh_out = run(hosts, True, True, use_hint=False)
-    same = all(torch.equal(a, b) for a, b in zip(hbm_out, ser_out)) and all(torch.equal(a, b) for a, b in zip(hbm_out, ovl_out))
+    psa.tier_init(tier)
+    uns_ms, uns_stats, _, uns_out = run(hosts, True, True, staged=False)
+    same = all(torch.equal(a, b) for a, b in zip(hbm_out, ser_out)) and all(torch.equal(a, b) for a, b in zip(hbm_out, ovl_out)) \
+        and all(torch.equal(a, b) for a, b in zip(hbm_out, uns_out))
     assert psa.read_device_error(ws) == 0
 
     def summary(ms, st):
@@ -213,7 +224,8 @@ def host_tier_leg(psa, args, cfg, layers, metas, eps, m, tuning_kw, dev):
                 "hit_ratio_first_step": float(st[0, :, 0].sum() / max(used[0].sum(), 1)),
                 "hit_ratio_steady": float(st[half:, :, 0].sum() / max(used[half:].sum(), 1)),
                 "slices_used_per_step": float(used[half:].sum(1).mean()),
-                "host_link_MB_per_step_steady": float((st[half:, :, 1] + st[half:, :, 2]).sum(1).mean() * 8192 / 1e6),
+                "host_link_MB_per_step_steady": float((st[half:, :, 1] + st[half:, :, 2] - st[half:, :, 4]).sum(1).mean() * 8192 / 1e6),
+                "placed_from_staging_per_step_steady": float(st[half:, :, 4].sum(1).mean()),
                 "evicted_per_step_steady": float(st[half:, :, 3].sum(1).mean())}
 
     return {"layers": ids, "steps": n_steps, "pinned_GiB": total * 8192 / 2**30, "slots": num_slots,
@@ -222,9 +234,11 @@ def host_tier_leg(psa, args, cfg, layers, metas, eps, m, tuning_kw, dev):
             "tier_update_on_the_same_stream": summary(ser_ms, ser_stats),
             "tier_update_on_a_second_stream": summary(ovl_ms, ovl_stats),
             "tier_update_on_a_second_stream_no_depth_hint": summary(noh_ms, noh_stats),
+            "tier_update_on_a_second_stream_no_staging": summary(uns_ms, uns_stats),
             "outputs_equal_all_in_hbm": bool(same),
             "note": "queries drift from step to step, the cache does not grow; host_link_MB counts slices read in "
-                    "place by the attention kernels (misses) plus slices copied into slots"}
+                    "place by the attention kernels (misses) plus slices the update fetched from host memory (those "
+                    "placed that did not come from the staging buffer)"}
 
 
 def other_workload(psa, idx, eps, m, steps, dev):

@@ -78,6 +78,15 @@ typedef enum { PSA_SCORE_UPPER_BOUND = 0, PSA_SCORE_CUBOID_CENTER = 1 } psa_scor
  *              psa_tier_init, owned by the caller, shared by every descriptor that names this pool
  *   slot_pool  device, num_slots * 8192 bytes, 16-byte aligned: slot s holds a key slice at s * 8192 and a
  *              value slice at s * 8192 + 4096, each [page_size][head_dim]
+ *   staging    device or NULL, psa_tier_staging_bytes(staging_slices) bytes, 256-byte aligned, its first 256
+ *              bytes zero before its first use: where the attention kernels leave a copy of every slice they
+ *              read from host memory, so that the psa_tier_update that follows moves it into its slot from GPU
+ *              memory and the slice crosses the host link once, not twice (Sec. 3.3 loads a missing block
+ *              once).  Slices beyond staging_slices are simply fetched again by the update.  Unlike state and
+ *              slot_pool this buffer belongs to ONE descriptor at a time: between a decode call that names it
+ *              and the psa_tier_update of the same descriptor (which empties it) no other descriptor may use
+ *              it, and the cache must not be appended to.  Layers whose attention and update overlap (two
+ *              streams) alternate between two such buffers.  NULL: every missing slice is fetched by the update.
  */
 #define PSA_TIER_MAX_SLOTS (1 << 26)   /* 512 GiB of slots: more than any GPU holds */
 typedef struct {
@@ -86,6 +95,8 @@ typedef struct {
     int64_t total_slices;       /* 1 .. 2^31 - 1                                                   */
     int64_t num_slots;          /* 1 .. PSA_TIER_MAX_SLOTS                                         */
     int64_t slice_base;         /* id of this descriptor's page 0, KV head 0                       */
+    void *staging;              /* or NULL                                                         */
+    int64_t staging_slices;     /* 1 .. 2^24 entries of 8 KiB (ignored without staging)            */
 } psa_tier;
 
 /* Shapes and layout of ONE layer's paged KV cache (PagedAttention layout, Sec. 2.1 "KV Cache"). */
@@ -259,8 +270,9 @@ psa_status psa_dense_attention(const psa_kv_desc *desc, const void *q, float *ou
  * Two-tier block store (Sec. 3.1, 3.4).  All of it runs on the GPU, on `stream`; the host is not in the loop.
  *
  * psa_tier_state_bytes: bytes of psa_tier.state for these sizes (0 if they are out of range).
- * psa_tier_init: empties the pool (no slice has a slot, clock 0).  Only state, total_slices and num_slots
- *   of `tier` are read.
+ * psa_tier_staging_bytes: bytes of a psa_tier.staging buffer with room for this many slices (0 if out of range).
+ * psa_tier_init: empties the pool (no slice has a slot, clock 0) and, if tier->staging is given, that staging
+ *   buffer.  Only state, total_slices, num_slots and staging of `tier` are read.
  * psa_tier_update_workspace_bytes: bytes of scratch psa_tier_update needs for this descriptor (0 on an
  *   invalid one or one without a tier).
  * psa_tier_update: after a decode call on `desc` (same stream, or ordered after it), with that call's
@@ -277,8 +289,9 @@ psa_status psa_dense_attention(const psa_kv_desc *desc, const void *q, float *ou
  *   be placed twice; nothing faults, one of the two slots is wasted until it ages out).
  *     order        device [batch][num_kv_heads][max_blocks_per_seq] int32, as written by the decode call
  *     blocks_read  device [batch][num_kv_heads] int32, as written by the decode call
- *     stats_out    device int32[4] or NULL: slices used that had a slot, that had none, slices placed,
- *                  slices that lost their slot
+ *     stats_out    device int32[5] or NULL: slices used that had a slot, that had none, slices placed,
+ *                  slices that lost their slot, slices placed from the staging buffer (the others placed were
+ *                  fetched from host memory by the update)
  *   Concurrency: calls that share a state must not overlap each other; a decode call may overlap an
  *   update only if its slices are in the update's busy range and it was enqueued after the previous
  *   update of its own layer completed.
@@ -286,6 +299,7 @@ psa_status psa_dense_attention(const psa_kv_desc *desc, const void *q, float *ou
  * pools the GPU cannot address), PSA_ERR_WORKSPACE_TOO_SMALL, PSA_ERR_LAUNCH.
  */
 size_t psa_tier_state_bytes(int64_t total_slices, int64_t num_slots);
+size_t psa_tier_staging_bytes(int64_t staging_slices);
 psa_status psa_tier_init(const psa_tier *tier, void *stream);
 size_t psa_tier_update_workspace_bytes(const psa_kv_desc *desc);
 psa_status psa_tier_update(const psa_kv_desc *desc, const int32_t *order, const int32_t *blocks_read,

@@ -36,7 +36,8 @@ class _KvDesc(C.Structure):
 
 class _Tier(C.Structure):
     _fields_ = [("state", C.c_void_p), ("slot_pool", C.c_void_p), ("total_slices", C.c_int64),
-                ("num_slots", C.c_int64), ("slice_base", C.c_int64)]
+                ("num_slots", C.c_int64), ("slice_base", C.c_int64), ("staging", C.c_void_p),
+                ("staging_slices", C.c_int64)]
 
 
 class _Tuning(C.Structure):
@@ -100,6 +101,8 @@ def load_library() -> C.CDLL:
         lib.psa_dense_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, vp, sz, vp]
         lib.psa_tier_state_bytes.restype = sz
         lib.psa_tier_state_bytes.argtypes = [C.c_int64, C.c_int64]
+        lib.psa_tier_staging_bytes.restype = sz
+        lib.psa_tier_staging_bytes.argtypes = [C.c_int64]
         lib.psa_tier_init.restype = C.c_int
         lib.psa_tier_init.argtypes = [C.POINTER(_Tier), vp]
         lib.psa_tier_update_workspace_bytes.restype = sz
@@ -148,9 +151,23 @@ class Tier:
         self.slot_pool = torch.empty((num_slots, 2, 16, 128), dtype=torch.int16, device=device)
         _check(lib.psa_tier_init(C.byref(self.c(0)), _stream(stream)), "psa_tier_init")
 
-    def c(self, slice_base: int) -> _Tier:
+    def c(self, slice_base: int, staging: torch.Tensor | None = None) -> _Tier:
+        if staging is None:
+            return _Tier(self.state.data_ptr(), self.slot_pool.data_ptr(), self.total_slices, self.num_slots,
+                         int(slice_base), None, 0)
         return _Tier(self.state.data_ptr(), self.slot_pool.data_ptr(), self.total_slices, self.num_slots,
-                     int(slice_base))
+                     int(slice_base), staging.data_ptr(), int(staging.staging_slices))
+
+    @staticmethod
+    def staging_buffer(slices: int, device="cuda") -> torch.Tensor:
+        """A zero-filled staging buffer with room for `slices` slices (see psa_tier.staging): pass it as
+        KvCache.staging of the layer whose attention is about to run."""
+        nbytes = int(load_library().psa_tier_staging_bytes(int(slices)))
+        if nbytes == 0:
+            raise ValueError("staging size out of range")
+        buf = torch.zeros(nbytes, dtype=torch.uint8, device=device)
+        buf.staging_slices = int(slices)
+        return buf
 
     def tables(self):
         """(slot_of [total_slices], owner [num_slots], stamp [num_slots], clock) as host arrays: a look
@@ -178,6 +195,7 @@ class KvCache:
     num_q_heads: int
     tier: object = None        # Tier or None
     slice_base: int = 0
+    staging: object = None     # a Tier.staging_buffer or None (with a tier only)
 
     def desc(self) -> _KvDesc:
         P, H, T, D = self.k_pool.shape
@@ -194,9 +212,9 @@ class KvCache:
             return None
         assert self.k_pool.is_pinned() and self.v_pool.is_pinned(), "with a tier the pools are pinned host tensors"
         # one struct per cache, kept alive (and in place) for as long as any descriptor may point to it
-        key = (id(self.tier), int(self.slice_base))
+        key = (id(self.tier), int(self.slice_base), id(self.staging))
         if getattr(self, "_tier_key", None) != key:
-            self._tier_c, self._tier_key = self.tier.c(self.slice_base), key
+            self._tier_c, self._tier_key = self.tier.c(self.slice_base, self.staging), key
         return C.addressof(self._tier_c)
 
 
@@ -363,6 +381,10 @@ def tier_state_bytes(total_slices: int, num_slots: int) -> int:
     return int(load_library().psa_tier_state_bytes(total_slices, num_slots))
 
 
+def tier_staging_bytes(staging_slices: int) -> int:
+    return int(load_library().psa_tier_staging_bytes(int(staging_slices)))
+
+
 def tier_init(tier: Tier, stream=None) -> None:
     _check(load_library().psa_tier_init(C.byref(tier.c(0)), _stream(stream)), "psa_tier_init")
 
@@ -375,13 +397,14 @@ def tier_update_workspace_bytes(kv: KvCache) -> int:
 def tier_update(kv: KvCache, order: torch.Tensor, blocks_read: torch.Tensor, busy_first: int = 0, busy_count: int = 0,
                 stats: torch.Tensor | None = None, workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
     """Brings the slot pool up to date with the slices the decode call that wrote `order` and
-    `blocks_read` used.  Returns `stats` (device int32[4]: hits, misses, placed, evicted)."""
+    `blocks_read` used.  Returns `stats` (device int32[5]: hits, misses, placed, evicted, placed from the
+    staging buffer)."""
     d = kv.desc()
     dev = order.device
     if workspace is None:
         workspace = torch.empty(tier_update_workspace_bytes(kv), dtype=torch.uint8, device=dev)
     if stats is None:
-        stats = torch.zeros(4, dtype=torch.int32, device=dev)
+        stats = torch.zeros(5, dtype=torch.int32, device=dev)
     assert order.dtype == torch.int32 and order.is_contiguous()
     assert blocks_read.dtype == torch.int32 and blocks_read.is_contiguous()
     st = load_library().psa_tier_update(C.byref(d), _ptr(order), _ptr(blocks_read), int(busy_first), int(busy_count),

@@ -41,6 +41,9 @@ psa_status check_tier(const psa_kv_desc *d, psa_kv_desc *out) {
         return PSA_ERR_INVALID_ARG;
     if (t->total_slices < 1 || t->total_slices > INT32_MAX || t->num_slots < 1 || t->num_slots > PSA_TIER_MAX_SLOTS)
         return PSA_ERR_INVALID_ARG;
+    if (t->staging && ((reinterpret_cast<uintptr_t>(t->staging) & 255u) || t->staging_slices < 1 ||
+                       t->staging_slices > (1 << 24)))
+        return PSA_ERR_INVALID_ARG;
     if (d->num_pages < 1) return PSA_ERR_INVALID_ARG;
     if (t->slice_base < 0 || t->slice_base + (long long)d->num_pages * d->num_kv_heads > t->total_slices)
         return PSA_ERR_INVALID_ARG;
@@ -258,9 +261,15 @@ size_t psa_tier_state_bytes(int64_t total_slices, int64_t num_slots) {
     return psa::tier_state_bytes(total_slices, num_slots);
 }
 
+size_t psa_tier_staging_bytes(int64_t staging_slices) {
+    if (staging_slices < 1 || staging_slices > (1 << 24)) return 0;
+    return psa::tier_staging_bytes(staging_slices);
+}
+
 psa_status psa_tier_init(const psa_tier *tier, void *stream) {
     if (!tier || !tier->state || (reinterpret_cast<uintptr_t>(tier->state) & 255u)) return PSA_ERR_INVALID_ARG;
     if (psa_tier_state_bytes(tier->total_slices, tier->num_slots) == 0) return PSA_ERR_INVALID_ARG;
+    if (tier->staging && (reinterpret_cast<uintptr_t>(tier->staging) & 255u)) return PSA_ERR_INVALID_ARG;
     return psa::launch_tier_init(tier, (hipStream_t)stream) == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
 }
 

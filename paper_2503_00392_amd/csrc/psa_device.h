@@ -29,7 +29,23 @@ struct KvView {
     const int32_t *ctx_lens;
     int32_t batch, num_q_heads, num_kv_heads, num_pages, max_blocks;
     const uint8_t *slot_pool;   // second tier only: 8 KiB slots (key slice, value slice); else NULL
+    // second tier with a staging buffer only (else staging == NULL): where slices read from host memory are
+    // left for the update that follows
+    uint8_t *staging;           // [256 B: entry counter][staging_cap slice ids][staging_cap x (key slice, value slice)]
+    int32_t *staged_at;         // [total_slices] slice id -> staging entry, -1 = none (in the tier's state)
+    long long slice_base;       // id of page 0, KV head 0
+    int32_t staging_cap;
 };
+
+// Layout of a staging buffer.
+__host__ __device__ __forceinline__ size_t staging_entries_offset(int cap) {
+    return 256 + ((size_t)cap * 4 + 255) / 256 * 256;
+}
+__device__ __forceinline__ uint32_t *staging_count(uint8_t *st) { return reinterpret_cast<uint32_t *>(st); }
+__device__ __forceinline__ int32_t *staging_ids(uint8_t *st) { return reinterpret_cast<int32_t *>(st + 256); }
+__device__ __forceinline__ uint8_t *staging_entry(uint8_t *st, int cap, int idx) {
+    return st + staging_entries_offset(cap) + (size_t)idx * (2 * 4096);
+}
 
 // Kernel-side view of a psa_tier and its state.
 struct TierView {
@@ -40,6 +56,9 @@ struct TierView {
     uint8_t *slot_pool;
     long long slice_base, total_slices;
     int num_slots;
+    int32_t *staged_at;     // [total_slices] slice -> entry of the staging buffer in use, -1 = none
+    uint8_t *staging;       // this descriptor's staging buffer or NULL
+    int staging_cap;
 };
 
 // Where the key slice of ranked block `loc` of KV head h lives: loc >= 0 is a page of the pool, loc < 0
@@ -51,6 +70,32 @@ __device__ __forceinline__ const uint8_t *key_slice(const KvView &kv, int loc, i
 __device__ __forceinline__ const uint8_t *value_slice(const KvView &kv, int loc, int h) {
     return loc >= 0 ? kv.v_pool + ((size_t)loc * kv.num_kv_heads + h) * kSliceBytes
                     : kv.slot_pool + (size_t)(~loc) * (2 * kSliceBytes) + kSliceBytes;
+}
+
+// A wave that has just read the key slice of (page, KV head h) from host memory -- lane l holds bytes 16 l .. 16 l + 15
+// of each of its four 1 KiB rows -- leaves a copy in the staging buffer, for the tier update that follows the call;
+// the wave that later reads the value slice adds it to the same entry.  Entries beyond the buffer's capacity are
+// not made (the update fetches those slices itself).
+__device__ __forceinline__ void stage_key_slice(const KvView &kv, int page, int h, const uint4 (&rows)[4], int lane) {
+    int entry = 0;
+    if (lane == 0) entry = (int)atomicAdd(staging_count(kv.staging), 1u);
+    entry = __builtin_amdgcn_readfirstlane(entry);
+    if (entry < 0 || entry >= kv.staging_cap) return;
+    uint8_t *e = staging_entry(kv.staging, kv.staging_cap, entry) + lane * 16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(e + i * 1024) = rows[i];
+    if (lane == 0) {
+        const long long id = kv.slice_base + (long long)page * kv.num_kv_heads + h;
+        staging_ids(kv.staging)[entry] = (int)id;
+        kv.staged_at[id] = entry;
+    }
+}
+__device__ __forceinline__ void stage_value_slice(const KvView &kv, int page, int h, const uint4 (&rows)[4], int lane) {
+    const int entry = kv.staged_at[kv.slice_base + (long long)page * kv.num_kv_heads + h];
+    if (entry < 0 || entry >= kv.staging_cap) return;
+    uint8_t *e = staging_entry(kv.staging, kv.staging_cap, entry) + kSliceBytes + lane * 16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(e + i * 1024) = rows[i];
 }
 
 // ---- workspace of psa_decode_attention -----------------------------------------------------

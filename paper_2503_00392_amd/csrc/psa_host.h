@@ -7,6 +7,12 @@
 
 namespace psa {
 
+// Layout of a psa_tier's state: header, slice -> slot, slot -> slice, slot -> stamp, slice -> staging entry.
+inline size_t tier_align(size_t v) { return (v + 255) / 256 * 256; }
+inline size_t tier_staged_at_offset(long long total_slices, long long num_slots) {
+    return 256 + tier_align((size_t)total_slices * 4) + 2 * tier_align((size_t)num_slots * 4);
+}
+
 inline KvView make_view(const psa_kv_desc *d) {
     KvView kv;
     kv.k_pool = static_cast<const uint8_t *>(d->k_pool);
@@ -19,6 +25,13 @@ inline KvView make_view(const psa_kv_desc *d) {
     kv.num_pages = d->num_pages;
     kv.max_blocks = d->max_blocks_per_seq;
     kv.slot_pool = d->tier ? static_cast<const uint8_t *>(d->tier->slot_pool) : nullptr;
+    const bool staged = d->tier && d->tier->staging;
+    kv.staging = staged ? static_cast<uint8_t *>(d->tier->staging) : nullptr;
+    kv.staged_at = staged ? reinterpret_cast<int32_t *>(static_cast<uint8_t *>(d->tier->state) +
+                                                        tier_staged_at_offset(d->tier->total_slices, d->tier->num_slots))
+                          : nullptr;
+    kv.slice_base = d->tier ? d->tier->slice_base : 0;
+    kv.staging_cap = staged ? (int32_t)d->tier->staging_slices : 0;
     return kv;
 }
 
@@ -70,6 +83,7 @@ struct DecodeArgs {
 };
 // psa_tier.hip
 size_t tier_state_bytes(long long total_slices, long long num_slots);
+size_t tier_staging_bytes(long long staging_slices);
 TierView make_tier_view(const psa_tier *t);
 size_t tier_update_workspace_bytes(const psa_kv_desc *d);
 hipError_t launch_tier_init(const psa_tier *tier, hipStream_t st);

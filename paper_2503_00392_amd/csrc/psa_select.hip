@@ -403,6 +403,8 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
         for (int u = 0; u < kBatch; ++u) {
             const int i = i0 + u;
             if (i < nblk) {
+                // (second tier with a staging buffer: a slice that came over the host link is kept for the update)
+                if (kv.staging != nullptr && sh.page[i] >= 0) stage_key_slice(kv, sh.page[i], h, ka[u], lane);
                 f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
                 // the slice arrived as four coalesced 1 KiB rows of lanes (loading it in the operand's layout
                 // would touch sixteen 64-byte segments per instruction); the wave turns it into that layout

@@ -19,12 +19,14 @@ constexpr int kTierThreads = 256;
 constexpr unsigned long long kNoKey = ~0ull;
 constexpr uint32_t kMaxAge = 65535;      // updates after which a slot is as old as it gets
 // words of the state header
-constexpr int kClock = 0, kMisses = 1, kHits = 3, kEvicted = 4;
-
-static size_t tier_align(size_t v) { return (v + 255) / 256 * 256; }
+constexpr int kClock = 0, kMisses = 1, kHits = 3, kEvicted = 4, kFromStaging = 5;
 
 size_t tier_state_bytes(long long total_slices, long long num_slots) {
-    return 256 + tier_align((size_t)total_slices * 4) + 2 * tier_align((size_t)num_slots * 4);
+    return tier_staged_at_offset(total_slices, num_slots) + tier_align((size_t)total_slices * 4);
+}
+
+size_t tier_staging_bytes(long long staging_slices) {
+    return staging_entries_offset((int)staging_slices) + (size_t)staging_slices * (2 * kSliceBytes);
 }
 
 TierView make_tier_view(const psa_tier *t) {
@@ -39,6 +41,9 @@ TierView make_tier_view(const psa_tier *t) {
     v.slice_base = t->slice_base;
     v.total_slices = t->total_slices;
     v.num_slots = (int)t->num_slots;
+    v.staged_at = reinterpret_cast<int32_t *>(base + tier_staged_at_offset(t->total_slices, t->num_slots));
+    v.staging = static_cast<uint8_t *>(t->staging);
+    v.staging_cap = t->staging ? (int)t->staging_slices : 0;
     return v;
 }
 
@@ -46,7 +51,8 @@ __global__ __launch_bounds__(kTierThreads) void tier_init_kernel(TierView t) {
     const long long i = (long long)blockIdx.x * kTierThreads + threadIdx.x;
     const long long stride = (long long)gridDim.x * kTierThreads;
     if (i < 64) t.header[i] = 0;
-    for (long long j = i; j < t.total_slices; j += stride) t.slot_of[j] = -1;
+    for (long long j = i; j < t.total_slices; j += stride) { t.slot_of[j] = -1; t.staged_at[j] = -1; }
+    if (i == 0 && t.staging) *staging_count(t.staging) = 0;
     for (long long j = i; j < t.num_slots; j += stride) { t.owner[j] = -1; t.stamp[j] = 0; }
 }
 
@@ -309,8 +315,9 @@ __global__ __launch_bounds__(kTierThreads) void sort_scatter_kernel(const unsign
     if (live) out[counts[(size_t)digit * tiles + blockIdx.x] + rank] = key;
 }
 
-// The j-th miss takes the j-th candidate slot: the slice is copied from host memory (two 4 KiB slices, one
-// 16-byte load per thread each) and the tables are brought up to date.  Workgroups stride over the pairs.
+// The j-th miss takes the j-th candidate slot: the slice is copied into it (two 4 KiB slices, one 16-byte load
+// per thread each) -- from the staging buffer if the attention kernels left it there, from host memory if not --
+// and the tables are brought up to date.  Workgroups stride over the pairs.
 __global__ __launch_bounds__(kTierThreads) void tier_promote_kernel(KvView kv, TierView t,
                                                                     const int32_t *__restrict__ miss_ids,
                                                                     const uint32_t *__restrict__ miss_offset, int S,
@@ -328,7 +335,16 @@ __global__ __launch_bounds__(kTierThreads) void tier_promote_kernel(KvView kv, T
         const long long id = miss_ids[(size_t)lo * kv.max_blocks + (j - miss_offset[lo])];
         const int slot = (int)(uint32_t)cand;
         const size_t src = (size_t)(id - t.slice_base) * kSliceBytes + threadIdx.x * 16;
-        const uint4 k = ld16(kv.k_pool + src), v = ld16(kv.v_pool + src);
+        const int entry = t.staging ? t.staged_at[id] : -1;
+        uint4 k, v;
+        if (entry >= 0 && entry < t.staging_cap) {
+            const uint8_t *e = staging_entry(t.staging, t.staging_cap, entry) + threadIdx.x * 16;
+            k = ld16(e);
+            v = ld16(e + kSliceBytes);
+        } else {
+            k = ld16(kv.k_pool + src);
+            v = ld16(kv.v_pool + src);
+        }
         uint8_t *dst = t.slot_pool + (size_t)slot * (2 * kSliceBytes) + threadIdx.x * 16;
         *reinterpret_cast<uint4 *>(dst) = k;
         *reinterpret_cast<uint4 *>(dst + kSliceBytes) = v;
@@ -341,7 +357,17 @@ __global__ __launch_bounds__(kTierThreads) void tier_promote_kernel(KvView kv, T
             t.owner[slot] = (int)id;
             t.slot_of[id] = slot;
             t.stamp[slot] = now;
+            if (entry >= 0 && entry < t.staging_cap) atomicAdd(&t.header[kFromStaging], 1u);
         }
+    }
+}
+
+// Empties the staging buffer: every entry's slice forgets it.  (The counter itself is cleared by the finishing kernel.)
+__global__ __launch_bounds__(kTierThreads) void tier_unstage_kernel(TierView t) {
+    const uint32_t n = min(*staging_count(t.staging), (uint32_t)t.staging_cap);
+    for (uint32_t i = blockIdx.x * kTierThreads + threadIdx.x; i < n; i += gridDim.x * kTierThreads) {
+        const int id = staging_ids(t.staging)[i];
+        if (id >= 0 && id < t.total_slices) t.staged_at[id] = -1;
     }
 }
 
@@ -357,7 +383,10 @@ __global__ void tier_finish_kernel(TierView t, const unsigned long long *__restr
         stats_out[1] = (int32_t)t.header[kMisses];
         stats_out[2] = (int32_t)min(t.header[kMisses], (uint32_t)lo);
         stats_out[3] = (int32_t)t.header[kEvicted];
+        stats_out[4] = (int32_t)t.header[kFromStaging];
     }
+    if (t.staging) *staging_count(t.staging) = 0;
+    t.header[kFromStaging] = 0;
     t.header[kClock] += 1;
     t.header[kMisses] = 0;
     t.header[kHits] = 0;
@@ -442,6 +471,11 @@ hipError_t launch_tier_update(const psa_kv_desc *d, const int32_t *order, const 
     if ((e = hipGetLastError()) != hipSuccess) return e;
     tier_promote_kernel<<<2048, kTierThreads, 0, st>>>(kv, t, miss_ids, miss_offset, S, cand_in);
     if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (t.staging) {
+        const int ugrid = (t.staging_cap + kTierThreads - 1) / kTierThreads;
+        tier_unstage_kernel<<<ugrid < 1024 ? ugrid : 1024, kTierThreads, 0, st>>>(t);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     tier_finish_kernel<<<1, 64, 0, st>>>(t, cand_in, stats_out);
     return hipGetLastError();
 }

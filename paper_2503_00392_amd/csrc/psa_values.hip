@@ -40,8 +40,9 @@ __device__ __forceinline__ int head_stop(const StreamCtl *ctl, int g, int N) {
 //             8cl..8cl+7.
 // Output per unit and head: (L, sum of p, numerator[128]) for the final merge.
 // =================================================================================================
+constexpr int kValueDepth = 2;      // value slices a wave keeps in flight
 template <int DT, int G>
-__global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int CB) {
+__global__ __launch_bounds__(256, 4) void attend_kernel(KvView kv, DecodeWs ws, int CB) {
     __shared__ float st_acc[4][G][kHeadDim];
     __shared__ float st_l[4][G];
     __shared__ float st_ref[G];
@@ -99,12 +100,12 @@ __global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int
 #pragma unroll
     for (int t = 0; t < 8; ++t) acc[t] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
     float l = 0.0f;
-    for (int j0 = 0; j0 < jmax; j0 += 2) {
-        Slice v[2];
-        float4 x[2];
-        int valid[2], blk[2];
+    for (int j0 = 0; j0 < jmax; j0 += kValueDepth) {
+        Slice v[kValueDepth];
+        float4 x[kValueDepth];
+        int valid[kValueDepth], blk[kValueDepth];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {              // (index clamped, loads made anyway: no branch around a load)
+        for (int u = 0; u < kValueDepth; ++u) {    // (index clamped, loads made anyway: no branch around a load)
             const int j = min(j0 + u, jmax - 1);
             blk[u] = wave + 4 * j;
             v[u] = load_slice(value_slice(kv, __shfl(pg, j), h), lane);
@@ -112,8 +113,12 @@ __global__ __launch_bounds__(256) void attend_kernel(KvView kv, DecodeWs ws, int
             valid[u] = min(kPage, ctx - __shfl(od, j) * kPage);
         }
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < kValueDepth; ++u) {
             if (j0 + u < jmax) {
+                if (kv.staging != nullptr) {               // (second tier: see stage_key_slice)
+                    const int loc = __shfl(pg, j0 + u);
+                    if (loc >= 0) stage_value_slice(kv, loc, h, v[u].r, lane);
+                }
                 if (valid[u] < kPage) zero_invalid_rows(v[u], rg, valid[u]);
                 // tokens beyond `valid` hold -inf logits; blocks beyond the head's stop, and heads beyond the
                 // group, weigh nothing

@@ -144,9 +144,14 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
 
 
 def test_tier_state_sizes(lib):
-    # header + slice table + two slot tables, each rounded up to 256 bytes; 0 for sizes out of range
-    assert psa.tier_state_bytes(1, 1) == 256 + 3 * 256
-    assert psa.tier_state_bytes(1000, 100) == 256 + 4096 + 2 * 512
+    # header + slice table + two slot tables + the slices' staging entries, each rounded up to 256 bytes; 0 for
+    # sizes out of range
+    assert psa.tier_state_bytes(1, 1) == 256 + 4 * 256
+    assert psa.tier_state_bytes(1000, 100) == 256 + 4096 + 2 * 512 + 4096
+    # a staging buffer: header, one id per entry (rounded up to 256 bytes), 8 KiB per entry
+    assert psa.tier_staging_bytes(1) == 256 + 256 + 8192
+    assert psa.tier_staging_bytes(1000) == 256 + 4096 + 1000 * 8192
+    assert psa.tier_staging_bytes(0) == 0 and psa.tier_staging_bytes((1 << 24) + 1) == 0
     for bad in ((0, 1), (1, 0), (-5, 3), (1 << 31, 1), (1, 1 << 31)):
         assert psa.tier_state_bytes(*bad) == 0
     # a descriptor without a tier has no update scratch

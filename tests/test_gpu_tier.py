@@ -8,7 +8,9 @@ caches (page, KV head) slices.  Checked here:
   * after every update the library's tables (slice -> slot, slot -> slice, stamps, clock) and the update's
     counts equal, entry by entry, what the model in oracle/tier_oracle.py gives for the same sequence of
     used slices, evictions and the busy range included;
-  * a cached slice holds the bytes of its host copy, also after tokens were appended.
+  * a cached slice holds the bytes of its host copy, also after tokens were appended;
+  * with a staging buffer the same holds, and the slices the attention read from host memory reach their slots
+    from the staging buffer (counted), as far as the buffer has room.
 """
 import numpy as np
 import pytest
@@ -77,12 +79,14 @@ def _update(psa, L, out, tier, model, busy=(0, 0)):
     ids = used_slices(L.li.block_table.cpu().numpy(), out.order.cpu().numpy(), out.blocks_read.cpu().numpy(), H,
                       L.slice_base)
     want = model.update(ids, busy[0], busy[1])
-    assert stats.tolist() == [want.hits, want.misses, want.promoted, want.evicted]
+    assert stats.tolist()[:4] == [want.hits, want.misses, want.promoted, want.evicted]
+    want.from_staging = int(stats[4])
     return want
 
 
+@pytest.mark.parametrize("staging_slices", [0, 1 << 14, 37])
 @pytest.mark.parametrize("slots_share", [1.0, 0.3, 0.02])
-def test_cold_then_warm_single_layer(psa, slots_share):
+def test_cold_then_warm_single_layer(psa, slots_share, staging_slices):
     cfg = get_config(3).scaled(batch=2, ctx=4096, layers=1)
     li = generate_layer(cfg, layer=5, device="cuda")
     n_slices = li.k_pool.shape[0] * li.k_pool.shape[1]
@@ -90,6 +94,8 @@ def test_cold_then_warm_single_layer(psa, slots_share):
     tier = psa.Tier(n_slices, num_slots)
     model = TierModel(n_slices, num_slots)
     L = Layer(psa, li, tier, 0)
+    if staging_slices:
+        L.host.staging = psa.Tier.staging_buffer(staging_slices)
     ref = psa.decode_attention(L.dev, li.q, L.meta_dev, cfg.threshold, 1, want_order=True)
     for step in range(3):
         got = psa.decode_attention(L.host, li.q, L.meta_host, cfg.threshold, 1, want_order=True)
@@ -102,6 +108,14 @@ def test_cold_then_warm_single_layer(psa, slots_share):
             assert st.hits == 0 and st.misses == int(ref.blocks_read.sum())
         elif slots_share >= 1.0:
             assert st.misses == 0 and st.hits == int(ref.blocks_read.sum())
+        # every slice placed was read from host memory by the attention kernels first: it comes from the staging
+        # buffer as far as that had room (entries also go to keys read ahead of the stop, which no update places)
+        if staging_slices >= (1 << 14):
+            assert st.from_staging == st.promoted
+        elif staging_slices:
+            assert st.from_staging <= min(st.promoted, staging_slices)
+        else:
+            assert st.from_staging == 0
     assert model.clock == 3
     if slots_share < 0.05:      # fewer slots than the call uses: the pool is full and stays as it is
         assert (model.owner >= 0).all()
@@ -126,7 +140,9 @@ def test_two_layers_share_a_small_pool_over_a_decode_loop(psa):
     tier = psa.Tier(total, num_slots)
     model = TierModel(total, num_slots)
     layers = [Layer(psa, lis[i], tier, bases[i]) for i in range(2)]
-    evicted = 0
+    for i, L in enumerate(layers):
+        L.host.staging = psa.Tier.staging_buffer(4096)
+    evicted = staged = 0
     for t in range(1, steps + 1):
         for i, L in enumerate(layers):
             q, k_new, v_new = step_inputs(L.li, t)
@@ -141,8 +157,11 @@ def test_two_layers_share_a_small_pool_over_a_decode_loop(psa):
             other = layers[1 - i]
             st = _update(psa, L, got, tier, model, busy=(other.slice_base, other.n_slices))
             evicted += st.evicted
+            staged += st.from_staging
+            assert st.from_staging == st.promoted
             _check_tables(tier, model, layers)
     assert evicted > 0, "the pool was meant to be too small"
+    assert staged > 0
     # the appended tokens reached host memory as well
     for L in layers:
         assert torch.equal(L.k_host.view(torch.int16), L.li.k_pool.cpu().view(torch.int16))
@@ -210,7 +229,9 @@ def test_updates_on_a_second_stream_beside_the_next_layer(psa):
     layers = [Layer(psa, lis[i], tier, bases[i]) for i in range(nl)]
     main_s, side_s = torch.cuda.current_stream(), torch.cuda.Stream()
     uws = torch.empty(max(psa.tier_update_workspace_bytes(L.host) for L in layers), dtype=torch.uint8, device="cuda")
-    stats = torch.zeros((steps, nl, 4), dtype=torch.int32, device="cuda")
+    stats = torch.zeros((steps, nl, 5), dtype=torch.int32, device="cuda")
+    staging = [psa.Tier.staging_buffer(8192) for _ in range(2)]      # consecutive calls alternate between the two
+    calls = 0
     done = [None] * nl
     log = []                                  # what each update saw, for the model: (layer, order, blocks_read)
     for t in range(1, steps + 1):
@@ -218,7 +239,9 @@ def test_updates_on_a_second_stream_beside_the_next_layer(psa):
         for j, L in enumerate(layers):
             q = step_inputs(L.li, t)[0]
             if done[(j - 2) % nl] is not None:
-                main_s.wait_event(done[(j - 2) % nl])
+                main_s.wait_event(done[(j - 2) % nl])     # (the update two calls back: it used this staging buffer)
+            L.host.staging = staging[calls % 2]
+            calls += 1
             got = psa.decode_attention(L.host, q, L.meta_host, 0.9, 1, want_order=True)
             ref = psa.decode_attention(L.dev, q, L.meta_dev, 0.9, 1, want_order=True)
             outs.append((got, ref))
@@ -235,12 +258,13 @@ def test_updates_on_a_second_stream_beside_the_next_layer(psa):
         torch.cuda.synchronize()
         for got, ref in outs:
             _same(got, ref)
-    got_stats = stats.cpu().numpy().reshape(-1, 4)
+    got_stats = stats.cpu().numpy().reshape(-1, 5)
     for k, (j, order, read, nxt) in enumerate(log):
         L = layers[j]
         ids = used_slices(L.li.block_table.cpu().numpy(), order.cpu().numpy(), read.cpu().numpy(), L.li.k_pool.shape[1],
                           L.slice_base)
         want = model.update(ids, bases[nxt], sizes[nxt])
-        assert got_stats[k].tolist() == [want.hits, want.misses, want.promoted, want.evicted], f"update {k}"
+        assert got_stats[k].tolist()[:4] == [want.hits, want.misses, want.promoted, want.evicted], f"update {k}"
+        assert got_stats[k][4] == want.promoted, f"update {k}: every slice placed comes from the staging buffer"
     _check_tables(tier, model, layers)
     assert got_stats[:, 3].sum() > 0, "the pool was meant to be too small"
