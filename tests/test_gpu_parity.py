@@ -35,6 +35,10 @@ CASES = {
     "c5_uniform": (_small(5, batch=2, ctx=4096), {}),
     "mha_g1": (_small(1, num_q_heads=8, num_kv_heads=8, ctx=2000), {}),
     "gqa_g2": (_small(1, num_q_heads=16, num_kv_heads=8, ctx=1500, dtype="bf16"), {}),
+    # flat attention goes deep: more chunks than the stop rule folds at a time (64 with one head per KV head, 32
+    # with two), so its state is carried from one group of chunks to the next
+    "flat_g1_many_chunks": (_small(5, batch=1, ctx=40000, num_q_heads=4, num_kv_heads=4), {}),
+    "flat_g2_many_chunks": (_small(5, batch=1, ctx=20000, num_q_heads=8, num_kv_heads=4), {}),
 }
 
 
