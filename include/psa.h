@@ -124,7 +124,9 @@ typedef struct {
     int32_t chunk_blocks;   /* ranked blocks per work item: a multiple of 4 in 8..64 (default 32)      */
     int32_t window_chunks;  /* least number of chunks of one (request, KV head) read beyond the chunks
                                already folded into the stop rule; the window grows to a quarter of the
-                               folded count, at most 256 (default: from the number of streams)               */
+                               folded count, and to this number times the (request, KV head) pairs of the
+                               call divided by those not yet finished, at most 256 (default: 96 MiB of
+                               keys over all pairs, 2 to 24 chunks)                                    */
     int32_t spin_limit;     /* looks (about a microsecond apart) a workgroup takes at the window before it
                                reads its chunk regardless (default 1<<14); the wait only limits read-ahead  */
     int32_t force_bitonic;  /* 1: always rank with the bitonic network (testing); 0: automatic        */

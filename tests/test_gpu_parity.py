@@ -130,7 +130,7 @@ def test_result_does_not_depend_on_tuning(psa, case, chunk, window, spin):
 
 
 def test_repeated_calls_are_bitwise_identical(psa, case):
-    """Scheduling is dynamic (atomic tickets) but every reduction has a fixed order."""
+    """Scheduling is dynamic (which chunks are published when the stop rule looks) but every reduction has a fixed order."""
     name, cfg, li, pb = case
     a = gc.run_gpu_decode(li, cfg.threshold, 1)
     b = gc.run_gpu_decode(li, cfg.threshold, 1)
