@@ -155,6 +155,61 @@ void oracle_block_metadata(const oracle_shape *sh, const uint16_t *k_pool, const
     }
 }
 
+/* ---------- mean-key metadata (Sec. 2.2 "KV Cache Selection": metadata vectors that represent a block's
+ * keys; the per-channel mean is the smallest of the constructions in use, half the bytes of the cuboid) ---- */
+/*
+ * Rounds a binary64 value to the 16-bit storage type, once, to nearest with ties to even: the exponent comes from
+ * frexp, the scaling is by powers of two (exact), the rounding is nearbyint's in the default rounding mode.  The
+ * values this is used on are means of storage-type numbers, so neither overflow nor NaN occurs; infinities and NaN
+ * are passed on as the type's own.
+ */
+static uint16_t encode(double x, int dtype) {
+    const int mant_bits = dtype ? 7 : 10, bias = dtype ? 127 : 15, exp_max = dtype ? 255 : 31;
+    uint16_t sign = (uint16_t)(signbit(x) ? 0x8000u : 0u);
+    if (isnan(x)) return (uint16_t)(sign | ((unsigned)exp_max << mant_bits) | 1u);
+    double a = fabs(x);
+    if (a == 0.0) return sign;
+    if (isinf(a)) return (uint16_t)(sign | ((unsigned)exp_max << mant_bits));
+    int e;
+    (void)frexp(a, &e);                      /* a = f * 2^e, f in [0.5, 1): the leading bit has weight 2^(e-1) */
+    int lead = e - 1;
+    int emin = 1 - bias;                     /* exponent of the smallest normal number */
+    if (lead < emin) {                       /* subnormal range: a fixed grid of 2^(emin - mant_bits) */
+        double steps = nearbyint(ldexp(a, mant_bits - emin));
+        return (uint16_t)(sign | (unsigned)steps);       /* (reaching 2^mant_bits is the smallest normal: same bits) */
+    }
+    double frac = nearbyint(ldexp(a, mant_bits - lead));  /* in [2^mant_bits, 2^(mant_bits+1)] */
+    if (frac >= ldexp(1.0, mant_bits + 1)) { frac = ldexp(1.0, mant_bits); lead += 1; }
+    if (lead + bias >= exp_max) return (uint16_t)(sign | ((unsigned)exp_max << mant_bits));
+    return (uint16_t)(sign | ((unsigned)(lead + bias) << mant_bits) | ((unsigned)frac - (1u << mant_bits)));
+}
+
+/*
+ * means[p][h][c] = the mean over the page's valid tokens of k[t][c], summed token by token in binary64 (exact for
+ * any keys whose magnitudes in one channel span less than 2^38, which covers every generated input), divided by
+ * the count and rounded once to the storage type.  A page with no valid token gets +0, and so does a channel
+ * whose mean is zero (the sum starts from +0).
+ */
+void oracle_block_means(const oracle_shape *sh, const uint16_t *k_pool, const int32_t *page_fill,
+                        uint16_t *means) {
+    const int H = sh->num_kv_heads, T = sh->page_size, D = sh->head_dim;
+#pragma omp parallel for schedule(static)
+    for (int p = 0; p < sh->num_pages; ++p) {
+        int fill = page_fill ? page_fill[p] : T;
+        if (fill > T) fill = T;
+        for (int h = 0; h < H; ++h) {
+            const uint16_t *kb = k_pool + ((size_t)p * H + h) * T * D;
+            uint16_t *out = means + ((size_t)p * H + h) * D;
+            for (int c = 0; c < D; ++c) {
+                if (fill <= 0) { out[c] = 0; continue; }
+                double sum = 0.0;
+                for (int t = 0; t < fill; ++t) sum += decode(kb[(size_t)t * D + c], sh->dtype);
+                out[c] = encode(sum / (double)fill, sh->dtype);
+            }
+        }
+    }
+}
+
 /* ---------- criticality scores (Algorithm 1, line 5) -------------------------------------- */
 /*
  * scorer 0 (the default reading of q . B_meta for cuboid metadata):
@@ -163,6 +218,9 @@ void oracle_block_metadata(const oracle_shape *sh, const uint16_t *k_pool, const
  * scorer 1 (a reading of the "cuboid-mean" metadata that Sec. 3.1 names as the default without
  *   defining it): the scaled logit of the cuboid's centre, q . (kmin + kmax)/2 / sqrt d, which is
  *   also the mean of the largest and the smallest logit the cuboid allows.  Parity unpinned.
+ * scorer 2 (mean-key metadata, `meta` is then the [page][KV head][channel] array of oracle_block_means): the
+ *   scaled logit of the block's mean key, q . mean / sqrt d -- the mean of the block's token logits, up to the
+ *   rounding of the stored mean.  Parity unpinned (a construction the paper names among others, Sec. 2.2).
  * CS[b] = max over the heads g of the group (reading: one ranking per KV head must serve all its
  * query heads; for scorer 0 max keeps the bound valid for each of them).
  * ub: [batch][num_q_heads][max_blocks] per-head scores, cs: [batch][num_kv_heads][max_blocks];
@@ -178,8 +236,8 @@ void oracle_block_scores(const oracle_shape *sh, const uint16_t *q, const uint16
         for (int h = 0; h < H; ++h) {
             for (int b = 0; b < N; ++b) {
                 int page = block_table[(size_t)r * sh->max_blocks + b];
-                const uint16_t *mn = meta + ((size_t)page * H + h) * 2 * D;
-                const uint16_t *mx = mn + D;
+                const uint16_t *mn = meta + ((size_t)page * H + h) * (scorer == 2 ? 1 : 2) * D;
+                const uint16_t *mx = scorer == 2 ? mn : mn + D;        /* (one vector per block with scorer 2) */
                 double best = -INFINITY;
                 for (int g = 0; g < G; ++g) {
                     const uint16_t *qg = q + ((size_t)r * Hq + h * G + g) * D;
@@ -188,7 +246,7 @@ void oracle_block_scores(const oracle_shape *sh, const uint16_t *q, const uint16
                         double qc = decode(qg[c], sh->dtype);
                         double a = qc * decode(mn[c], sh->dtype);
                         double z = qc * decode(mx[c], sh->dtype);
-                        acc += scorer == 1 ? 0.5 * (a + z) : (a > z ? a : z);
+                        acc += scorer == 2 ? a : (scorer == 1 ? 0.5 * (a + z) : (a > z ? a : z));
                     }
                     acc *= inv_sqrt_d;
                     if (ub) ub[((size_t)r * Hq + h * G + g) * sh->max_blocks + b] = acc;

@@ -137,7 +137,17 @@ def block_metadata(pb: Problem, page_fill=None) -> np.ndarray:
     return meta
 
 
-UPPER_BOUND, CUBOID_CENTER = 0, 1      # scorers (Algorithm 1, line 5; see psa_oracle.c)
+def block_means(pb: Problem, page_fill=None) -> np.ndarray:
+    """Mean-key metadata [P][H][D] (raw 16-bit patterns of the cache's type): see oracle_block_means."""
+    P, H, T, D = pb.k_pool.shape
+    means = np.zeros((P, H, D), dtype=np.uint16)
+    fill = None if page_fill is None else _i32(page_fill)
+    sh = pb.shape
+    _load().oracle_block_means(C.byref(sh), _p(pb.k_pool, C.c_uint16), _p(fill, C.c_int32), _p(means, C.c_uint16))
+    return means
+
+
+UPPER_BOUND, CUBOID_CENTER, MEAN_KEY = 0, 1, 2      # scorers (Algorithm 1, line 5; see psa_oracle.c)
 
 
 def block_scores(pb: Problem, meta: np.ndarray, scorer: int = UPPER_BOUND):
@@ -231,7 +241,7 @@ def psa_decode(pb: Problem, eps: float, m: int = 1, curves: bool = False,
                meta: np.ndarray | None = None, scorer: int = UPPER_BOUND) -> DecodeResult:
     """The whole path: metadata -> scores -> ranking -> progressive loop (Algorithm 1)."""
     if meta is None:
-        meta = block_metadata(pb, pb.page_fill())
+        meta = block_means(pb, pb.page_fill()) if scorer == MEAN_KEY else block_metadata(pb, pb.page_fill())
     _, cs = block_scores(pb, meta, scorer)
     order = block_order(pb, cs)
     res = psa_decode_ordered(pb, order, eps, m, curves)
@@ -246,7 +256,7 @@ def topk_attention(pb: Problem, k: int, meta: np.ndarray | None = None,
     definition of attention over the first min(k, N) ranked blocks.  mass_est is Algorithm 1's P_acc
     evaluated there (lines 15-16), read off the full curve of a run that never stops."""
     if meta is None:
-        meta = block_metadata(pb, pb.page_fill())
+        meta = block_means(pb, pb.page_fill()) if scorer == MEAN_KEY else block_metadata(pb, pb.page_fill())
     _, cs = block_scores(pb, meta, scorer)
     order = block_order(pb, cs)
     B, Hq, H, D, T, P, MB = pb.dims

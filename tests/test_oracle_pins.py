@@ -4,6 +4,7 @@ Each test names the passage it checks.  A plausible mistake in the oracle (a dro
 sign or index, a transposed operand, an off-by-one in N_left) fails at least one of them.
 """
 import math
+from fractions import Fraction
 import os
 
 import numpy as np
@@ -203,12 +204,94 @@ def test_center_score_is_the_mean_of_the_extreme_logits_of_the_cuboid(dtype):
             np.testing.assert_array_equal(cs[r, h, :n], ce[r, h * G:(h + 1) * G, :n].max(0))
 
 
+def _nearest_16bit(x: Fraction, dtype: int) -> int:
+    """The storage type's bit pattern nearest to the exact rational x (ties to the even pattern), found by
+    exact comparison: every finite non-negative pattern is tried as a neighbour of x's truncation."""
+    neg = x < 0
+    a = -x if neg else x
+    top = 0x7bff if dtype == po.F16 else 0x7f7f                      # largest finite pattern
+    vals = lambda b: Fraction(float(po.decode(np.array([b], dtype=np.uint16), dtype)[0]))
+    lo, hi = 0, top                                                   # patterns are monotone in value
+    while lo < hi:
+        mid = (lo + hi + 1) // 2
+        if vals(mid) <= a:
+            lo = mid
+        else:
+            hi = mid - 1
+    below, above = lo, min(lo + 1, top)
+    d0, d1 = a - vals(below), vals(above) - a
+    pick = below if (d0 < d1 or (d0 == d1 and below % 2 == 0) or above == below) else above
+    return pick | (0x8000 if neg else 0)
+
+
+@pytest.mark.parametrize("dtype", [po.F16, po.BF16])
+def test_mean_key_metadata_is_the_exactly_rounded_mean_of_the_valid_keys(dtype):
+    """Mean-key metadata against exact rational arithmetic: the mean of the block's valid keys per channel,
+    rounded once to the nearest pattern of the storage type (ties to even).  Partly filled pages count their
+    valid tokens only, an empty page gives +0, a one-token page gives the token itself."""
+    rng = np.random.default_rng(29)
+    pb = ref.random_problem(rng, B=2, Hq=4, Hkv=2, d=8, T=4, ctx=(13, 6), dtype=dtype)
+    fill = pb.page_fill()
+    # values that stress the rounding: tiny and large magnitudes, exact ties (x and x + 1 ulp average to a tie)
+    k = pb.k_pool.copy()
+    k[0, 0, 0, 0], k[0, 0, 1, 0], k[0, 0, 2, 0], k[0, 0, 3, 0] = 0x3c00, 0x3c01, 0x3c00, 0x3c01
+    k[0, 0, :, 1] = [0x0001, 0x0001, 0x0002, 0x0000]                       # subnormals
+    k[0, 1, :, 2] = [0x8000, 0x8000, 0x8000, 0x8000]                       # all -0
+    pb = po.Problem(pb.q, k, pb.v_pool, pb.block_table, pb.ctx_lens, pb.dtype)
+    means = po.block_means(pb, fill)
+    P, H, T, D = pb.k_pool.shape
+    assert means[0, 1, 2] == 0                                            # a zero mean is +0, whatever the zeros' signs
+    for p in range(P):
+        for h in range(H):
+            for c in range(D):
+                n = int(fill[p])
+                if n == 0:
+                    assert means[p, h, c] == 0
+                    continue
+                vals = [Fraction(float(po.decode(pb.k_pool[p, h, t, c:c + 1], dtype)[0])) for t in range(n)]
+                exact = sum(vals) / n
+                if exact == 0:
+                    assert means[p, h, c] == 0
+                    continue
+                assert means[p, h, c] == _nearest_16bit(exact, dtype), (p, h, c)
+                if n == 1:
+                    assert means[p, h, c] == pb.k_pool[p, h, 0, c]
+
+
+@pytest.mark.parametrize("dtype", [po.F16, po.BF16])
+def test_mean_key_score_is_the_mean_of_the_blocks_token_logits(dtype):
+    """Scorer 2: q . mean / sqrt(d) = the mean of the scaled logits of the block's tokens, up to the rounding of
+    the stored mean (half a unit in the last place per channel); the group reduce is a max; with one token per
+    block the score is that token's logit exactly."""
+    rng = np.random.default_rng(31)
+    pb = ref.random_problem(rng, B=2, Hq=6, Hkv=2, d=16, T=4, ctx=(13, 29), dtype=dtype)
+    means = po.block_means(pb, pb.page_fill())
+    per_head, cs = po.block_scores(pb, means, po.MEAN_KEY)
+    G, T = 3, 4
+    ulp = 2.0 ** (-10 if dtype == po.F16 else -7)
+    for r in range(2):
+        n = int(pb.num_blocks()[r])
+        for hq in range(6):
+            q = po.decode(pb.q[r, hq], pb.dtype)
+            s = ref.logits(pb, r, hq)
+            for b in range(n):
+                blk = s[b * T:(b + 1) * T]
+                mean_vec = po.decode(means[pb.block_table[r, b], hq // G], pb.dtype)
+                bound = float(np.abs(q) @ (np.abs(mean_vec) * ulp * 0.5 + 2.0 ** -24)) / math.sqrt(16) + 1e-12
+                assert abs(per_head[r, hq, b] - blk.mean()) <= bound
+                assert abs(per_head[r, hq, b] - q @ mean_vec / math.sqrt(16)) < 1e-12
+                if len(blk) == 1:
+                    assert abs(per_head[r, hq, b] - blk[0]) < 1e-12
+        for h in range(2):
+            np.testing.assert_array_equal(cs[r, h, :n], per_head[r, h * G:(h + 1) * G, :n].max(0))
+
+
 def test_scorer_changes_the_ranking_not_the_rule():
     """With either scorer the progressive loop is the same function of the ranking it is given."""
     pb = _problem(51)
-    for scorer in (po.UPPER_BOUND, po.CUBOID_CENTER):
+    for scorer in (po.UPPER_BOUND, po.CUBOID_CENTER, po.MEAN_KEY):
         res = po.psa_decode(pb, 0.9, 2, scorer=scorer)
-        meta = po.block_metadata(pb, pb.page_fill())
+        meta = po.block_means(pb, pb.page_fill()) if scorer == po.MEAN_KEY else po.block_metadata(pb, pb.page_fill())
         _, cs = po.block_scores(pb, meta, scorer)
         again = po.psa_decode_ordered(pb, po.block_order(pb, cs), 0.9, 2)
         assert np.array_equal(res.n_selected, again.n_selected) and np.array_equal(res.out, again.out)
