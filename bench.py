@@ -623,13 +623,17 @@ def main():
                               torch.empty((B, H), dtype=torch.int32, device=dev),
                               torch.empty((B, Hq), dtype=torch.float32, device=dev), None, None, None)
         scorers = {}
-        for name, code in (("upper_bound", psa.SCORE_UPPER_BOUND), ("cuboid_center", psa.SCORE_CUBOID_CENTER)):
+        # mean-key metadata: one vector per block, half the bytes of the cuboid (built here, outside the timed steps)
+        mean_metas = [psa.build_block_means(kvs[i], page_fill=layers[i].page_fill) for i in range(L)]
+        for name, code in (("upper_bound", psa.SCORE_UPPER_BOUND), ("cuboid_center", psa.SCORE_CUBOID_CENTER),
+                           ("mean_key", psa.SCORE_MEAN_KEY)):
+            use = mean_metas if code == psa.SCORE_MEAN_KEY else metas
             read, true_mass, gap, short = [], [], [], []
             for rep in range(2):
                 if rep == 1:
                     e0.record()
                 for i in range(L):
-                    psa.decode_attention(kvs[i], layers[i].q, metas[i], eps, m, workspace=ws, outputs=so,
+                    psa.decode_attention(kvs[i], layers[i].q, use[i], eps, m, workspace=ws, outputs=so,
                                          tuning=tun, scorer=code)
                     if rep == 0:
                         live = torch.isfinite(dlses[i])
@@ -644,9 +648,11 @@ def main():
                              "true_mass_mean": float(np.mean(true_mass)),
                              "estimate_minus_true_mass_mean": float(np.mean(gap)),
                              "heads_with_true_mass_below_threshold": float(np.mean(short)),
+                             "metadata_bytes_per_block": 256 if code == psa.SCORE_MEAN_KEY else 512,
                              "ms_per_step": e0.elapsed_time(e1)}
             log(f"[bench] scorer {name}: {scorers[name]}")
         assert psa.read_device_error(ws) == 0
+        del mean_metas
 
     # ---- the oracle on the host cores, bounded sample ----------------------------------------------------
     cpu = parity = None

@@ -61,8 +61,13 @@ enum {
  *   PSA_SCORE_UPPER_BOUND    sum_c max(q_c kmin_c, q_c kmax_c) / sqrt(d): the largest scaled logit any
  *                            key inside the block's bounding cuboid can give (default)
  *   PSA_SCORE_CUBOID_CENTER  q . (kmin + kmax)/2 / sqrt(d): the scaled logit of the cuboid's centre, a
- *                            reading of the "cuboid-mean" metadata Sec. 3.1 names as its default      */
-typedef enum { PSA_SCORE_UPPER_BOUND = 0, PSA_SCORE_CUBOID_CENTER = 1 } psa_scorer;
+ *                            reading of the "cuboid-mean" metadata Sec. 3.1 names as its default
+ *   PSA_SCORE_MEAN_KEY       q . mean / sqrt(d) over mean-key metadata (psa_build_block_means: one vector
+ *                            per block, half the bytes of the cuboid): the mean of the block's scaled
+ *                            logits.  Sec. 2.2 lists per-block vectors derived from the keys as what
+ *                            selection algorithms score by; this is the smallest of them.  The `meta`
+ *                            argument of the attention calls is then the means buffer.                */
+typedef enum { PSA_SCORE_UPPER_BOUND = 0, PSA_SCORE_CUBOID_CENTER = 1, PSA_SCORE_MEAN_KEY = 2 } psa_scorer;
 
 /*
  * Optional second tier (Sec. 3.1 KV cache manager, Sec. 3.4 unified memory management).  With a tier the
@@ -184,6 +189,19 @@ psa_status psa_append_kv(const psa_kv_desc *desc, const void *k_new, const void 
                          int32_t *status, void *stream);
 
 /*
+ * Mean-key metadata for PSA_SCORE_MEAN_KEY (Sec. 2.2 "KV Cache Selection": metadata vectors that stand for a
+ * block's keys): per (page, KV head) and channel the mean of the page's valid keys, computed in binary64 and
+ * rounded once, to nearest-even, to desc->dtype; a zero mean and a page without valid tokens give +0.
+ *   means      out [num_pages][num_kv_heads][head_dim], desc->dtype
+ *   page_fill, page_list, num_listed   as for psa_build_block_metadata
+ * psa_append_kv does not maintain this buffer (a rounded mean cannot be updated in place exactly): after an
+ * append, rebuild the pages that received a token with a page list.
+ * Errors: as psa_build_block_metadata.
+ */
+psa_status psa_build_block_means(const psa_kv_desc *desc, void *means, const int32_t *page_fill,
+                                 const int32_t *page_list, int32_t num_listed, void *stream);
+
+/*
  * One decode step of Progressive Sparse Attention for one layer (Algorithm 1; Sec. 3.2 for the
  * microbatch size and for the batched form in which every query stops on its own).
  * Per (request, KV head): score every block from its metadata (line 5: the largest scaled logit
@@ -193,7 +211,8 @@ psa_status psa_append_kv(const psa_kv_desc *desc, const void *k_new, const void 
  * n that is a multiple of check_granularity (or the last block) where
  *   P_acc = AS_acc / (AS_acc + AS_min * N_left) > threshold            (lines 13-18).
  *   q            [batch][num_q_heads][head_dim], desc->dtype
- *   meta         as written by psa_build_block_metadata (pages' valid-token counts included)
+ *   meta         as written by psa_build_block_metadata (pages' valid-token counts included); with
+ *                PSA_SCORE_MEAN_KEY as written by psa_build_block_means
  *   threshold    epsilon in [0,1]; 1 never stops early, so the result is dense attention
  *   check_granularity  m >= 1 (Sec. 3.2 "microbatch")
  *   out          [batch][num_q_heads][head_dim] float32

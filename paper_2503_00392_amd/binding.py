@@ -86,6 +86,8 @@ def load_library() -> C.CDLL:
         lib.psa_dense_workspace_bytes.argtypes = [C.POINTER(_KvDesc)]
         lib.psa_build_block_metadata.restype = C.c_int
         lib.psa_build_block_metadata.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, i32, vp]
+        lib.psa_build_block_means.restype = C.c_int
+        lib.psa_build_block_means.argtypes = [C.POINTER(_KvDesc), vp, vp, vp, i32, vp]
         lib.psa_decode_attention.restype = C.c_int
         lib.psa_decode_attention.argtypes = [C.POINTER(_KvDesc), vp, vp, f32, i32, i32, vp, vp, vp, vp, vp,
                                              vp, vp, vp, C.POINTER(_Tuning), vp, sz, vp]
@@ -248,6 +250,20 @@ def build_block_metadata(kv: KvCache, meta: torch.Tensor | None = None, page_fil
     return meta
 
 
+def build_block_means(kv: KvCache, means: torch.Tensor | None = None, page_fill=None, page_list=None,
+                      stream=None) -> torch.Tensor:
+    """psa_build_block_means; allocates `means` ([P][Hkv][128], the pool's type) if not given."""
+    P, H, T, D = kv.k_pool.shape
+    if means is None:
+        means = torch.empty((P, H, D), dtype=kv.k_pool.dtype, device=kv.block_table.device)
+    d = kv.desc()
+    n_listed = 0 if page_list is None else int(page_list.numel())
+    st = load_library().psa_build_block_means(C.byref(d), _ptr(means), _ptr(page_fill), _ptr(page_list), n_listed,
+                                              _stream(stream))
+    _check(st, "psa_build_block_means")
+    return means
+
+
 def append_kv(kv: KvCache, k_new: torch.Tensor, v_new: torch.Tensor, meta: torch.Tensor,
               status: torch.Tensor | None = None, stream=None) -> None:
     """psa_append_kv: writes into kv.k_pool, kv.v_pool, kv.ctx_lens and meta in place."""
@@ -260,7 +276,7 @@ def append_kv(kv: KvCache, k_new: torch.Tensor, v_new: torch.Tensor, meta: torch
     _check(st, "psa_append_kv")
 
 
-SCORE_UPPER_BOUND, SCORE_CUBOID_CENTER = 0, 1      # psa_scorer
+SCORE_UPPER_BOUND, SCORE_CUBOID_CENTER, SCORE_MEAN_KEY = 0, 1, 2      # psa_scorer
 
 
 @dataclass

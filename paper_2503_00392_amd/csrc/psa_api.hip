@@ -110,6 +110,23 @@ psa_status psa_build_block_metadata(const psa_kv_desc *d, void *meta, const int3
     return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
 }
 
+psa_status psa_build_block_means(const psa_kv_desc *d, void *means, const int32_t *page_fill,
+                                 const int32_t *page_list, int32_t num_listed, void *stream) {
+    psa_status st = check_desc(d, false, false);
+    if (st != PSA_OK) return st;
+    psa_kv_desc tiered;
+    if (d->tier) {      // pools in host memory: the kernel reads them over the host link
+        if ((st = check_tier(d, &tiered)) != PSA_OK) return st;
+        d = &tiered;
+    }
+    if (!means && d->num_pages > 0) return PSA_ERR_INVALID_ARG;
+    if (num_listed < 0 || (num_listed > 0 && !page_list)) return PSA_ERR_INVALID_ARG;
+    if ((long long)d->num_pages * d->num_kv_heads > INT32_MAX) return PSA_ERR_UNSUPPORTED;
+    if (page_list && num_listed == 0) return PSA_OK;
+    hipError_t e = psa::launch_means(d, means, page_fill, page_list, num_listed, (hipStream_t)stream);
+    return e == hipSuccess ? PSA_OK : PSA_ERR_LAUNCH;
+}
+
 psa_status psa_append_kv(const psa_kv_desc *d, const void *k_new, const void *v_new, void *meta,
                          int32_t *status, void *stream) {
     psa_status st = check_desc(d, true, true);
@@ -134,7 +151,8 @@ static psa_status decode_common(const psa_kv_desc *d, const void *q, const void 
     if (st != PSA_OK) return st;
     if (!(threshold >= 0.0f && threshold <= 1.0f)) return PSA_ERR_INVALID_ARG;   // also rejects NaN
     if (check_granularity < 1) return PSA_ERR_INVALID_ARG;
-    if (scorer != PSA_SCORE_UPPER_BOUND && scorer != PSA_SCORE_CUBOID_CENTER) return PSA_ERR_INVALID_ARG;
+    if (scorer != PSA_SCORE_UPPER_BOUND && scorer != PSA_SCORE_CUBOID_CENTER && scorer != PSA_SCORE_MEAN_KEY)
+        return PSA_ERR_INVALID_ARG;
     if (d->max_blocks_per_seq > psa::kMaxBlocks) return PSA_ERR_UNSUPPORTED;
     if (tuning) {
         const int cb = tuning->chunk_blocks;

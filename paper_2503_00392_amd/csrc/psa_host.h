@@ -50,6 +50,9 @@ hipError_t launch_dense(const psa_kv_desc *d, const void *q, float *out, float *
 hipError_t launch_metadata(const psa_kv_desc *d, void *meta, const int32_t *page_fill,
                            const int32_t *page_list, int num_listed, hipStream_t st);
 
+hipError_t launch_means(const psa_kv_desc *d, void *means, const int32_t *page_fill, const int32_t *page_list,
+                        int num_listed, hipStream_t st);
+
 // psa_append.hip
 hipError_t launch_append(const psa_kv_desc *d, const void *k_new, const void *v_new, void *meta,
                          int32_t *status, hipStream_t st);

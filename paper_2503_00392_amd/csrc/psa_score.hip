@@ -12,6 +12,8 @@ constexpr int kMaxRounds = 4;      // rounds a workgroup of score_kernel makes a
 //   UB[g][b] = (1/sqrt d) sum_c max(q_c kmin_c, q_c kmax_c) = (1/sqrt d) (q+ . kmax + q- . kmin)
 //   with q+ = max(q,0), q- = min(q,0).
 // Cuboid centre (CENTER = 1): (1/sqrt d) q . (kmin + kmax)/2 = (1/(2 sqrt d)) (q . kmax + q . kmin).
+// Mean key (CENTER = 2, this kernel only): `meta` holds one vector per (page, KV head), 256 bytes, the mean of the
+// block's keys; the score is (1/sqrt d) q . mean.
 // Either way CS[b] = max over the heads g of the group.
 // grid (ceil(max_blocks / (64 rounds)), S), 256 threads; a workgroup covers 64*rounds consecutive blocks, wave w
 // the 16*rounds blocks from 16*rounds*w.  A 16-lane row handles one block per step: lane cl takes channels
@@ -52,7 +54,7 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
         for (int j = 0; j < 4; ++j) {
             const uint32_t neg = ((w[j] >> 15) & 0x00010001u) * 0xFFFFu;   // 0xFFFF in each negative half
             qn[g][j] = CENTER ? w[j] : (w[j] & neg);
-            qp[g][j] = CENTER ? w[j] : (w[j] & ~neg);
+            qp[g][j] = CENTER == 2 ? 0u : (CENTER ? w[j] : (w[j] & ~neg));
         }
     }
 
@@ -63,9 +65,10 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
         for (int it = 0; it < 4; ++it) {
             const int j = min(16 * rd + 4 * it + row, mine - 1);     // (clamped: the loads need no branch)
             const int page = __shfl(page_of_lane, j);
-            const uint8_t *mp = meta + ((size_t)page * kv.num_kv_heads + h) * kMetaBytes + cl * 16;
+            const uint8_t *mp = meta + ((size_t)page * kv.num_kv_heads + h) * (CENTER == 2 ? 256 : kMetaBytes) + cl * 16;
             lo[it] = ld16(mp);
-            hi[it] = ld16(mp + 256);
+            if constexpr (CENTER == 2) hi[it] = make_uint4(0, 0, 0, 0);
+            else hi[it] = ld16(mp + 256);
         }
     };
     auto reduce = [&](int rd, const uint4 (&lo)[4], const uint4 (&hi)[4]) {
@@ -83,7 +86,7 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
 #pragma unroll
                 for (int x = 0; x < 4; ++x) p = dot2<DT>(b[x], qp[g][x], p);
                 p = row_sum16(p);
-                cs = fmaxf(cs, p * (CENTER ? 0.5f * kScale : kScale));
+                cs = fmaxf(cs, p * (CENTER == 1 ? 0.5f * kScale : kScale));
             }
             if (cl == 0 && j < mine) {
                 scores[(size_t)s * kv.max_blocks + base + j] = cs;
@@ -272,6 +275,11 @@ static hipError_t launch_score_t(const KvView &kv, int scorer, const void *q, co
     long long per = ((long long)S * kv.max_blocks) / (4ll * compute_units() * kScoreBlocks);
     const int rounds = per < 1 ? 1 : (per > kMaxRounds ? kMaxRounds : (int)per);
     const dim3 grid_r((kv.max_blocks + kScoreBlocks * rounds - 1) / (kScoreBlocks * rounds), S);
+    if (scorer == 2) {
+        score_kernel<DT, G, 2><<<grid_r, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
+                                                       scores_out, ws.header, rounds);
+        return hipGetLastError();
+    }
     if constexpr (G >= 8) {
         if (scorer == 1)
             score_mfma_kernel<DT, G, 1><<<grid, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,

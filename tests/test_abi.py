@@ -98,7 +98,7 @@ def test_decode_rejects_bad_scalars_and_null_buffers(lib):
     assert _decode(lib, d, threshold=-0.01) == 1
     assert _decode(lib, d, threshold=1.01) == 1
     assert _decode(lib, d, m=0) == 1
-    assert _decode(lib, d, scorer=2) == 1 and _decode(lib, d, scorer=-1) == 1
+    assert _decode(lib, d, scorer=3) == 1 and _decode(lib, d, scorer=-1) == 1
     for name in ("q", "meta", "out", "nsel", "mass", "ws"):
         assert _decode(lib, d, **{name: None}) == 1, name
     assert _decode(lib, d, ws_bytes=1024) == 3
@@ -133,6 +133,10 @@ def test_dense_and_metadata_reject_on_the_host(lib):
     assert lib.psa_build_block_metadata(C.byref(d), 0x10, None, None, -1, None) == 1
     assert lib.psa_build_block_metadata(C.byref(d), 0x10, None, 0x20, 0, None) == 0     # empty list: nothing to do
     assert lib.psa_build_block_metadata(C.byref(_desc(dtype=5)), 0x10, None, None, 0, None) == 2
+    assert lib.psa_build_block_means(C.byref(d), None, None, None, 0, None) == 1
+    assert lib.psa_build_block_means(C.byref(d), 0x10, None, None, 3, None) == 1        # count without a list
+    assert lib.psa_build_block_means(C.byref(d), 0x10, None, 0x20, 0, None) == 0        # empty list: nothing to do
+    assert lib.psa_build_block_means(C.byref(_desc(dtype=5)), 0x10, None, None, 0, None) == 2
     assert lib.psa_read_device_error(None, None, None) == 1
 
 

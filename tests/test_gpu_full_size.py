@@ -162,3 +162,15 @@ def test_center_scorer_full_size_config3(psa):
     rep = gc.check_decode_against_oracle(gc.to_problem(li), gpu, cfg.threshold, 1, requests=[1, 2], scorer=po.CUBOID_CENTER)
     print(f"\n[config 3 layer 23 centre scorer] {rep}")
     rep.assert_accounted()
+
+
+def test_mean_key_scorer_full_size_config3(psa):
+    cfg = get_config(3)
+    li = generate_layer(cfg, layer=23, device="cuda")
+    means = psa.build_block_means(gc.to_kv(li), page_fill=li.page_fill)
+    gpu = gc.run_gpu_decode(li, cfg.threshold, 1, meta=means, scorer=psa.SCORE_MEAN_KEY)
+    _properties(psa, cfg, li, gpu, cfg.threshold, 1)
+    rep = gc.check_decode_against_oracle(gc.to_problem(li), gpu, cfg.threshold, 1, requests=[0, 3], scorer=po.MEAN_KEY)
+    print(f"\n[config 3 layer 23 mean-key scorer] {rep}")
+    rep.assert_accounted()
+

@@ -226,6 +226,30 @@ def test_cuboid_center_scorer_matches_oracle(psa, case):
     assert gc.rel_l2(top.out.cpu().numpy().astype(np.float64), own).max() <= gc.OUT_RTOL
 
 
+def test_mean_key_metadata_and_scorer_match_oracle(psa, case):
+    """The third scorer: one mean vector per block (bit for bit the oracle's exactly rounded means, partly filled
+    pages included), scored by the mean key's logit; everything after the score is the same path."""
+    name, cfg, li, pb = case
+    kv = gc.to_kv(li)
+    means = psa.build_block_means(kv, page_fill=li.page_fill)
+    torch.cuda.synchronize()
+    want = po.block_means(pb, li.page_fill.cpu().numpy())
+    assert np.array_equal(means.view(torch.int16).cpu().numpy().view(np.uint16), want)
+    # a listed rebuild writes the listed pages only, and the same bits
+    listed = torch.arange(0, li.k_pool.shape[0], 3, dtype=torch.int32, device="cuda")
+    again = torch.zeros_like(means)
+    psa.build_block_means(kv, means=again, page_fill=li.page_fill, page_list=listed)
+    torch.cuda.synchronize()
+    got = again.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got[::3], want[::3]) and not got[1::3].any()
+    for m in (1, 4):
+        gpu = gc.run_gpu_decode(li, cfg.threshold, m, meta=means, scorer=psa.SCORE_MEAN_KEY)
+        rep = gc.check_decode_against_oracle(pb, gpu, cfg.threshold, m, scorer=po.MEAN_KEY)
+        print(f"\n[{name} mean-key scorer m={m}] {rep}")
+        assert rep.empty == int((pb.num_blocks() == 0).sum()) * pb.q.shape[1]
+        rep.assert_accounted()
+
+
 @pytest.mark.parametrize("which", ["c1_ragged", "c3_small_bf16"])
 def test_incremental_decode_loop(psa, which):
     """Several decode steps in a row: append the step's token (K, V, metadata, length -- all on the GPU),
