@@ -389,57 +389,72 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     // ---- keys: wave w takes blocks [16*it + 4*w, +4), each a 4 KiB slice read as four coalesced 1 KiB
     //      loads.  A operand of the product: row n = token n of the block, same channel assignment as
     //      the queries. ----------------------------------------------------------------------------
-    for (int i0 = wave * kBatch; i0 < nblk; i0 += (kSelectThreads / 64) * kBatch) {
+    auto issue = [&](int i, uint4 (&dst)[4]) {
+        const uint8_t *kp = key_slice(kv, sh.page[i], h) + lane * 16;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) dst[kk] = ld16(kp + kk * 1024);
+    };
+    auto consume = [&](int i, const uint4 (&k)[4]) {
+        // (second tier with a staging buffer: a slice that came over the host link is kept for the update)
+        if (kv.staging != nullptr && sh.page[i] >= 0) stage_key_slice(kv, sh.page[i], h, k, lane);
+        f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        // the slice arrived as four coalesced 1 KiB rows of lanes (loading it in the operand's layout
+        // would touch sixteen 64-byte segments per instruction); the wave turns it into that layout
+        // through its own LDS patch (row = token, 17 16-byte words apart: no bank conflicts)
+        uint4 *stg = sh.stage[wave];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) stg[(kk * 4 + (lane >> 4)) * 17 + (lane & 15)] = k[kk];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+        uint4 a[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) a[kk] = stg[arow * 17 + kk * 4 + kq];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) acc = mfma_16x16x32<DT>(a[kk], qb[kk], acc);
+        // the lane now holds head n's logits of tokens kq, 4+kq, 8+kq, 12+kq
+        const int valid = sh.valid[i];
+        float sc[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) sc[x] = (4 * x + kq < valid) ? acc[x] * kScaleLog2 : -INFINITY;
+        if (n < G)
+            *reinterpret_cast<float4 *>(lg_out + ((size_t)i * G + n) * kPage + 4 * kq) =
+                make_float4(sc[0], sc[1], sc[2], sc[3]);
+        // the block's log-sum-exp for head n, across the 4 token groups
+        float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        float sum = (exp2_fast(sc[0] - mx) + exp2_fast(sc[1] - mx)) +
+                    (exp2_fast(sc[2] - mx) + exp2_fast(sc[3] - mx));
+        sum += __shfl_xor(sum, 16);
+        sum += __shfl_xor(sum, 32);
+        if (lane < G) sh.Lb[i][lane] = mx + log2_fast(sum);
+    };
+    constexpr int kWaves = kSelectThreads / 64;
+    if (nblk == 2 * kWaves * kBatch) {
+        // A whole chunk of 32 blocks, eight per wave: a rolling window.  Four slices are in flight; the oldest is
+        // worked on and its registers go to the next load at once, so the wave never stands with nothing in
+        // flight between rounds (a quarter of a round is arithmetic, LDS and stores).
         uint4 ka[kBatch][4];
+        auto block_of = [&](int k) { return (k / kBatch) * (kWaves * kBatch) + wave * kBatch + (k % kBatch); };
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            if (i0 + u < nblk) {
-                const uint8_t *kp = key_slice(kv, sh.page[i0 + u], h) + lane * 16;
+        for (int u = 0; u < kBatch; ++u) issue(block_of(u), ka[u]);
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) ka[u][kk] = ld16(kp + kk * 1024);
-            }
+        for (int k = 0; k < 2 * kBatch; ++k) {
+            consume(block_of(k), ka[k % kBatch]);
+            if (k + kBatch < 2 * kBatch) issue(block_of(k + kBatch), ka[k % kBatch]);
         }
+    } else {
+        for (int i0 = wave * kBatch; i0 < nblk; i0 += kWaves * kBatch) {
+            uint4 ka[kBatch][4];
 #pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-            const int i = i0 + u;
-            if (i < nblk) {
-                // (second tier with a staging buffer: a slice that came over the host link is kept for the update)
-                if (kv.staging != nullptr && sh.page[i] >= 0) stage_key_slice(kv, sh.page[i], h, ka[u], lane);
-                f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
-                // the slice arrived as four coalesced 1 KiB rows of lanes (loading it in the operand's layout
-                // would touch sixteen 64-byte segments per instruction); the wave turns it into that layout
-                // through its own LDS patch (row = token, 17 16-byte words apart: no bank conflicts)
-                uint4 *stg = sh.stage[wave];
+            for (int u = 0; u < kBatch; ++u)
+                if (i0 + u < nblk) issue(i0 + u, ka[u]);
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) stg[(kk * 4 + (lane >> 4)) * 17 + (lane & 15)] = ka[u][kk];
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-                uint4 a[4];
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) a[kk] = stg[arow * 17 + kk * 4 + kq];
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-                __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) acc = mfma_16x16x32<DT>(a[kk], qb[kk], acc);
-                // the lane now holds head n's logits of tokens kq, 4+kq, 8+kq, 12+kq
-                const int valid = sh.valid[i];
-                float sc[4];
-#pragma unroll
-                for (int x = 0; x < 4; ++x) sc[x] = (4 * x + kq < valid) ? acc[x] * kScaleLog2 : -INFINITY;
-                if (n < G)
-                    *reinterpret_cast<float4 *>(lg_out + ((size_t)i * G + n) * kPage + 4 * kq) =
-                        make_float4(sc[0], sc[1], sc[2], sc[3]);
-                // the block's log-sum-exp for head n, across the 4 token groups
-                float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                float sum = (exp2_fast(sc[0] - mx) + exp2_fast(sc[1] - mx)) +
-                            (exp2_fast(sc[2] - mx) + exp2_fast(sc[3] - mx));
-                sum += __shfl_xor(sum, 16);
-                sum += __shfl_xor(sum, 32);
-                if (lane < G) sh.Lb[i][lane] = mx + log2_fast(sum);
-            }
+            for (int u = 0; u < kBatch; ++u)
+                if (i0 + u < nblk) consume(i0 + u, ka[u]);
         }
     }
     lds_barrier();
