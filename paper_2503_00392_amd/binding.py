@@ -241,7 +241,7 @@ def build_block_metadata(kv: KvCache, meta: torch.Tensor | None = None, page_fil
     """psa_build_block_metadata; allocates `meta` ([P][Hkv][2][128], the pool's type) if not given."""
     P, H, T, D = kv.k_pool.shape
     if meta is None:
-        meta = torch.empty((P, H, 2, D), dtype=kv.k_pool.dtype, device=kv.k_pool.device)
+        meta = torch.empty((P, H, 2, D), dtype=kv.k_pool.dtype, device=kv.block_table.device)
     d = kv.desc()
     n_listed = 0 if page_list is None else int(page_list.numel())
     st = load_library().psa_build_block_metadata(C.byref(d), _ptr(meta), _ptr(page_fill), _ptr(page_list),

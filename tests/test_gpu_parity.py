@@ -269,6 +269,7 @@ def test_incremental_decode_loop(psa, which):
     kv = gc.to_kv(li)
     fill0 = torch.from_numpy(gc.to_problem(li).page_fill()).cuda()
     meta = psa.build_block_metadata(kv, page_fill=fill0)
+    means = psa.build_block_means(kv, page_fill=fill0)      # mean-key metadata: rebuilt for the touched pages each step
     pb = gc.to_problem(li)
     status = torch.full((cfg.batch,), -1, dtype=torch.int32, device="cuda")
     for t in range(1, steps + 1):
@@ -294,6 +295,14 @@ def test_incremental_decode_loop(psa, which):
         assert psa.read_device_error(out._workspace) == 0
         rep = gc.check_decode_against_oracle(pb, out, cfg.threshold, 1)
         rep.assert_accounted()
+        # mean-key metadata is not maintained by the append: the pages that received a token are rebuilt from a list
+        touched = torch.tensor([int(pb.block_table[r, (int(pb.ctx_lens[r]) - 1) // 16]) for r in range(cfg.batch)],
+                               dtype=torch.int32, device="cuda")
+        fill_dev = torch.from_numpy(fill.astype(np.int32)).cuda()
+        psa.build_block_means(kv, means=means, page_fill=fill_dev, page_list=touched)
+        torch.cuda.synchronize()
+        want_means = po.block_means(pb, fill)
+        assert np.array_equal(as_bits(means)[used], want_means[used]), f"mean-key metadata differs after step {t}"
     assert np.array_equal(pb.ctx_lens, np.array(start) + steps)
 
 

@@ -188,6 +188,22 @@ def test_fixed_budget_and_ragged_batch_with_a_tier(psa):
     _same(got, ref)
 
 
+def test_metadata_builds_read_a_tiered_cache_in_place(psa):
+    """Both metadata builds over pools in pinned host memory give the bits they give over the same pools in device
+    memory."""
+    cfg = get_config(3).scaled(batch=2, ctx=3000, layers=1)
+    li = generate_layer(cfg, layer=4, device="cuda", poison_tail=True)
+    n_slices = li.k_pool.shape[0] * li.k_pool.shape[1]
+    tier = psa.Tier(n_slices, 64)
+    L = Layer(psa, li, tier, 0)
+    fill = torch.from_numpy(gc.to_problem(li).page_fill()).cuda()
+    for build in (psa.build_block_metadata, psa.build_block_means):
+        a = build(L.dev, page_fill=fill)
+        b = build(L.host, page_fill=fill)
+        torch.cuda.synchronize()
+        assert b.is_cuda and torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
 def test_tier_arguments_are_checked_on_the_host(psa):
     cfg = get_config(1).scaled(ctx=256)
     li = generate_layer(cfg, device="cuda")
