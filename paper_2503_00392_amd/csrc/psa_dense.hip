@@ -134,7 +134,7 @@ __global__ __launch_bounds__(512) void dense_combine_kernel(const float *__restr
                                                             int G, int num_kv_heads, int num_q_heads,
                                                             float *__restrict__ out,
                                                             float *__restrict__ lse) {
-    __shared__ float red[512];
+    __shared__ float red[8];
     __shared__ float wgt[1024];                 // rescale factor of every split (nsplit <= 1024)
     __shared__ float num_part[4][kHeadDim];
     __shared__ float den_part[4];
@@ -145,14 +145,11 @@ __global__ __launch_bounds__(512) void dense_combine_kernel(const float *__restr
     const size_t stride = (size_t)G * kDenseStride;
     float M = -INFINITY;
     for (int i = tid; i < nsplit; i += 512) { const float mi = src[i * stride]; wgt[i] = mi; M = fmaxf(M, mi); }
-    red[tid] = M;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
+    if ((tid & 63) == 0) red[tid >> 6] = M;
     __syncthreads();
-    for (int d = 256; d >= 1; d >>= 1) {
-        if (tid < d) red[tid] = fmaxf(red[tid], red[tid + d]);
-        __syncthreads();
-    }
-    M = red[0];
-    __syncthreads();
+    M = fmaxf(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])), fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7])));
     for (int i = tid; i < nsplit; i += 512) {
         const float mi = wgt[i];
         wgt[i] = (mi == -INFINITY || M == -INFINITY) ? 0.0f : exp2_fast(mi - M);

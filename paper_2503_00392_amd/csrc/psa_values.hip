@@ -183,7 +183,7 @@ __global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, i
                                                        int32_t *__restrict__ blocks_read,
                                                        float *__restrict__ lse_out,
                                                        int32_t *__restrict__ traffic_out) {
-    __shared__ float red[512];
+    __shared__ float red[8];
     __shared__ float wgt[kMaxBlocks / 4];        // per-unit rescale factor (value units are >= 4 blocks)
     __shared__ __attribute__((aligned(16))) float num_part[kUnitLanes][kHeadDim];
     const int s = blockIdx.x / G, g = blockIdx.x % G, tid = threadIdx.x;
@@ -204,13 +204,12 @@ __global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, i
     // reference maximum over the units
     float M = -INFINITY;
     for (int i = tid; i < nun; i += 512) { const float mi = src[i * stride]; wgt[i] = mi; M = fmaxf(M, mi); }
-    red[tid] = M;
+    // (over the wave with lane exchanges, over the eight waves through LDS: two barriers instead of ten)
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
+    if ((tid & 63) == 0) red[tid >> 6] = M;
     __syncthreads();
-    for (int d = 256; d >= 1; d >>= 1) {
-        if (tid < d) red[tid] = fmaxf(red[tid], red[tid + d]);
-        __syncthreads();
-    }
-    M = red[0];
+    M = fmaxf(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])), fmaxf(fmaxf(red[4], red[5]), fmaxf(red[6], red[7])));
     __syncthreads();
     // per-unit weights and the denominator
     float den = 0.0f;
@@ -220,13 +219,11 @@ __global__ __launch_bounds__(512) void finalize_kernel(KvView kv, DecodeWs ws, i
         wgt[i] = w;
         den += src[i * stride + 1] * w;
     }
-    red[tid] = den;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) den += __shfl_xor(den, d);          // (a fixed tree: reproducible)
+    if ((tid & 63) == 0) red[tid >> 6] = den;
     __syncthreads();
-    for (int d = 256; d >= 1; d >>= 1) {
-        if (tid < d) red[tid] += red[tid + d];
-        __syncthreads();
-    }
-    den = red[0];
+    den = ((red[0] + red[1]) + (red[2] + red[3])) + ((red[4] + red[5]) + (red[6] + red[7]));
     // numerator: channels 4*cq .. 4*cq+3, units uj, uj+16, ...; four loads in flight per thread
     float4 num = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     for (int i0 = uj; i0 < nun; i0 += 4 * kUnitLanes) {
