@@ -339,7 +339,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-            "(the path shards by request or by KV head with no exchange, see DESIGN.md)")
+            "(the path shards by request or by KV head with no exchange between the shards)")
         sys.exit(2)
 
     import numpy as np
@@ -518,7 +518,7 @@ def main():
                 phase_ms[n].append(hev.elapsed_ms(ev[j], ev[j + 1]))
     hev.destroy()
     phase_avg = {n: float(np.mean(v)) for n, v in phase_ms.items()}
-    # algorithmic bytes per launch ("Measurement"): the selection kernel must move the key
+    # algorithmic bytes per launch: the selection kernel must move the key
     # slices of the blocks read and their page ids, the attention kernel the value slices and page ids,
     # the scoring kernel the metadata and the block table.  Scratch the implementation adds (stored
     # logits, partials) is not counted.
