@@ -20,7 +20,7 @@ __device__ __forceinline__ Slice load_slice(const uint8_t *slice_base, int lane)
     Slice s;
     const uint8_t *p = slice_base + lane * 16;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) s.r[i] = ld16(p + i * 1024);
+    for (int i = 0; i < 4; ++i) s.r[i] = ld16_stream(p + i * 1024);
     return s;
 }
 

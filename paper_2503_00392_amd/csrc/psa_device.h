@@ -174,6 +174,13 @@ __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float acc) {
 typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+// Four floats written once and read once, by a later kernel, and four such floats read (see ld16_stream).
+__device__ __forceinline__ void store_stream(float *p, f32x4_t v) {
+    __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t *>(p));
+}
+__device__ __forceinline__ f32x4_t load_stream(const float *p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(p));
+}
 template <int DT>
 __device__ __forceinline__ f32x4_t mfma_16x16x32(const uint4 &a, const uint4 &b, f32x4_t c) {
     if constexpr (DT == 0) {
@@ -247,6 +254,15 @@ __device__ __forceinline__ void lds_barrier() {
 
 // 16-byte global load of 8 packed 16-bit values.
 __device__ __forceinline__ uint4 ld16(const uint8_t *p) { return *reinterpret_cast<const uint4 *>(p); }
+
+// The same for data that is read once (key and value slices, metadata records, the stored logits): marked
+// non-temporal, so that hundreds of megabytes streaming through a launch do not push out of the caches what is
+// used again -- queries, page lists, control words, the logits on their way to the next kernel.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld16_stream(const uint8_t *p) {
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 __device__ __forceinline__ int clamp_page(int page, int num_pages, int32_t *header) {
     if ((unsigned)page >= (unsigned)num_pages) {

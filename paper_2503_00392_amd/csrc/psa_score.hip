@@ -66,9 +66,9 @@ __global__ __launch_bounds__(256) void score_kernel(KvView kv, const uint8_t *__
             const int j = min(16 * rd + 4 * it + row, mine - 1);     // (clamped: the loads need no branch)
             const int page = __shfl(page_of_lane, j);
             const uint8_t *mp = meta + ((size_t)page * kv.num_kv_heads + h) * (CENTER == 2 ? 256 : kMetaBytes) + cl * 16;
-            lo[it] = ld16(mp);
+            lo[it] = ld16_stream(mp);
             if constexpr (CENTER == 2) hi[it] = make_uint4(0, 0, 0, 0);
-            else hi[it] = ld16(mp + 256);
+            else hi[it] = ld16_stream(mp + 256);
         }
     };
     auto reduce = [&](int rd, const uint4 (&lo)[4], const uint4 (&hi)[4]) {
@@ -155,8 +155,8 @@ __global__ __launch_bounds__(256) void score_pages_kernel(KvView kv, const uint8
             const int j = min((4 * rd + it) * BS + sub, mine - 1);     // (clamped: the loads need no branch)
             const int page = __shfl(page_of_lane, j);
             const uint8_t *mp = meta + ((size_t)page * H + h) * kMetaBytes + cl * 16;
-            lo[it] = ld16(mp);
-            hi[it] = ld16(mp + 256);
+            lo[it] = ld16_stream(mp);
+            hi[it] = ld16_stream(mp + 256);
         }
     };
     auto reduce = [&](int rd, const uint4 (&lo)[4], const uint4 (&hi)[4]) {
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(KvView kv, const uint8_
     const uint8_t *mp = meta + ((size_t)page * kv.num_kv_heads + h) * kMetaBytes + kq * 16;
     uint4 a[8];
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) a[kk] = ld16(mp + kk * 64);
+    for (int kk = 0; kk < 8; ++kk) a[kk] = ld16_stream(mp + kk * 64);
     // B operand: column n = head n; the same 8 numbers of the record's index range, taken from q with the
     // entries of the wrong sign zeroed (steps 0-3 meet the minima, 4-7 the maxima)
     f32x4_t d = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -318,7 +318,7 @@ __global__ __launch_bounds__(512) void score_pages_mfma_kernel(KvView kv, const 
         const int page = __shfl(page_of_lane, min(16 * rd + n, mine - 1));     // (clamped: the loads need no branch)
         const uint8_t *mp = meta + ((size_t)page * H + h) * kMetaBytes + kq * 16;
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) dst[kk] = ld16(mp + kk * 64);
+        for (int kk = 0; kk < 8; ++kk) dst[kk] = ld16_stream(mp + kk * 64);
     };
     auto reduce = [&](int rd, const uint4 (&src)[8]) {
         f32x4_t d = {0.0f, 0.0f, 0.0f, 0.0f};

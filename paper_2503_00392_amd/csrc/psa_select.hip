@@ -392,7 +392,7 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
     auto issue = [&](int i, uint4 (&dst)[4]) {
         const uint8_t *kp = key_slice(kv, sh.page[i], h) + lane * 16;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) dst[kk] = ld16(kp + kk * 1024);
+        for (int kk = 0; kk < 4; ++kk) dst[kk] = ld16_stream(kp + kk * 1024);
     };
     auto consume = [&](int i, const uint4 (&k)[4]) {
         // (second tier with a staging buffer: a slice that came over the host link is kept for the update)
@@ -420,8 +420,7 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
 #pragma unroll
         for (int x = 0; x < 4; ++x) sc[x] = (4 * x + kq < valid) ? acc[x] * kScaleLog2 : -INFINITY;
         if (n < G)
-            *reinterpret_cast<float4 *>(lg_out + ((size_t)i * G + n) * kPage + 4 * kq) =
-                make_float4(sc[0], sc[1], sc[2], sc[3]);
+            store_stream(lg_out + ((size_t)i * G + n) * kPage + 4 * kq, f32x4_t{sc[0], sc[1], sc[2], sc[3]});
         // the block's log-sum-exp for head n, across the 4 token groups
         float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
         mx = fmaxf(mx, __shfl_xor(mx, 16));

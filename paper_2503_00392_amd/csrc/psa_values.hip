@@ -102,14 +102,14 @@ __global__ __launch_bounds__(256, 4) void attend_kernel(KvView kv, DecodeWs ws, 
     float l = 0.0f;
     for (int j0 = 0; j0 < jmax; j0 += kValueDepth) {
         Slice v[kValueDepth];
-        float4 x[kValueDepth];
+        f32x4_t x[kValueDepth];
         int valid[kValueDepth], blk[kValueDepth];
 #pragma unroll
         for (int u = 0; u < kValueDepth; ++u) {    // (index clamped, loads made anyway: no branch around a load)
             const int j = min(j0 + u, jmax - 1);
             blk[u] = wave + 4 * j;
             v[u] = load_slice(value_slice(kv, __shfl(pg, j), h), lane);
-            x[u] = *reinterpret_cast<const float4 *>(lg + (size_t)blk[u] * (kPage * G));
+            x[u] = load_stream(lg + (size_t)blk[u] * (kPage * G));
             valid[u] = min(kPage, ctx - __shfl(od, j) * kPage);
         }
 #pragma unroll
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(256, 4) void attend_kernel(KvView kv, DecodeWs ws, 
                 // tokens beyond `valid` hold -inf logits; blocks beyond the head's stop, and heads beyond the
                 // group, weigh nothing
                 const bool on = cl < G && blk[u] < mycnt;
-                float pw[4] = {x[u].x, x[u].y, x[u].z, x[u].w};
+                float pw[4] = {x[u][0], x[u][1], x[u][2], x[u][3]};
                 uint32_t hi[4], lo[4];
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
