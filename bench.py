@@ -427,7 +427,7 @@ def main():
     ceiling_gbs = probe.numel() / (float(np.median(probe_ms)) * 1e-3) / 1e9
     read_ceiling = {"GBps": ceiling_gbs, "GBps_best": probe.numel() / (min(probe_ms) * 1e-3) / 1e9,
                     "frac_of_peak": ceiling_gbs / HBM_PEAK_GBS, "bytes": probe.numel(), "runs": len(probe_ms),
-                    "kernel": "bench_stream_read_probe (plain 16-byte loads, one pass)"}
+                    "kernel": "bench_stream_read_probe (16-byte non-temporal loads, one pass)"}
     del probe
     log(f"[bench] streaming-read ceiling {ceiling_gbs:.0f} GB/s")
 
