@@ -196,8 +196,8 @@ __global__ __launch_bounds__(256) void score_pages_kernel(KvView kv, const uint8
 }
 
 // =================================================================================================
-// Scoring on the matrix cores (used at G = 8, where the version above is bound by its arithmetic; at G <= 4
-// it is the faster one, its loads being fully coalesced).  Upper bound (CENTER = 0):
+// Scoring on the matrix cores (used at G = 8 when the KV-head count does not allow the page-by-page kernel above:
+// the stream-by-stream packed-dot kernel is bound by its arithmetic there).  Upper bound (CENTER = 0):
 //   UB[g][b] = (1/sqrt d) sum_c max(q_c kmin_c, q_c kmax_c) = (1/sqrt d) (q- . kmin + q+ . kmax)
 //   with q+ = max(q,0), q- = min(q,0).
 // Cuboid centre (CENTER = 1): (1/sqrt d) q . (kmin + kmax)/2 = (1/(2 sqrt d)) (q . kmin + q . kmax).
@@ -231,7 +231,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(KvView kv, const uint8_
     const uint8_t *mp = meta + ((size_t)page * kv.num_kv_heads + h) * kMetaBytes + kq * 16;
     uint4 a[8];
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) a[kk] = ld16_stream(mp + kk * 64);
+    for (int kk = 0; kk < 8; ++kk) a[kk] = ld16(mp + kk * 64);      // (half a cache line per record and load: the other half is the next load's, so not marked read-once)
     // B operand: column n = head n; the same 8 numbers of the record's index range, taken from q with the
     // entries of the wrong sign zeroed (steps 0-3 meet the minima, 4-7 the maxima)
     f32x4_t d = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -266,87 +266,6 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(KvView kv, const uint8_
     }
 }
 
-// =================================================================================================
-// The matrix-core scoring page by page (see score_pages_kernel for why): one wave per KV head, so that the
-// workgroup reads the whole metadata of its blocks' pages (512 bytes x H, contiguous) at the same time, and
-// every wave makes several rounds of 16 blocks with the next round's records in flight while it multiplies
-// (score_mfma_kernel above loads one round and leaves).  Same products in the same order: same bits.
-// grid (ceil(max_blocks / nb), batch), 64 * H threads (H = 2, 4 or 8); a workgroup covers nb <= 64
-// consecutive blocks of one request, nb a multiple of 16.
-// =================================================================================================
-template <int DT, int G, int CENTER>
-__global__ __launch_bounds__(512) void score_pages_mfma_kernel(KvView kv, const uint8_t *__restrict__ q,
-                                                               const uint8_t *__restrict__ meta,
-                                                               float *__restrict__ scores,
-                                                               float *__restrict__ scores_out, int32_t *header,
-                                                               int nb) {
-    const int r = blockIdx.y, H = kv.num_kv_heads, h = threadIdx.x >> 6, s = r * H + h;
-    const int lane = threadIdx.x & 63, kq = lane >> 4, n = lane & 15;
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 2) header[threadIdx.x] = 0;
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 2) header[kValueCount] = 0;   // value work list
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 3) header[kClosedStreams] = 0;
-    const int ctx = ctx_clamped_quiet(kv, r);
-    const int N = (ctx + kPage - 1) / kPage;
-    const int base = blockIdx.x * nb;
-    if (base >= N) return;
-    const int mine = min(nb, N - base);                 // blocks of this workgroup
-    const int32_t *table = kv.block_table + (size_t)r * kv.max_blocks;
-    const int page_of_lane = clamp_page_quiet(table[base + min(lane, mine - 1)], kv.num_pages);   // lane = block
-
-    // B operand, as in score_mfma_kernel: column n = head n, steps 0-3 meet the minima, 4-7 the maxima
-    uint4 b[8];
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-        b[kk] = make_uint4(0, 0, 0, 0);
-        if (n < G) {
-            const int ch = (32 * kk + 8 * kq) & 127;
-            b[kk] = ld16(q + ((size_t)(r * kv.num_q_heads + h * G + n) * kHeadDim + ch) * 2);
-            if (!CENTER) {
-                uint32_t w[4] = {b[kk].x, b[kk].y, b[kk].z, b[kk].w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t neg = ((w[j] >> 15) & 0x00010001u) * 0xFFFFu;
-                    w[j] &= (kk >= 4) ? ~neg : neg;
-                }
-                b[kk] = make_uint4(w[0], w[1], w[2], w[3]);
-            }
-        }
-    }
-    // A operand of round rd: row n = block base + 16 rd + n; step kk holds bytes 64 kk + 16 kq .. +15 of its record
-    uint4 a[2][8];
-    auto fetch = [&](int rd, uint4 (&dst)[8]) {
-        const int page = __shfl(page_of_lane, min(16 * rd + n, mine - 1));     // (clamped: the loads need no branch)
-        const uint8_t *mp = meta + ((size_t)page * H + h) * kMetaBytes + kq * 16;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) dst[kk] = ld16_stream(mp + kk * 64);
-    };
-    auto reduce = [&](int rd, const uint4 (&src)[8]) {
-        f32x4_t d = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) d = mfma_16x16x32<DT>(src[kk], b[kk], d);
-        // lane (kq, n): head n of blocks 16 rd + 4kq .. + 4kq+3; the maximum over the heads of the group
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float v = n < G ? d[j] : -INFINITY;
-            v = row_max16(v) * (CENTER ? 0.5f * kScale : kScale);
-            const int b2 = 16 * rd + 4 * kq + j;
-            if (n == 0 && b2 < mine) {
-                scores[(size_t)s * kv.max_blocks + base + b2] = v;
-                if (scores_out) scores_out[(size_t)s * kv.max_blocks + base + b2] = v;
-            }
-        }
-    };
-    const int nr = (mine + 15) / 16;                    // rounds: at most 4
-    fetch(0, a[0]);
-#pragma unroll
-    for (int rd = 0; rd < 4; ++rd) {
-        if (rd < nr) {
-            if (rd + 1 < nr) fetch(rd + 1, a[(rd + 1) & 1]);
-            reduce(rd, a[rd & 1]);
-        }
-    }
-}
-
 template <int DT, int G>
 static hipError_t launch_score_t(const KvView &kv, int scorer, const void *q, const void *meta, const DecodeWs &ws,
                                  float *scores_out, hipStream_t st) {
@@ -361,26 +280,7 @@ static hipError_t launch_score_t(const KvView &kv, int scorer, const void *q, co
                                                        scores_out, ws.header, rounds);
         return hipGetLastError();
     }
-    if constexpr (G >= 8) {
-        const int H = kv.num_kv_heads;
-        if (H == 2 || H == 4 || H == 8) {
-            // blocks per workgroup: as many rounds of 16 (up to four) as still leave two workgroups per compute unit
-            long long rounds_p = ((long long)kv.batch * kv.max_blocks) / (2ll * compute_units() * 16);
-            const int nb = 16 * (rounds_p < 1 ? 1 : (rounds_p > 4 ? 4 : (int)rounds_p));
-            const dim3 grid_p((kv.max_blocks + nb - 1) / nb, kv.batch);
-            if (scorer == 1)
-                score_pages_mfma_kernel<DT, G, 1><<<grid_p, 64 * H, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta,
-                                                                             ws.scores, scores_out, ws.header, nb);
-            else
-                score_pages_mfma_kernel<DT, G, 0><<<grid_p, 64 * H, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta,
-                                                                             ws.scores, scores_out, ws.header, nb);
-        } else if (scorer == 1)
-            score_mfma_kernel<DT, G, 1><<<grid, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
-                                                              scores_out, ws.header);
-        else
-            score_mfma_kernel<DT, G, 0><<<grid, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
-                                                              scores_out, ws.header);
-    } else if (kv.num_kv_heads > 1 && 16 % kv.num_kv_heads == 0) {
+    if (kv.num_kv_heads > 1 && 16 % kv.num_kv_heads == 0) {
         // all KV heads of a page together; blocks per workgroup: as many (up to 64) as still leave four
         // workgroups per compute unit, in whole rounds of four steps
         const int round_blocks = 4 * (16 / kv.num_kv_heads);
@@ -394,6 +294,13 @@ static hipError_t launch_score_t(const KvView &kv, int scorer, const void *q, co
         else
             score_pages_kernel<DT, G, 0><<<grid_p, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
                                                                  scores_out, ws.header, nb);
+    } else if constexpr (G >= 8) {
+        if (scorer == 1)
+            score_mfma_kernel<DT, G, 1><<<grid, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
+                                                              scores_out, ws.header);
+        else
+            score_mfma_kernel<DT, G, 0><<<grid, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,
+                                                              scores_out, ws.header);
     } else {
         if (scorer == 1)
             score_kernel<DT, G, 1><<<grid_r, 256, 0, st>>>(kv, (const uint8_t *)q, (const uint8_t *)meta, ws.scores,

@@ -32,8 +32,8 @@ CASES = {
     # long enough (2500 blocks, 16 streams) for the ranking to be shared by several workgroups per stream
     "c2_ranking_in_parts": (_small(2, batch=2, ctx=40000), {}),
     "c4_ragged_g8": (_small(4, batch=6, ctx=6000, ctx_min=100), {}),
-    # group of 8 with KV-head counts the page-by-page matrix scoring does not take (3) and does (2: 128-thread
-    # workgroups, ragged last rounds)
+    # group of 8 with a KV-head count the page-by-page scoring does not take (3: scored on the matrix cores) and one
+    # it does (2: eight blocks per step)
     "g8_three_kv_heads": (_small(4, batch=2, ctx=5000, ctx_min=900, num_q_heads=24, num_kv_heads=3), {}),
     "g8_two_kv_heads": (_small(4, batch=3, ctx=3000, ctx_min=50, num_q_heads=16, num_kv_heads=2, dtype="bf16"), {}),
     "c5_uniform": (_small(5, batch=2, ctx=4096), {}),
