@@ -51,7 +51,8 @@ __global__ __launch_bounds__(256) void dense_split_kernel(KvView kv, const uint8
         const uint8_t *kp = kv.k_pool + off + row_token * kRowBytes + rg * 16;
         uint4 ka[4];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) ka[kk] = ld16_stream(kp + kk * 64);
+        for (int kk = 0; kk < 4; ++kk) ka[kk] = ld16(kp + kk * 64);     // (operand layout: half a cache line per row and load, the
+                                                                         // next load takes the other half -- not marked read-once)
         Slice v = load_slice(kv.v_pool + off, lane);
         const int valid = min(kPage, ctx - b * kPage);
         f32x4_t s4 = {0.0f, 0.0f, 0.0f, 0.0f};
