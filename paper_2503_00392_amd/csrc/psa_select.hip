@@ -111,7 +111,9 @@ __device__ __forceinline__ void nap(int tries) {
     if (tries > 1) __builtin_amdgcn_s_sleep(20);
 }
 
-template <int G>
+constexpr int kStagedBlocks = 32;     // chunks of up to this many blocks keep their logits in LDS until they are done
+
+template <int G, bool STAGE>
 struct SelectShared {
     uint4 qb[4][64];                       // B operand of the QK^T product of the workgroup's stream, by lane
     float Lb[kMaxChunkBlocks][G];          // per-block log2-sum-exp2
@@ -120,6 +122,8 @@ struct SelectShared {
     int go;                                // after the wait for the window: 1 = read the chunk, 0 = the stream closed
     unsigned long long kp0;                // the stream's progress word as the workgroup first saw it
     uint4 stage[kSelectThreads / 64][16 * 17];   // per wave: one key slice, rows padded to 272 bytes
+    // the chunk's logits in the layout of the workspace, written out as one piece (STAGE only)
+    __attribute__((aligned(16))) float lg[STAGE ? kStagedBlocks : 1][G][kPage];
 };
 
 // How far a stream can still go, in chunks, given what the fold knows after n blocks.  AS_acc only grows and
@@ -327,8 +331,8 @@ __device__ void fold_stream(const KvView &kv, const DecodeWs &ws, int s, float e
 
 // Physical page and valid-token count of each ranked block of chunk c of stream s -> LDS.  Issued before
 // the workgroup looks at the window, so that the loads overlap its wait.
-template <int G>
-__device__ __forceinline__ void stage_pages(SelectShared<G> &sh, const KvView &kv, const DecodeWs &ws, int CB,
+template <int G, bool STAGE>
+__device__ __forceinline__ void stage_pages(SelectShared<G, STAGE> &sh, const KvView &kv, const DecodeWs &ws, int CB,
                                             int s, int c) {
     const int tid = threadIdx.x;
     const int ctx = stream_ctx(kv, s);
@@ -347,8 +351,8 @@ __device__ __forceinline__ void stage_pages(SelectShared<G> &sh, const KvView &k
 // B operand of the QK^T product of stream s -> LDS (every wave of the workgroup reads it from there): column
 // n = lane%16 is query head n (zero beyond the group), k block kq = lane/16; for step kk the lane holds
 // channels 8*(4*kk + kq) .. +7.  (The caller's next barrier makes it visible.)
-template <int G>
-__device__ __forceinline__ void load_queries(SelectShared<G> &sh, const KvView &kv, const uint8_t *__restrict__ q,
+template <int G, bool STAGE>
+__device__ __forceinline__ void load_queries(SelectShared<G, STAGE> &sh, const KvView &kv, const uint8_t *__restrict__ q,
                                              int s) {
     const int tid = threadIdx.x;
     if (tid < 256) {
@@ -364,8 +368,8 @@ __device__ __forceinline__ void load_queries(SelectShared<G> &sh, const KvView &
 // Key work of one workgroup: chunk c of stream s.  Ends with the chunk published (wave 0 stores the chunk's
 // words, which the stream's folding wave is looking at).
 // =================================================================================================
-template <int DT, int G>
-__device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8_t *__restrict__ q,
+template <int DT, int G, bool STAGE>
+__device__ void process_chunk(SelectShared<G, STAGE> &sh, const KvView &kv, const uint8_t *__restrict__ q,
                               const DecodeWs &ws, float eps, int m, int CB, int budget, int s, int c) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = s % kv.num_kv_heads;
@@ -419,8 +423,10 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
         float sc[4];
 #pragma unroll
         for (int x = 0; x < 4; ++x) sc[x] = (4 * x + kq < valid) ? acc[x] * kScaleLog2 : -INFINITY;
-        if (n < G)
-            store_stream(lg_out + ((size_t)i * G + n) * kPage + 4 * kq, f32x4_t{sc[0], sc[1], sc[2], sc[3]});
+        if (n < G) {
+            if constexpr (STAGE) *reinterpret_cast<f32x4_t *>(&sh.lg[i][n][4 * kq]) = f32x4_t{sc[0], sc[1], sc[2], sc[3]};
+            else store_stream(lg_out + ((size_t)i * G + n) * kPage + 4 * kq, f32x4_t{sc[0], sc[1], sc[2], sc[3]});
+        }
         // the block's log-sum-exp for head n, across the 4 token groups
         float mx = fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3]));
         mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -457,6 +463,15 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
         }
     }
     lds_barrier();
+    // The chunk's logits leave as one contiguous piece (8 KiB at G = 4), every thread 16 bytes at a time.  Writes
+    // are what this kernel pays most for per byte (the stored logits are 6 % of what it moves and a tenth of its
+    // time); in whole, neighbouring cache lines they cost a third less than as 256 bytes per block in between
+    // the loads.
+    if constexpr (STAGE) {
+        const float *staged = &sh.lg[0][0][0];
+        for (int idx = tid * 4; idx < nblk * G * kPage; idx += kSelectThreads * 4)
+            store_stream(lg_out + idx, *reinterpret_cast<const f32x4_t *>(staged + idx));
+    }
     // the blocks' L_b, for the fold's block-by-block pass; complete before the chunk is published
     for (int idx = tid; idx < nblk * G; idx += kSelectThreads)
         st_relaxed(&ws.block_lse[row0 * G + idx], sh.Lb[idx / G][idx % G]);
@@ -493,12 +508,12 @@ __device__ void process_chunk(SelectShared<G> &sh, const KvView &kv, const uint8
 // workgroups are the folds, one wave per stream (they start first and stay until their streams close); then one
 // workgroup per (chunk, stream), streams fastest.
 // =================================================================================================
-template <int DT, int G>
+template <int DT, int G, bool STAGE>
 __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, const uint8_t *__restrict__ q,
                                                                 DecodeWs ws, float eps, int m, int CB, int budget,
                                                                 int window, int spin_limit,
                                                                 const int32_t *depth_hint) {
-    __shared__ SelectShared<G> sh;
+    __shared__ SelectShared<G, STAGE> sh;
     const int S = kv.batch * kv.num_kv_heads;
     const int folders = min((S + 3) / 4, kMaxFoldGroups);
     if ((int)blockIdx.x < folders) {
@@ -520,8 +535,8 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
     if (threadIdx.x == 0) kp_first = ld_relaxed(&ws.ctl[s].key_progress);
     const int N = (stream_ctx(kv, s) + kPage - 1) / kPage;
     if (c * CB >= N) return;
-    load_queries<G>(sh, kv, q, s);
-    stage_pages<G>(sh, kv, ws, CB, s, c);
+    load_queries<G, STAGE>(sh, kv, q, s);
+    stage_pages<G, STAGE>(sh, kv, ws, CB, s, c);
     if (threadIdx.x == 0) sh.kp0 = kp_first;
     lds_barrier();
     if (c >= (int)(sh.kp0 >> 32)) return;          // closed, out of reach, or beyond a block budget
@@ -556,7 +571,7 @@ __global__ __launch_bounds__(kSelectThreads, 4) void select_kernel(KvView kv, co
     lds_barrier();
     if (!sh.go) return;
     if (threadIdx.x == 0) atomicAdd(&ws.ctl[s].k_blocks, min(CB, N - c * CB));     // traffic accounting
-    process_chunk<DT, G>(sh, kv, q, ws, eps, m, CB, budget, s, c);
+    process_chunk<DT, G, STAGE>(sh, kv, q, ws, eps, m, CB, budget, s, c);
 }
 
 template <int DT, int G>
@@ -565,8 +580,12 @@ static hipError_t launch_select_t(const KvView &kv, const void *q, const DecodeW
     const unsigned S = (unsigned)(kv.batch * kv.num_kv_heads);
     const unsigned folders = (S + 3) / 4 < (unsigned)kMaxFoldGroups ? (S + 3) / 4 : (unsigned)kMaxFoldGroups;
     const unsigned grid = folders + S * (unsigned)plan.max_chunks;
-    select_kernel<DT, G><<<grid, kSelectThreads, 0, st>>>(kv, (const uint8_t *)q, ws, eps, m, plan.chunk_blocks,
-                                               budget, plan.window_chunks, plan.spin_limit, plan.depth_hint);
+    if (plan.chunk_blocks <= kStagedBlocks)
+        select_kernel<DT, G, true><<<grid, kSelectThreads, 0, st>>>(kv, (const uint8_t *)q, ws, eps, m, plan.chunk_blocks,
+                                                         budget, plan.window_chunks, plan.spin_limit, plan.depth_hint);
+    else
+        select_kernel<DT, G, false><<<grid, kSelectThreads, 0, st>>>(kv, (const uint8_t *)q, ws, eps, m, plan.chunk_blocks,
+                                                          budget, plan.window_chunks, plan.spin_limit, plan.depth_hint);
     return hipGetLastError();
 }
 
